@@ -1,0 +1,198 @@
+"""Pins for the data-path oracle (pack / reduce / unpack / update) against library routines,
+closed forms and special cases.  None of these calls the HIP library."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import datapath as od
+from paper_1811_11141_amd import workloads as wl
+
+
+def np_grads(w, seed):
+    return [[t.numpy() for t in rep] for rep in wl.make_gradients(w, seed)]
+
+
+# ---- pack / unpack: pure bit copies --------------------------------------------------------
+
+def test_pack_is_concatenation_in_arrival_order():
+    w = wl.tiny_workload(3)
+    bits = wl.random_bit_patterns(w, 3, n_replicas=1)[0]
+    group = [6, 5, 4, 3]                         # 0-based layers, highest first
+    merged = od.pack(bits, group)
+    expect = np.concatenate([bits[l] for l in group])
+    assert merged.dtype == np.uint32 and np.array_equal(merged, expect)
+    assert merged.size == sum(int(w.p[l]) for l in group)        # Condition 3: no padding
+
+
+def test_pack_unpack_roundtrip_bits():
+    for seed in range(5):
+        w = wl.tiny_workload(seed)
+        bits = wl.random_bit_patterns(w, seed, n_replicas=1)[0]
+        groups = [[7, 6], [5], [4, 3, 2], [1, 0]]
+        out = [np.zeros_like(b) for b in bits]
+        for grp in groups:
+            od.unpack(od.pack(bits, grp), out, grp)
+        for a, b in zip(bits, out):
+            assert np.array_equal(a, b)
+
+
+def test_unpack_touches_only_its_group():
+    w = wl.custom_workload([5, 7, 3], 1)
+    bits = wl.random_bit_patterns(w, 1, 1)[0]
+    out = [np.full_like(b, 0xDEADBEEF) for b in bits]
+    od.unpack(od.pack(bits, [2, 1]), out, [2, 1])
+    assert np.array_equal(out[2], bits[2]) and np.array_equal(out[1], bits[1])
+    assert np.all(out[0] == 0xDEADBEEF)
+
+
+# ---- reduce --------------------------------------------------------------------------------
+
+def test_reduce_single_worker_is_identity():
+    x = np.random.default_rng(0).standard_normal(1000).astype(np.float32)
+    assert np.array_equal(od.reduce([x]).view(np.uint32), x.view(np.uint32))
+
+
+def test_reduce_equal_replicas():
+    """Two equal copies: x + x and the halving are exact, so the result is x bit for bit.
+    For N = 4, 8, 16 the running sums k*x stay exact when x has at most 11 significant bits
+    (fp16-representable values), and the power-of-two scale is exact again."""
+    x = (np.random.default_rng(1).standard_normal(4099) * 1e-3).astype(np.float32)
+    assert np.array_equal(od.reduce([x.copy(), x.copy()]).view(np.uint32), x.view(np.uint32))
+    xs = x.astype(np.float16).astype(np.float32)
+    for n in (4, 8, 16):
+        assert np.array_equal(od.reduce([xs.copy() for _ in range(n)]).view(np.uint32),
+                              xs.view(np.uint32))
+
+
+def test_reduce_small_integers_exact_mean():
+    """Integer-valued inputs below 2^20 sum exactly in fp32; N = 8 divides exactly."""
+    rng = np.random.default_rng(2)
+    xs = [rng.integers(-1000, 1000, size=3001).astype(np.float32) for _ in range(8)]
+    exact = np.sum(np.stack(xs).astype(np.int64), axis=0) / 8.0
+    assert np.array_equal(od.reduce(xs).astype(np.float64), exact)
+
+
+def test_reduce_order_is_worker_0_first():
+    """(1e8 + 1) - 1e8 = 0 in fp32 but (1e8 - 1e8) + 1 = 1: pins left-to-right order."""
+    one = lambda v: np.array([v], dtype=np.float32)
+    assert od.reduce([one(1e8), one(1.0), one(-1e8), one(0.0)])[0] == 0.0
+    assert od.reduce([one(1e8), one(-1e8), one(1.0), one(0.0)])[0] == 0.25
+    assert od.reduce([one(1.0), one(1e8), one(-1e8), one(0.0)])[0] == 0.0
+    # a pairwise (tree) order would give (1+1) + (1e8-1e8) = 2 -> 0.5; left-to-right gives 0
+    assert od.reduce([one(1.0), one(1.0), one(1e8), one(-1e8)])[0] == 0.0
+
+
+def test_reduce_matches_fp64_within_bound():
+    rng = np.random.default_rng(3)
+    for n in (2, 3, 4, 8, 16):
+        xs = [(rng.standard_normal(10007) * 1e-3).astype(np.float32) for _ in range(n)]
+        got = od.reduce(xs).astype(np.float64)
+        stack = np.stack(xs).astype(np.float64)
+        exact = stack.mean(axis=0)
+        bound = (n + 1) * 2.0 ** -24 * np.abs(stack).sum(axis=0) / n + 1e-45
+        assert np.all(np.abs(got - exact) <= bound)
+
+
+def test_reduce_scale_is_multiplication_by_fp32_reciprocal():
+    """N = 3: x * fl(1/3) differs from x / 3 for some x; the definition is the product."""
+    x = np.arange(1, 2001, dtype=np.float32)
+    zeros = np.zeros_like(x)
+    got = od.reduce([x, zeros, zeros])
+    inv = np.float32(1.0) / np.float32(3.0)
+    assert np.array_equal(got, x * inv)
+    assert not np.array_equal(got, x / np.float32(3.0))
+
+
+def test_reduce_threads_do_not_change_bits():
+    rng = np.random.default_rng(4)
+    xs = [(rng.standard_normal(100003) * 1e-3).astype(np.float32) for _ in range(8)]
+    assert np.array_equal(od.reduce(xs, 1), od.reduce(xs, 4))
+
+
+def test_reduce_keeps_denormals():
+    tiny = np.full(16, 2.0 ** -140, dtype=np.float32)
+    got = od.reduce([tiny, tiny])
+    assert np.array_equal(got, tiny) and got[0] != 0.0
+
+
+# ---- update --------------------------------------------------------------------------------
+
+def test_sgd_zero_momentum_is_paper_update():
+    """mu = 0, v = 0: w <- w - lr*g (Eq. 1), two roundings."""
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal(5000).astype(np.float32)
+    g = rng.standard_normal(5000).astype(np.float32)
+    w0, v = w.copy(), np.zeros_like(w)
+    od.sgd(w, v, g, 0.1, 0.0)
+    assert np.array_equal(w, w0 - np.float32(0.1) * g)
+    assert np.array_equal(v, g)
+
+
+def test_sgd_matches_torch_optimizer():
+    rng = np.random.default_rng(6)
+    w = rng.standard_normal(4097).astype(np.float32) * 0.1
+    v = np.zeros_like(w)
+    param = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.SGD([param], lr=0.1, momentum=0.9, dampening=0, nesterov=False,
+                          weight_decay=0)
+    for _ in range(5):
+        g = (rng.standard_normal(w.size) * 1e-2).astype(np.float32)
+        od.sgd(w, v, g, 0.1, 0.9)
+        param.grad = torch.from_numpy(g.copy())
+        opt.step()
+        ref = param.detach().numpy()
+        assert np.allclose(w, ref, rtol=1e-6, atol=1e-9)
+        buf = opt.state[param]["momentum_buffer"].numpy()
+        assert np.allclose(v, buf, rtol=1e-6, atol=1e-12)
+
+
+def test_sgd_constant_gradient_closed_form():
+    """Constant g: v_k = g (1 - mu^k)/(1 - mu), w_k = w_0 - lr * sum_j v_j (fp64 closed form)."""
+    g = np.full(64, 0.25, dtype=np.float32)
+    w = np.ones(64, dtype=np.float32)
+    v = np.zeros(64, dtype=np.float32)
+    lr, mu, acc = 0.1, 0.9, 0.0
+    for k in range(1, 9):
+        od.sgd(w, v, g, lr, mu)
+        vk = 0.25 * (1 - mu ** k) / (1 - mu)
+        acc += vk
+        assert np.allclose(v, vk, rtol=1e-6)
+        assert np.allclose(w, 1.0 - lr * acc, rtol=1e-6)
+
+
+# ---- whole path ----------------------------------------------------------------------------
+
+def test_path_independent_of_grouping_and_equals_mean():
+    """The averaged gradient of a layer does not depend on how layers are grouped, and is the
+    plain mean (library routine, fp64) within the fp32 summation bound."""
+    w = wl.tiny_workload(11)
+    grads = np_grads(w, 11)
+    L = w.L
+    plans = [[[l] for l in range(L - 1, -1, -1)], [list(range(L - 1, -1, -1))],
+             [[7, 6, 5], [4], [3, 2, 1, 0]]]
+    outs = [od.merged_gradient_path(grads, grp) for grp in plans]
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for l in range(L):
+        mean = np.mean(np.stack([grads[g][l] for g in range(w.n_workers)]).astype(np.float64), 0)
+        assert np.allclose(outs[0][l], mean, rtol=1e-5, atol=1e-9)
+
+
+def test_path_with_update_three_steps_vs_torch():
+    w = wl.tiny_workload(12)
+    ws, vs = wl.make_weights(w, 12)
+    ws = [t.numpy().copy() for t in ws]
+    vs = [t.numpy().copy() for t in vs]
+    params = [torch.nn.Parameter(torch.from_numpy(x.copy())) for x in ws]
+    opt = torch.optim.SGD(params, lr=0.1, momentum=0.9)
+    groups = [[7, 6], [5, 4, 3], [2], [1, 0]]
+    for step in range(3):
+        grads = np_grads(w, 12 + step)
+        od.merged_gradient_path(grads, groups, ws, vs, lr=0.1, mu=0.9)
+        for l, prm in enumerate(params):
+            stack = torch.stack([torch.from_numpy(grads[g][l]) for g in range(w.n_workers)])
+            prm.grad = stack.double().mean(0).float()
+        opt.step()
+        for l, prm in enumerate(params):
+            assert np.allclose(ws[l], prm.detach().numpy(), rtol=2e-6, atol=1e-8)

@@ -1,0 +1,261 @@
+"""Pins for the planner oracle: values the paper prints, hand-worked cases, closed forms
+and invariants.  None of these calls the HIP library."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import planner as op
+from paper_1811_11141_amd import workloads as wl
+
+
+def rand_case(rng, L, a=None):
+    p = np.clip(np.rint(2.0 ** rng.uniform(6, 16, size=L)), 64, 65536).astype(np.int64).tolist()
+    tb = rng.uniform(0.1, 2.0, size=L).tolist()
+    return p, tb, 0.0, (0.5 if a is None else a), 1e-6
+
+
+# ---- values printed in the paper ---------------------------------------------------------
+
+def test_allreduce_example_line(golden):
+    """Section I example: the line through (200 KB, 1.5 ms), (400 KB, 1.8 ms); merging two
+    200 KB messages into one saves exactly one startup a (Section IV-A, C.2)."""
+    ex = golden["allreduce_example"]
+    (m1, m2), (t1, t2) = ex["bytes"], ex["ms"]
+    b = (t2 - t1) / (m2 - m1)
+    a = t1 - b * m1
+    assert a == pytest.approx(ex["implied_a_ms"], rel=1e-12)
+    assert b == pytest.approx(ex["implied_b_ms_per_byte"], rel=1e-12)
+    assert op.t_ar(a, b, m1) == pytest.approx(t1)
+    assert op.t_ar(a, b, m2) == pytest.approx(t2)
+    saved = 2 * op.t_ar(a, b, m1) - op.t_ar(a, b, 2 * m1)
+    assert saved == pytest.approx(a, rel=1e-12)
+
+
+def test_ring_startup_values(golden):
+    """Section V-A prints 2(N-1)*alpha for N = 2, 4, 8; Table II's ring row must give them
+    from one alpha."""
+    rs = golden["ring_startup"]
+    for n, us in zip(rs["nodes"], rs["startup_us"]):
+        a, _ = op.table2_cost("ring", n, rs["alpha_us"], 0.0, 0.0)
+        assert a == pytest.approx(us, abs=5e-3)
+
+
+def test_table2_rows():
+    """Table II at N = 8 with alpha=1, beta=2, gamma=3 worked by hand."""
+    assert op.table2_cost("binary_tree", 8, 1, 2, 3) == (6.0, 21.0)
+    assert op.table2_cost("recursive_doubling", 8, 1, 2, 3) == (3.0, 15.0)
+    a, b = op.table2_cost("recursive_halving_doubling", 8, 1, 2, 3)
+    assert (a, b) == (6.0, pytest.approx(4 - 7 / 8 + 3))
+    a, b = op.table2_cost("ring", 8, 1, 2, 3)
+    assert (a, b) == (14.0, pytest.approx(14 / 8 * 2 + 7 / 8 * 3))
+
+
+def test_workload_shapes_match_paper_sizes(golden):
+    ms = golden["model_sizes"]
+    r50, goo = wl.cnn_workload("resnet50"), wl.cnn_workload("googlenet")
+    assert abs(r50.P - ms["resnet50_params_approx"]) / ms["resnet50_params_approx"] < 0.01
+    assert abs(goo.P - ms["googlenet_params_approx"]) / ms["googlenet_params_approx"] < 0.03
+    assert abs(4 * r50.P - ms["resnet50_bytes_per_iter_approx"]) < 1e6
+    assert (r50.L, r50.P) == (161, 25_557_032)
+    assert (goo.L, goo.P) == (128, 13_378_280)
+    assert (wl.cnn_workload("alexnet").L, wl.cnn_workload("alexnet").P) == (16, 61_100_840)
+    assert (wl.cnn_workload("vgg16").L, wl.cnn_workload("vgg16").P) == (32, 138_357_544)
+    for w in (r50, goo):
+        frac_in = np.mean((w.p >= 16) & (w.p <= ms["layer_size_range"][1]))
+        assert frac_in == 1.0
+
+
+# ---- hand-worked cases ---------------------------------------------------------------------
+
+def test_three_layer_example_every_partition(golden):
+    ex = golden["hand_worked_three_layers"]
+    args = (ex["p"], ex["tb_ms"], ex["tf_ms"], ex["a_ms"], ex["b_ms_per_byte"])
+    for key, t in ex["t_iter"].items():
+        merged = [int(x) for x in key.split(",")] if key else []
+        assert op.simulate(*args, merged) == pytest.approx(t, rel=1e-12)
+    assert op.algorithm1(*args) == ex["theorem1_merged"]
+    t_best, m_best = op.brute_force(*args)
+    assert t_best == pytest.approx(ex["optimum"], rel=1e-12) and tuple(m_best) == (2,)
+    _, t_wfbp = op.wfbp_timeline(*args)
+    assert t_wfbp == pytest.approx(ex["t_iter"][""], rel=1e-12)
+
+
+def test_algorithm1_hand_traces(golden):
+    for c in golden["hand_worked_traces"]["cases"]:
+        args = (c["p"], c["tb_ms"], 0.0, c["a_ms"], c["b_ms_per_byte"])
+        merged = op.algorithm1(*args)
+        assert merged == c["merged"], c["note"]
+        assert op.simulate(*args, merged) == pytest.approx(c["t_iter"], rel=1e-12)
+        if "t_iter_wfbp" in c:
+            assert op.wfbp_timeline(*args)[1] == pytest.approx(c["t_iter_wfbp"], rel=1e-12)
+
+
+# ---- closed forms --------------------------------------------------------------------------
+
+def test_case1_closed_form():
+    """Eq. 11: if every t_c(l) <= t_b(l-1) then t_iter = t_f + t_b + t_c(1)."""
+    rng = np.random.default_rng(7)
+    for _ in range(50):
+        L = int(rng.integers(2, 12))
+        p = rng.integers(64, 4096, size=L).tolist()
+        a, b, tf = 0.05, 1e-6, float(rng.uniform(0, 3))
+        tb = rng.uniform(0.2, 2.0, size=L).tolist()       # > a + b*4*4096 = 0.066
+        expect = tf + sum(tb) + (a + b * 4 * p[0])
+        assert op.wfbp_timeline(p, tb, tf, a, b)[1] == pytest.approx(expect, rel=1e-12)
+        assert op.simulate(p, tb, tf, a, b, []) == pytest.approx(expect, rel=1e-12)
+
+
+def test_comm_bound_closed_form():
+    """If every t_c(l) >= t_b(l-1) the channel never idles after layer L:
+    t_iter = t_f + t_b(L) + sum_l t_c(l)."""
+    rng = np.random.default_rng(8)
+    for _ in range(50):
+        L = int(rng.integers(2, 12))
+        p = rng.integers(10_000, 100_000, size=L).tolist()
+        a, b, tf = 3.0, 1e-5, float(rng.uniform(0, 3))
+        tb = rng.uniform(0.1, 2.0, size=L).tolist()
+        expect = tf + tb[-1] + sum(a + b * 4 * x for x in p)
+        assert op.wfbp_timeline(p, tb, tf, a, b)[1] == pytest.approx(expect, rel=1e-12)
+        assert op.simulate(p, tb, tf, a, b, []) == pytest.approx(expect, rel=1e-12)
+
+
+def test_single_group_is_naive_ssgd():
+    """Eq. 3 with one message: t_f + t_b + (a + b*4P) (the SyncEASGD scheme of Section I)."""
+    rng = np.random.default_rng(9)
+    for _ in range(50):
+        L = int(rng.integers(1, 12))
+        p, tb, tf, a, b = rand_case(rng, L)
+        tf = 1.25
+        expect = tf + sum(tb) + a + b * 4 * sum(p)
+        assert op.simulate(p, tb, tf, a, b, range(2, L + 1)) == pytest.approx(expect, rel=1e-12)
+
+
+def test_backward_start_eq6():
+    tau_b = op.backward_start([1.0, 2.0, 4.0], 0.5)
+    assert tau_b == [0.5 + 4.0 + 2.0, 0.5 + 4.0, 0.5]
+    assert op.backward_finish([1.0, 2.0, 4.0], 0.5) == [7.5, 6.5, 4.5]
+
+
+def test_superadditivity_eq10():
+    rng = np.random.default_rng(10)
+    for _ in range(200):
+        a, b = rng.uniform(1e-3, 2), rng.uniform(1e-8, 1e-5)
+        m1, m2 = (int(x) for x in rng.integers(4, 10**7, size=2))
+        assert op.t_ar(a, b, m1) + op.t_ar(a, b, m2) > op.t_ar(a, b, m1 + m2)
+
+
+# ---- invariants of the two separately written evaluators -----------------------------------
+
+def test_no_merging_reproduces_wfbp():
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        L = int(rng.integers(1, 10))
+        p, tb, tf, a, b = rand_case(rng, L, a=float(rng.uniform(0, 2)))
+        assert op.simulate(p, tb, tf, a, b, []) == op.wfbp_timeline(p, tb, tf, a, b)[1]
+
+
+def test_brute_force_bounds_and_counts():
+    assert sum(1 for _ in op.all_merge_sets(8)) == 128
+    assert sum(1 for _ in op.all_merge_sets(1)) == 1
+    rng = np.random.default_rng(12)
+    for _ in range(40):
+        L = int(rng.integers(1, 9))
+        args = rand_case(rng, L)
+        t_best, m_best = op.brute_force(*args)
+        assert t_best == op.simulate(*args, m_best)
+        assert t_best <= op.simulate(*args, [])
+        assert t_best <= op.simulate(*args, range(2, L + 1))
+
+
+def test_a_zero_optimum_is_wfbp():
+    rng = np.random.default_rng(13)
+    for _ in range(40):
+        L = int(rng.integers(1, 9))
+        p, tb, tf, _, b = rand_case(rng, L)
+        t_best, _ = op.brute_force(p, tb, tf, 0.0, b * 50)
+        assert t_best == pytest.approx(op.wfbp_timeline(p, tb, tf, 0.0, b * 50)[1], rel=1e-12)
+
+
+def test_huge_startup_optimum_is_single_group():
+    rng = np.random.default_rng(14)
+    for _ in range(40):
+        L = int(rng.integers(2, 9))
+        p, tb, tf, _, b = rand_case(rng, L)
+        a = sum(tb[:-1]) * 1.01 + 1e-9          # a > sum_{l<L} t_b(l)
+        t_best, _ = op.brute_force(p, tb, tf, a, b)
+        assert t_best == pytest.approx(op.simulate(p, tb, tf, a, b, range(2, L + 1)), rel=1e-12)
+
+
+def test_two_layer_rule():
+    """L = 2: merging layer 2 is strictly better iff t_b(1) < a; Theorem 1 says the same."""
+    rng = np.random.default_rng(15)
+    for _ in range(300):
+        p, tb, tf, _, b = rand_case(rng, 2)
+        a = float(rng.uniform(0.05, 2.5))
+        t_sep, t_mrg = op.simulate(p, tb, tf, a, b, []), op.simulate(p, tb, tf, a, b, [2])
+        assert (t_mrg < t_sep) == (tb[0] < a)
+        assert op.algorithm1(p, tb, tf, a, b) == ([2] if tb[0] < a else [])
+
+
+def test_monotone_in_a_b_p():
+    rng = np.random.default_rng(16)
+    for _ in range(30):
+        L = int(rng.integers(2, 8))
+        p, tb, tf, a, b = rand_case(rng, L)
+        t0, _ = op.brute_force(p, tb, tf, a, b)
+        assert op.brute_force(p, tb, tf, a * 1.5, b)[0] >= t0
+        assert op.brute_force(p, tb, tf, a, b * 1.5)[0] >= t0
+        p2 = list(p)
+        p2[int(rng.integers(0, L))] += 5000
+        assert op.brute_force(p2, tb, tf, a, b)[0] >= t0
+
+
+def test_tf_is_a_pure_offset():
+    rng = np.random.default_rng(17)
+    for _ in range(30):
+        L = int(rng.integers(1, 8))
+        p, tb, _, a, b = rand_case(rng, L)
+        t0, _ = op.brute_force(p, tb, 0.0, a, b)
+        t1, _ = op.brute_force(p, tb, 8.0, a, b)
+        assert t1 == pytest.approx(t0 + 8.0, rel=1e-12)
+        assert op.algorithm1(p, tb, 0.0, a, b) == op.algorithm1(p, tb, 8.0, a, b)
+
+
+def test_theorem1_rule_bounds():
+    """The rule never loses to WFBP and never beats the optimum; it is not always optimal."""
+    rng = np.random.default_rng(18)
+    worse = 0
+    for _ in range(400):
+        L = int(rng.integers(1, 9))
+        args = rand_case(rng, L)
+        t_g = op.simulate(*args, op.algorithm1(*args))
+        t_w = op.simulate(*args, [])
+        t_o, _ = op.brute_force(*args)
+        assert t_g <= t_w * (1 + 1e-12)
+        assert t_o <= t_g
+        worse += t_g > t_o * (1 + 1e-9)
+    assert worse > 0
+
+
+def test_theorem1_merge_finishes_layer_below_earlier():
+    """Statement used in Theorem 1's proof: when the rule fires for layer l, sending l and
+    l-1 together finishes layer l-1's message strictly earlier than sending them apart."""
+    rng = np.random.default_rng(19)
+    fired = 0
+    for _ in range(300):
+        p, tb, tf, a, b = rand_case(rng, 3)
+        mu = op.backward_finish(tb, tf)
+        tau_c3 = mu[2]
+        if mu[1] - tau_c3 < a:
+            fired += 1
+            apart = max(tau_c3 + op.t_ar(a, b, 4 * p[2]), mu[1]) + op.t_ar(a, b, 4 * p[1])
+            together = max(tau_c3, mu[1]) + op.t_ar(a, b, 4 * (p[1] + p[2]))
+            assert together < apart
+    assert fired > 20
+
+
+def test_groups_from_merged():
+    assert op.groups_from_merged(5, [5, 3, 2]) == [[5, 4], [3, 2, 1]]
+    assert op.groups_from_merged(3, []) == [[3], [2], [1]]
+    assert op.groups_from_merged(1, []) == [[1]]
