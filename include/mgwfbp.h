@@ -1,0 +1,190 @@
+/*
+ * mgwfbp.h - C ABI of the MI355X merged-gradient reduction library (libmgwfbp.so).
+ *
+ * The library implements, for one GPU's share of a data-parallel S-SGD job, the data
+ * path behind MG-WFBP (Shi, Chu, Li, "MG-WFBP: Efficient Data Communication for
+ * Distributed Synchronous SGD Algorithms"):
+ *
+ *   plan    which consecutive layers send their gradients as one message
+ *           (Section III, Eq. 19-23; Section IV, Theorem 1 and Algorithm 1);
+ *   pack    the layer buffer of Algorithm 2: the gradients of a group laid end to end in
+ *           arrival order of the backward pass (Definition 1, Condition 3 / Eq. 16);
+ *   reduce  the arithmetic of the all-reduce: sum over the N workers, times 1/N (Eq. 2);
+ *   unpack  the averaged values back into per-layer tensors, optionally with the weight
+ *           update of Algorithm 2 (W = W - eta * grad, Eq. 1-2) extended by a momentum
+ *           buffer.
+ *
+ * Conventions
+ *   - Layers are 0-based in every array: index 0 is the paper's layer 1.  The backward pass
+ *     visits index L-1 first.  Groups are numbered in communication order: group 0 holds
+ *     the highest layers and is ready first.
+ *   - All gradients, weights and momentum buffers are fp32 (Section V).  Message sizes in
+ *     the cost model are bytes: a layer of p parameters is a 4p-byte message.
+ *   - The N workers' gradients are N replicas resident in this GPU's memory.
+ *   - "host" / "device" is stated for every pointer.  The caller owns every tensor, the
+ *     workspace and the stream.  The library owns the plan handle and the small device
+ *     tables created by mgwfbp_bind; mgwfbp_plan_destroy frees both.
+ *   - Every function returns a status code and never throws or aborts.  On failure
+ *     mgwfbp_last_error() describes the reason (thread-local, library-owned string).
+ *   - Device work is enqueued on the caller's HIP stream and is asynchronous; the caller
+ *     synchronises.  A launch failure is reported as MGWFBP_EHIP.
+ *   - Reduction arithmetic is fixed: acc = x_0; acc = acc + x_g for g = 1..N-1 in fp32
+ *     (round to nearest even, no fused multiply-add), result = acc * (1.0f / N).
+ *     Update arithmetic: v = mu*v + g; w = w - lr*v, each operation rounded separately.
+ *     Pack and unpack are bit copies.
+ *   - A plan handle must not be used from two threads at once.
+ */
+#ifndef MGWFBP_H
+#define MGWFBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mgwfbp_plan_s mgwfbp_plan_t; /* opaque */
+
+enum {
+    MGWFBP_OK = 0,
+    MGWFBP_EINVAL = -1, /* bad argument (null pointer, L < 1, N < 1, p = 0, negative or NaN time ...) */
+    MGWFBP_ENOMEM = -2, /* host or device allocation failed */
+    MGWFBP_EHIP = -3,   /* a HIP runtime call failed */
+    MGWFBP_ESTATE = -4  /* call not valid in the handle's state (e.g. launch before bind) */
+};
+
+enum {
+    MGWFBP_MODE_OPTIMAL = 0,      /* exact minimum of Eq. 19-23 by an O(L^2) dynamic program   */
+    MGWFBP_MODE_PAPER_GREEDY = 1, /* the rule of Theorem 1 / Algorithm 1                        */
+    MGWFBP_MODE_WFBP = 2,         /* no merging: every layer is its own group (Section II-C)    */
+    MGWFBP_MODE_SINGLE = 3        /* all layers in one group (the single-message scheme of Sec. I) */
+};
+
+/* Tuning keys for mgwfbp_plan_set_option (before mgwfbp_bind). */
+enum {
+    MGWFBP_OPT_TILE_ELEMS = 1,  /* elements of one layer handled by one workgroup; multiple of 1024, <= 8192 */
+    MGWFBP_OPT_SMALL_ELEMS = 2, /* layers shorter than this share gather tiles                      */
+    MGWFBP_OPT_NONTEMPORAL = 3  /* 1: streaming (non-temporal) loads and stores; 0: plain            */
+};
+
+/*
+ * Merge planning (Algorithm 1's inputs: a, b, L, N, p; t_b and t_f stand for T_b and T_f,
+ * which the paper derives from benchmarks of the first iterations).
+ *
+ *   L              number of learnable layers (>= 1)
+ *   p_elems        host [L]   parameters per layer, each >= 1
+ *   tb_ms          host [L]   backward time of each layer, finite and >= 0
+ *   tf_ms          forward time (a pure offset of the timeline), finite and >= 0
+ *   a_ms, b_ms_per_byte       all-reduce cost T_ar(M) = a + b*M (Eq. 9), finite and >= 0
+ *   N              number of workers (>= 1); only used for the 1/N scale
+ *   mode           MGWFBP_MODE_*
+ *   out            receives a new handle; free with mgwfbp_plan_destroy
+ *
+ * The predicted iteration time follows Eq. 6-8 with Conditions 1-3 for merged layers.
+ * Ties between equally good plans are broken towards smaller groups (Theorem 1's
+ * inequality is strict).
+ */
+int mgwfbp_plan(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                double a_ms, double b_ms_per_byte, int32_t N, int32_t mode, mgwfbp_plan_t **out);
+
+/*
+ * Same, but with the merged-gradient set M given by the caller (Eq. 22):
+ *   merged  host [L] bytes; merged[l] != 0 means layer l (0-based, l >= 1) sends its gradients
+ *           together with layer l-1.  merged[0] must be 0.
+ */
+int mgwfbp_plan_explicit(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                         double a_ms, double b_ms_per_byte, int32_t N, const uint8_t *merged,
+                         mgwfbp_plan_t **out);
+
+/*
+ * Read a plan back.  Every out-pointer is a host pointer and may be NULL.
+ *   n_groups         number of groups
+ *   group_of_layer   [L]  group id of each layer
+ *   offset_in_group  [L]  element offset of the layer inside its group's merged buffer
+ *                         (arrival order: the highest layer of a group has offset 0)
+ *   group_elems      [n_groups]  total elements of each group (no padding)
+ *   t_iter_ms        predicted iteration time of this plan
+ *   t_iter_wfbp_ms   predicted iteration time without merging
+ */
+int mgwfbp_plan_info(const mgwfbp_plan_t *plan, int32_t *n_groups, int32_t *group_of_layer,
+                     uint64_t *offset_in_group, uint64_t *group_elems, double *t_iter_ms,
+                     double *t_iter_wfbp_ms);
+
+/*
+ * Predicted timeline of the plan (Eq. 6-8): host arrays, any may be NULL.
+ *   mu_b          [L]         when each layer's gradients are ready (tau_b + t_b)
+ *   group_start   [n_groups]  tau_c of each group's message
+ *   group_finish  [n_groups]  tau_c + T_ar of each group's message
+ */
+int mgwfbp_plan_timeline(const mgwfbp_plan_t *plan, double *mu_b, double *group_start,
+                         double *group_finish);
+
+/* Set a tuning option (MGWFBP_OPT_*).  Only before mgwfbp_bind; MGWFBP_ESTATE afterwards. */
+int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
+
+/*
+ * Attach tensors and upload the segment, tile and pointer tables (once; the pointers are
+ * not re-read from host memory afterwards).  A second call replaces the binding.
+ *   grads  host array [N*L] of device pointers, worker-major: grads[g*L + l] is worker g's
+ *          gradient of layer l, p_elems[l] floats, 4-byte aligned (16-byte alignment of
+ *          every pointer of a layer enables 128-bit accesses for that layer)
+ *   out    host array [L] of device pointers receiving the averaged gradients, or NULL.
+ *          out[l] may be the same pointer as grads[0*L + l] (in place); any other overlap
+ *          between buffers is undefined.
+ *   w, v   host arrays [L] of device pointers (weights, momentum buffers), both or neither.
+ * The current HIP device at the time of the call owns the tables.
+ */
+int mgwfbp_bind(mgwfbp_plan_t *plan, const float *const *grads, float *const *out,
+                float *const *w, float *const *v);
+
+/*
+ * Workspace size in bytes for the materialised path on `group` (-1 = all groups at once):
+ * N packed replica buffers followed by one reduced buffer, each rounded up to 256 bytes.
+ */
+int mgwfbp_workspace_bytes(const mgwfbp_plan_t *plan, int32_t group, size_t *bytes);
+
+/*
+ * Pack + N-way reduce + unpack of one group (or all groups when group = -1) into out[].
+ *   workspace == NULL : one fused pass that never materialises the merged buffers.
+ *   workspace != NULL : device pointer, 256-byte aligned, at least mgwfbp_workspace_bytes;
+ *                       runs pack, reduce and unpack as three kernels through it.
+ *   hip_stream        : a hipStream_t (NULL = the default stream).
+ * Requires out[] to be bound.
+ */
+int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Same reduction fused with the update v = momentum*v + avg; w = w - lr*v on the bound
+ * w[], v[].  The averaged gradient is also written to out[] when out[] is bound.
+ */
+int mgwfbp_step(mgwfbp_plan_t *plan, int32_t group, float lr, float momentum, void *workspace,
+                size_t workspace_bytes, void *hip_stream);
+
+/* The three materialised steps on their own (workspace layout as above, required). */
+int mgwfbp_pack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t workspace_bytes,
+                void *hip_stream);
+int mgwfbp_reduce(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+int mgwfbp_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+
+/*
+ * Bandwidth probes used to calibrate measurements; they are not part of the method.
+ *   mgwfbp_probe_copy    dst[i] = src[i]                              (1 read + 1 write stream)
+ *   mgwfbp_probe_streams dst[i] = sum_g src[g*stride_elems + i] / n   (n read + 1 write streams)
+ * All pointers are device pointers, 16-byte aligned; n_elems a multiple of 4.
+ */
+int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream);
+int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_elems,
+                         uint64_t n_elems, float *dst, void *hip_stream);
+
+void mgwfbp_plan_destroy(mgwfbp_plan_t *plan);
+
+const char *mgwfbp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGWFBP_H */

@@ -1,0 +1,276 @@
+"""Thin ctypes binding of libmgwfbp.so (see include/mgwfbp.h for the contract of each call).
+
+Only argument marshalling happens here: every step of the path (planning, table building,
+pack, reduce, unpack, update) runs inside the library.  PyTorch tensors are accepted as
+sources of device pointers and streams; nothing is computed with them.  There is no CPU or
+PyTorch fallback: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmgwfbp.so")
+
+OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
+OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL = 1, 2, 3
+
+EXPORTS = [
+    "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
+    "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
+    "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
+    "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy", "mgwfbp_last_error",
+]
+
+
+class MgwfbpError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"mgwfbp error {code}: {msg}")
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1811_11141_amd.build` "
+            "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64, f64, f32, sz = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double,
+                                       C.c_float, C.c_size_t)
+    P = C.POINTER
+    lib.mgwfbp_plan.argtypes = [i32, P(u64), P(f64), f64, f64, f64, i32, i32, P(vp)]
+    lib.mgwfbp_plan_explicit.argtypes = [i32, P(u64), P(f64), f64, f64, f64, i32, P(C.c_uint8), P(vp)]
+    lib.mgwfbp_plan_info.argtypes = [vp, P(i32), P(i32), P(u64), P(u64), P(f64), P(f64)]
+    lib.mgwfbp_plan_timeline.argtypes = [vp, P(f64), P(f64), P(f64)]
+    lib.mgwfbp_plan_set_option.argtypes = [vp, i32, i64]
+    lib.mgwfbp_bind.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
+    lib.mgwfbp_workspace_bytes.argtypes = [vp, i32, P(sz)]
+    lib.mgwfbp_pack_reduce_unpack.argtypes = [vp, i32, vp, sz, vp]
+    lib.mgwfbp_step.argtypes = [vp, i32, f32, f32, vp, sz, vp]
+    for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
+        getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
+    lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
+    lib.mgwfbp_probe_streams.argtypes = [vp, i32, u64, u64, vp, vp]
+    lib.mgwfbp_plan_destroy.argtypes = [vp]
+    lib.mgwfbp_plan_destroy.restype = None
+    lib.mgwfbp_last_error.argtypes = []
+    lib.mgwfbp_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("mgwfbp_plan_destroy", "mgwfbp_last_error"):
+            getattr(lib, name).restype = i32
+    return lib
+
+
+_lib = _load()
+
+
+def last_error() -> str:
+    return _lib.mgwfbp_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise MgwfbpError(rc, last_error())
+
+
+def _ptr(x) -> int:
+    """Device address of a torch tensor, or the integer itself."""
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _stream(stream) -> int:
+    """hipStream_t handle: int, torch.cuda.Stream, or None for torch's current stream."""
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def _ptr_array(items: Optional[Sequence]) -> Optional[C.Array]:
+    if items is None:
+        return None
+    return (C.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+class Plan:
+    """Owner of one mgwfbp_plan_t handle."""
+
+    def __init__(self, handle: int, L: int, N: int, p: np.ndarray):
+        self._h = C.c_void_p(handle)
+        self.L, self.N = L, N
+        self.p = p
+        self._keep = None
+
+    # ---- read back -------------------------------------------------------------------
+    def info(self) -> dict:
+        ng = C.c_int32()
+        _check(_lib.mgwfbp_plan_info(self._h, C.byref(ng), None, None, None, None, None))
+        gol = np.zeros(self.L, dtype=np.int32)
+        off = np.zeros(self.L, dtype=np.uint64)
+        ge = np.zeros(ng.value, dtype=np.uint64)
+        t, tw = C.c_double(), C.c_double()
+        _check(_lib.mgwfbp_plan_info(self._h, C.byref(ng), gol.ctypes.data_as(C.POINTER(C.c_int32)),
+                                     off.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                     ge.ctypes.data_as(C.POINTER(C.c_uint64)), C.byref(t), C.byref(tw)))
+        return {"n_groups": ng.value, "group_of_layer": gol, "offset_in_group": off,
+                "group_elems": ge, "t_iter_ms": t.value, "t_iter_wfbp_ms": tw.value}
+
+    def timeline(self) -> dict:
+        ng = self.info()["n_groups"]
+        mu = np.zeros(self.L)
+        gs, gf = np.zeros(ng), np.zeros(ng)
+        dp = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+        _check(_lib.mgwfbp_plan_timeline(self._h, dp(mu), dp(gs), dp(gf)))
+        return {"mu_b": mu, "group_start": gs, "group_finish": gf}
+
+    def groups(self) -> List[List[int]]:
+        """0-based layers of each group in arrival order (highest first)."""
+        inf = self.info()
+        out: List[List[int]] = [[] for _ in range(inf["n_groups"])]
+        for l in range(self.L - 1, -1, -1):
+            out[int(inf["group_of_layer"][l])].append(l)
+        return out
+
+    def merged_layers(self) -> List[int]:
+        """The set M in the paper's 1-based numbering, descending."""
+        gol = self.info()["group_of_layer"]
+        return [l + 1 for l in range(self.L - 1, 0, -1) if gol[l] == gol[l - 1]]
+
+    # ---- set-up ----------------------------------------------------------------------
+    def set_option(self, key: int, value: int) -> None:
+        _check(_lib.mgwfbp_plan_set_option(self._h, key, value))
+
+    def bind(self, grads: Sequence[Sequence], out: Optional[Sequence] = None,
+             w: Optional[Sequence] = None, v: Optional[Sequence] = None) -> None:
+        """grads[g][l], out[l], w[l], v[l]: torch CUDA fp32 tensors (or raw device addresses)."""
+        if len(grads) != self.N or any(len(r) != self.L for r in grads):
+            raise ValueError("grads must be N lists of L tensors")
+        for name, lst in (("out", out), ("w", w), ("v", v)):
+            if lst is not None and len(lst) != self.L:
+                raise ValueError(f"{name} must hold L tensors")
+        for lst in list(grads) + [x for x in (out, w, v) if x is not None]:
+            for l, t in enumerate(lst):
+                if isinstance(t, int):
+                    continue
+                if not t.is_cuda or str(t.dtype) != "torch.float32" or not t.is_contiguous() \
+                        or t.numel() != int(self.p[l]):
+                    raise ValueError(f"layer {l}: need a contiguous CUDA fp32 tensor of {int(self.p[l])} elements")
+        flat = [t for rep in grads for t in rep]
+        _check(_lib.mgwfbp_bind(self._h, _ptr_array(flat), _ptr_array(out), _ptr_array(w),
+                                _ptr_array(v)))
+        self._keep = (grads, out, w, v)
+
+    def workspace_bytes(self, group: int = -1) -> int:
+        n = C.c_size_t()
+        _check(_lib.mgwfbp_workspace_bytes(self._h, group, C.byref(n)))
+        return int(n.value)
+
+    # ---- device calls ----------------------------------------------------------------
+    @staticmethod
+    def _ws(workspace):
+        if workspace is None:
+            return None, 0
+        if isinstance(workspace, tuple):
+            return C.c_void_p(workspace[0]), workspace[1]
+        return C.c_void_p(int(workspace.data_ptr())), workspace.numel() * workspace.element_size()
+
+    def pack_reduce_unpack(self, group: int = -1, workspace=None, stream=None) -> None:
+        ws, nb = self._ws(workspace)
+        _check(_lib.mgwfbp_pack_reduce_unpack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def step(self, lr: float, momentum: float, group: int = -1, workspace=None, stream=None) -> None:
+        ws, nb = self._ws(workspace)
+        _check(_lib.mgwfbp_step(self._h, group, lr, momentum, ws, nb, C.c_void_p(_stream(stream))))
+
+    def pack(self, workspace, group: int = -1, stream=None) -> None:
+        ws, nb = self._ws(workspace)
+        _check(_lib.mgwfbp_pack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def reduce(self, workspace, group: int = -1, stream=None) -> None:
+        ws, nb = self._ws(workspace)
+        _check(_lib.mgwfbp_reduce(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def unpack(self, workspace, group: int = -1, stream=None) -> None:
+        ws, nb = self._ws(workspace)
+        _check(_lib.mgwfbp_unpack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def destroy(self) -> None:
+        if self._h:
+            _lib.mgwfbp_plan_destroy(self._h)
+            self._h = C.c_void_p(0)
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _plan_args(p, tb_ms):
+    p_arr = np.ascontiguousarray(p, dtype=np.uint64)
+    tb = np.ascontiguousarray(tb_ms, dtype=np.float64)
+    if p_arr.ndim != 1 or tb.shape != p_arr.shape:
+        raise ValueError("p and tb_ms must be 1-D arrays of the same length")
+    return p_arr, tb
+
+
+def mgwfbp_plan(p, tb_ms, tf_ms: float, a_ms: float, b_ms_per_byte: float, N: int,
+                mode: int = MODE_OPTIMAL) -> Plan:
+    p_arr, tb = _plan_args(p, tb_ms)
+    h = C.c_void_p()
+    _check(_lib.mgwfbp_plan(len(p_arr), p_arr.ctypes.data_as(C.POINTER(C.c_uint64)),
+                            tb.ctypes.data_as(C.POINTER(C.c_double)), tf_ms, a_ms, b_ms_per_byte,
+                            N, mode, C.byref(h)))
+    return Plan(h.value, len(p_arr), N, p_arr)
+
+
+def mgwfbp_plan_explicit(p, tb_ms, tf_ms: float, a_ms: float, b_ms_per_byte: float, N: int,
+                         merged_layers: Sequence[int]) -> Plan:
+    """merged_layers: the set M in the paper's 1-based numbering (subset of {2..L})."""
+    p_arr, tb = _plan_args(p, tb_ms)
+    flags = np.zeros(len(p_arr), dtype=np.uint8)
+    for l in merged_layers:
+        flags[l - 1] = 1
+    h = C.c_void_p()
+    _check(_lib.mgwfbp_plan_explicit(len(p_arr), p_arr.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                     tb.ctypes.data_as(C.POINTER(C.c_double)), tf_ms, a_ms,
+                                     b_ms_per_byte, N, flags.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                     C.byref(h)))
+    return Plan(h.value, len(p_arr), N, p_arr)
+
+
+def mgwfbp_pack_reduce_unpack(plan: Plan, group: int = -1, workspace=None, stream=None) -> None:
+    plan.pack_reduce_unpack(group, workspace, stream)
+
+
+def mgwfbp_step(plan: Plan, lr: float, momentum: float, group: int = -1, workspace=None,
+                stream=None) -> None:
+    plan.step(lr, momentum, group, workspace, stream)
+
+
+def mgwfbp_probe_copy(src, dst, n_elems: int, stream=None) -> None:
+    _check(_lib.mgwfbp_probe_copy(C.c_void_p(_ptr(src)), C.c_void_p(_ptr(dst)), n_elems,
+                                  C.c_void_p(_stream(stream))))
+
+
+def mgwfbp_probe_streams(src, n_streams: int, stride_elems: int, n_elems: int, dst,
+                         stream=None) -> None:
+    _check(_lib.mgwfbp_probe_streams(C.c_void_p(_ptr(src)), n_streams, stride_elems, n_elems,
+                                     C.c_void_p(_ptr(dst)), C.c_void_p(_stream(stream))))
+
+
+def raw():
+    """The ctypes library object (for tests of the error paths)."""
+    return _lib

@@ -1,0 +1,424 @@
+// extern "C" entry points of libmgwfbp: argument checking, plan life cycle, table upload and
+// the translation of (group, workspace) into kernel launches.  See include/mgwfbp.h for the
+// contract of every call.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/mgwfbp.h"
+#include "plan.hpp"
+
+namespace mgwfbp {
+
+namespace {
+thread_local std::string g_error;
+}
+
+void set_error(const std::string &msg) { g_error = msg; }
+
+namespace {
+
+int fail(int code, const std::string &msg)
+{
+    set_error(msg);
+    return code;
+}
+
+bool good_time(double x) { return std::isfinite(x) && x >= 0.0; }
+
+int make_plan(int32_t L, const uint64_t *p, const double *tb, double tf, double a, double b,
+              int32_t N, mgwfbp_plan_t **out)
+{
+    if (!out) return fail(MGWFBP_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (L < 1 || L > (1 << 20)) return fail(MGWFBP_EINVAL, "L must be in [1, 2^20]");
+    if (N < 1 || N > 1024) return fail(MGWFBP_EINVAL, "N must be in [1, 1024]");
+    if (!p || !tb) return fail(MGWFBP_EINVAL, "p_elems or tb_ms is NULL");
+    if (!good_time(tf) || !good_time(a) || !good_time(b))
+        return fail(MGWFBP_EINVAL, "tf_ms, a_ms and b_ms_per_byte must be finite and >= 0");
+    for (int32_t l = 0; l < L; ++l) {
+        if (p[l] == 0) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] is 0");
+        if (p[l] > (1ull << 40)) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] too large");
+        if (!good_time(tb[l])) return fail(MGWFBP_EINVAL, "tb_ms[" + std::to_string(l) + "] must be finite and >= 0");
+    }
+    mgwfbp_plan_t *pl = new (std::nothrow) mgwfbp_plan_t();
+    if (!pl) return fail(MGWFBP_ENOMEM, "out of host memory");
+    try {
+        pl->L = L;
+        pl->N = N;
+        pl->p.assign(p, p + L);
+        pl->tb.assign(tb, tb + L);
+        pl->tf = tf;
+        pl->a = a;
+        pl->b = b;
+        // mu_b(l) = tau_b(l) + t_b(l) with tau_b from Eq. 6: accumulate from the top layer down
+        pl->mu_b.assign(L, 0.0);
+        double t = tf;
+        for (int32_t l = L - 1; l >= 0; --l) {
+            t = t + tb[l];
+            pl->mu_b[l] = t;
+        }
+        pl->merged.assign(L, 0);
+    } catch (const std::bad_alloc &) {
+        delete pl;
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+    *out = pl;
+    return MGWFBP_OK;
+}
+
+void release_device(mgwfbp_plan_t *pl)
+{
+    if (pl->d_blob) {
+        int cur = -1;
+        const bool sw = hipGetDevice(&cur) == hipSuccess && cur != pl->device && pl->device >= 0;
+        if (sw) (void)hipSetDevice(pl->device);
+        (void)hipFree(pl->d_blob);
+        if (sw) (void)hipSetDevice(cur);
+    }
+    pl->d_blob = nullptr;
+    pl->dt = DeviceTables();
+    pl->bound = false;
+}
+
+int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
+{
+    if (group < -1 || group >= static_cast<int32_t>(pl->groups.size()))
+        return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
+    if (group < 0) {
+        sc.tile_begin = 0;
+        sc.n_tiles = static_cast<uint32_t>(pl->tiles.size());
+        sc.elems = pl->total_elems;
+        sc.base_off = 0;
+        sc.needs_lds = pl->all_needs_lds;
+    } else {
+        const GroupInfo &g = pl->groups[group];
+        sc.tile_begin = g.tile_begin;
+        sc.n_tiles = g.tile_end - g.tile_begin;
+        sc.elems = g.elems;
+        sc.base_off = g.plan_off;
+        sc.needs_lds = g.needs_lds;
+    }
+    return MGWFBP_OK;
+}
+
+uint64_t padded(uint64_t elems) { return (elems + 63) & ~uint64_t(63); }
+
+int check_ws(const mgwfbp_plan_t *pl, const LaunchScope &sc, void *ws, size_t bytes)
+{
+    if (!ws) return fail(MGWFBP_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(MGWFBP_EINVAL, "workspace must be 256-byte aligned");
+    const size_t need = static_cast<size_t>(pl->N + 1) * padded(sc.elems) * sizeof(float);
+    if (bytes < need)
+        return fail(MGWFBP_EINVAL, "workspace too small: need " + std::to_string(need) + " bytes");
+    return MGWFBP_OK;
+}
+
+int check_bound(const mgwfbp_plan_t *pl, bool need_out, bool need_wv)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (!pl->bound) return fail(MGWFBP_ESTATE, "mgwfbp_bind has not been called");
+    if (need_out && !pl->has_out) return fail(MGWFBP_ESTATE, "out[] is not bound");
+    if (need_wv && !pl->has_wv) return fail(MGWFBP_ESTATE, "w[] and v[] are not bound");
+    return MGWFBP_OK;
+}
+
+int run(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws, size_t bytes,
+        void *stream)
+{
+    int rc = check_bound(pl, !step, step);
+    if (rc) return rc;
+    if (step && (!std::isfinite(lr) || !std::isfinite(mu)))
+        return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if (!ws) {
+        if (bytes != 0) return fail(MGWFBP_EINVAL, "workspace is NULL but workspace_bytes != 0");
+        return launch_fused(*pl, sc, step, lr, mu, stream);
+    }
+    if ((rc = check_ws(pl, sc, ws, bytes))) return rc;
+    float *w = static_cast<float *>(ws);
+    const uint64_t epad = padded(sc.elems);
+    if ((rc = launch_pack(*pl, sc, w, epad, stream))) return rc;
+    if ((rc = launch_reduce(*pl, sc, w, epad, stream))) return rc;
+    return launch_unpack(*pl, sc, w, epad, step, lr, mu, stream);
+}
+
+}  // namespace
+}  // namespace mgwfbp
+
+using namespace mgwfbp;
+
+extern "C" {
+
+int mgwfbp_plan(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                double a_ms, double b_ms_per_byte, int32_t N, int32_t mode, mgwfbp_plan_t **out)
+{
+    if (mode < MGWFBP_MODE_OPTIMAL || mode > MGWFBP_MODE_SINGLE) {
+        if (out) *out = nullptr;
+        return fail(MGWFBP_EINVAL, "unknown mode");
+    }
+    int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, out);
+    if (rc) return rc;
+    mgwfbp_plan_t *pl = *out;
+    try {
+        switch (mode) {
+        case MGWFBP_MODE_OPTIMAL: plan_optimal(*pl, pl->merged); break;
+        case MGWFBP_MODE_PAPER_GREEDY: plan_paper_greedy(*pl, pl->merged); break;
+        case MGWFBP_MODE_WFBP: pl->merged.assign(L, 0); break;
+        case MGWFBP_MODE_SINGLE:
+            pl->merged.assign(L, 1);
+            pl->merged[0] = 0;
+            break;
+        }
+        finish_plan(*pl);
+    } catch (const std::bad_alloc &) {
+        delete pl;
+        *out = nullptr;
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+    return MGWFBP_OK;
+}
+
+int mgwfbp_plan_explicit(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                         double a_ms, double b_ms_per_byte, int32_t N, const uint8_t *merged,
+                         mgwfbp_plan_t **out)
+{
+    if (!merged) {
+        if (out) *out = nullptr;
+        return fail(MGWFBP_EINVAL, "merged is NULL");
+    }
+    int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, out);
+    if (rc) return rc;
+    mgwfbp_plan_t *pl = *out;
+    if (merged[0]) {
+        delete pl;
+        *out = nullptr;
+        return fail(MGWFBP_EINVAL, "merged[0] must be 0: the lowest layer has nothing below it");
+    }
+    try {
+        for (int32_t l = 0; l < L; ++l) pl->merged[l] = merged[l] ? 1 : 0;
+        finish_plan(*pl);
+    } catch (const std::bad_alloc &) {
+        delete pl;
+        *out = nullptr;
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+    return MGWFBP_OK;
+}
+
+int mgwfbp_plan_info(const mgwfbp_plan_t *pl, int32_t *n_groups, int32_t *group_of_layer,
+                     uint64_t *offset_in_group, uint64_t *group_elems, double *t_iter_ms,
+                     double *t_iter_wfbp_ms)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (n_groups) *n_groups = static_cast<int32_t>(pl->groups.size());
+    if (group_of_layer) std::memcpy(group_of_layer, pl->group_of_layer.data(), sizeof(int32_t) * pl->L);
+    if (offset_in_group) std::memcpy(offset_in_group, pl->off_in_group.data(), sizeof(uint64_t) * pl->L);
+    if (group_elems)
+        for (size_t k = 0; k < pl->groups.size(); ++k) group_elems[k] = pl->groups[k].elems;
+    if (t_iter_ms) *t_iter_ms = pl->t_iter;
+    if (t_iter_wfbp_ms) *t_iter_wfbp_ms = pl->t_iter_wfbp;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_plan_timeline(const mgwfbp_plan_t *pl, double *mu_b, double *group_start,
+                         double *group_finish)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (mu_b) std::memcpy(mu_b, pl->mu_b.data(), sizeof(double) * pl->L);
+    for (size_t k = 0; k < pl->groups.size(); ++k) {
+        if (group_start) group_start[k] = pl->groups[k].start_ms;
+        if (group_finish) group_finish[k] = pl->groups[k].finish_ms;
+    }
+    return MGWFBP_OK;
+}
+
+int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (pl->bound) return fail(MGWFBP_ESTATE, "options must be set before mgwfbp_bind");
+    switch (key) {
+    case MGWFBP_OPT_TILE_ELEMS:
+        // upper bound: a tile is staged whole in LDS by the pack / unpack kernels (32 KiB)
+        if (value < 1024 || value > 8192 || (value % 1024) != 0)
+            return fail(MGWFBP_EINVAL, "tile_elems must be a multiple of 1024 in [1024, 8192]");
+        pl->opt.tile_elems = static_cast<uint32_t>(value);
+        return MGWFBP_OK;
+    case MGWFBP_OPT_SMALL_ELEMS:
+        if (value < 0 || value > 8192) return fail(MGWFBP_EINVAL, "small_elems must be in [0, 8192]");
+        pl->opt.small_elems = static_cast<uint32_t>(value);
+        return MGWFBP_OK;
+    case MGWFBP_OPT_NONTEMPORAL:
+        if (value != 0 && value != 1) return fail(MGWFBP_EINVAL, "nontemporal must be 0 or 1");
+        pl->opt.nontemporal = static_cast<int>(value);
+        return MGWFBP_OK;
+    default: return fail(MGWFBP_EINVAL, "unknown option key");
+    }
+}
+
+int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, float *const *w,
+                float *const *v)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (!grads) return fail(MGWFBP_EINVAL, "grads is NULL");
+    if ((w == nullptr) != (v == nullptr)) return fail(MGWFBP_EINVAL, "w and v must be given together");
+    const int32_t L = pl->L, N = pl->N;
+    for (int64_t i = 0; i < static_cast<int64_t>(N) * L; ++i) {
+        if (!grads[i]) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is NULL");
+        if (reinterpret_cast<uintptr_t>(grads[i]) & 3u) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is not 4-byte aligned");
+    }
+    for (int32_t l = 0; l < L; ++l) {
+        if (out && (!out[l] || (reinterpret_cast<uintptr_t>(out[l]) & 3u)))
+            return fail(MGWFBP_EINVAL, "out[" + std::to_string(l) + "] is NULL or misaligned");
+        if (w && (!w[l] || !v[l] || ((reinterpret_cast<uintptr_t>(w[l]) | reinterpret_cast<uintptr_t>(v[l])) & 3u)))
+            return fail(MGWFBP_EINVAL, "w/v[" + std::to_string(l) + "] is NULL or misaligned");
+    }
+    release_device(pl);
+
+    std::vector<const float *> src_tbl;
+    std::vector<float *> out_tbl, w_tbl, v_tbl;
+    try {
+        build_tables(*pl, grads, out, w, v, src_tbl, out_tbl, w_tbl, v_tbl);
+    } catch (const std::bad_alloc &) {
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+
+    // one device allocation: [segs][tiles][src][out][w][v], each part 256-byte aligned
+    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
+    const size_t b_seg = up(pl->segs.size() * sizeof(SegDev));
+    const size_t b_tile = up(pl->tiles.size() * sizeof(TileDev));
+    const size_t b_src = up(src_tbl.size() * sizeof(void *));
+    const size_t b_ptr = up(pl->segs.size() * sizeof(void *));
+    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr;
+    std::vector<char> host(total, 0);
+    size_t o = 0;
+    std::memcpy(host.data() + o, pl->segs.data(), pl->segs.size() * sizeof(SegDev));
+    const size_t o_seg = o; o += b_seg;
+    std::memcpy(host.data() + o, pl->tiles.data(), pl->tiles.size() * sizeof(TileDev));
+    const size_t o_tile = o; o += b_tile;
+    std::memcpy(host.data() + o, src_tbl.data(), src_tbl.size() * sizeof(void *));
+    const size_t o_src = o; o += b_src;
+    const size_t o_out = o; o += b_ptr;
+    const size_t o_w = o; o += b_ptr;
+    const size_t o_v = o; o += b_ptr;
+    if (out) std::memcpy(host.data() + o_out, out_tbl.data(), out_tbl.size() * sizeof(void *));
+    if (w) {
+        std::memcpy(host.data() + o_w, w_tbl.data(), w_tbl.size() * sizeof(void *));
+        std::memcpy(host.data() + o_v, v_tbl.data(), v_tbl.size() * sizeof(void *));
+    }
+
+    hipError_t e = hipGetDevice(&pl->device);
+    if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    e = hipMalloc(&pl->d_blob, total);
+    if (e != hipSuccess) {
+        pl->d_blob = nullptr;
+        return fail(e == hipErrorOutOfMemory ? MGWFBP_ENOMEM : MGWFBP_EHIP,
+                    std::string("hipMalloc of the plan tables: ") + hipGetErrorString(e));
+    }
+    e = hipMemcpy(pl->d_blob, host.data(), total, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        release_device(pl);
+        return fail(MGWFBP_EHIP, std::string("hipMemcpy of the plan tables: ") + hipGetErrorString(e));
+    }
+    char *d = static_cast<char *>(pl->d_blob);
+    pl->dt.segs = reinterpret_cast<const SegDev *>(d + o_seg);
+    pl->dt.tiles = reinterpret_cast<const TileDev *>(d + o_tile);
+    pl->dt.src = reinterpret_cast<const float *const *>(d + o_src);
+    pl->dt.out = out ? reinterpret_cast<float *const *>(d + o_out) : nullptr;
+    pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
+    pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
+    pl->has_out = out != nullptr;
+    pl->has_wv = w != nullptr;
+    pl->bound = true;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_workspace_bytes(const mgwfbp_plan_t *pl, int32_t group, size_t *bytes)
+{
+    if (!pl || !bytes) return fail(MGWFBP_EINVAL, "plan or bytes is NULL");
+    uint64_t elems;
+    if (group == -1) elems = pl->total_elems;
+    else if (group >= 0 && group < static_cast<int32_t>(pl->groups.size())) elems = pl->groups[group].elems;
+    else return fail(MGWFBP_EINVAL, "group out of range");
+    *bytes = static_cast<size_t>(pl->N + 1) * padded(elems) * sizeof(float);
+    return MGWFBP_OK;
+}
+
+int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace,
+                              size_t workspace_bytes, void *hip_stream)
+{
+    return run(pl, group, false, 0.0f, 0.0f, workspace, workspace_bytes, hip_stream);
+}
+
+int mgwfbp_step(mgwfbp_plan_t *pl, int32_t group, float lr, float momentum, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    return run(pl, group, true, lr, momentum, workspace, workspace_bytes, hip_stream);
+}
+
+int mgwfbp_pack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
+                void *hip_stream)
+{
+    int rc = check_bound(pl, false, false);
+    if (rc) return rc;
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+    return launch_pack(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+}
+
+int mgwfbp_reduce(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
+                  void *hip_stream)
+{
+    int rc = check_bound(pl, false, false);
+    if (rc) return rc;
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+    return launch_reduce(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+}
+
+int mgwfbp_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
+                  void *hip_stream)
+{
+    int rc = check_bound(pl, true, false);
+    if (rc) return rc;
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+    return launch_unpack(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), false, 0.0f,
+                         0.0f, hip_stream);
+}
+
+int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream)
+{
+    if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
+    if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) || (n_elems & 3u))
+        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned and n_elems a multiple of 4");
+    return launch_probe_copy(src, dst, n_elems, hip_stream);
+}
+
+int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_elems,
+                         uint64_t n_elems, float *dst, void *hip_stream)
+{
+    if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
+    if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) ||
+        (n_elems & 3u) || (stride_elems & 3u) || stride_elems < n_elems)
+        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples of 4, stride >= n_elems");
+    return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
+}
+
+void mgwfbp_plan_destroy(mgwfbp_plan_t *pl)
+{
+    if (!pl) return;
+    release_device(pl);
+    delete pl;
+}
+
+const char *mgwfbp_last_error(void) { return g_error.c_str(); }
+
+}  // extern "C"

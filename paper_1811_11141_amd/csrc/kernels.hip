@@ -1,0 +1,519 @@
+// gfx950 kernels of the merged-gradient data path.
+//
+//   k_fused   pack + N-way reduce + unpack (+ update) in one pass: element i of layer l is
+//             read from the N workers' tensors, summed in worker order, scaled by 1/N (Eq. 2)
+//             and written to the per-layer output; the merged buffer of Algorithm 2 never
+//             touches memory.
+//   k_pack    Algorithm 2's layer buffer: each worker's layers of a group laid end to end.
+//   k_reduce  Eq. 2 over N contiguous merged buffers.
+//   k_unpack  merged buffer back to per-layer tensors (+ update of Eq. 1-2 with momentum).
+//
+// The path is bound by HBM bandwidth (0.2-0.3 flop per byte), so the kernels are built
+// around 128-bit coalesced accesses with all N loads of a lane issued before the first add;
+// there is nothing for the matrix cores to do.  One workgroup of 256 lanes (4 wave64) owns
+// one tile.  Arithmetic order is fixed (worker 0 first, one rounding per operation; the file
+// is compiled with -ffp-contract=off) so results are reproducible bit for bit.
+#include <hip/hip_runtime.h>
+
+#include "../../include/mgwfbp.h"
+#include "plan.hpp"
+
+namespace mgwfbp {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Every tensor, table and workspace pointer handed to the kernels is device global memory.
+// Saying so lets the compiler emit global_load/global_store (scalar base + lane offset) in
+// place of flat accesses, which would also have to test for the LDS and scratch apertures.
+#define MGWFBP_GLOBAL __attribute__((address_space(1)))
+
+template <bool NT, class T>
+__device__ __forceinline__ T ld(const T *p)
+{
+    const MGWFBP_GLOBAL T *gp = (const MGWFBP_GLOBAL T *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(gp);
+    else return *gp;
+}
+
+template <bool NT, class T>
+__device__ __forceinline__ void st(T *p, T x)
+{
+    MGWFBP_GLOBAL T *gp = (MGWFBP_GLOBAL T *)p;
+    if constexpr (NT) __builtin_nontemporal_store(x, gp);
+    else *gp = x;
+}
+
+// v = mu*v + g ; w = w - lr*v with one rounding per operation.
+template <class T>
+__device__ __forceinline__ void sgd_momentum(T g, T &w, T &v, float lr, float mu)
+{
+    const T mv = v * mu;
+    const T vn = mv + g;
+    const T step = vn * lr;
+    v = vn;
+    w = w - step;
+}
+
+// Sum of the N workers' values at index i (in units of T), worker 0 first, times 1/N.
+// Fixed N: every load is issued before the first add so that N 128-bit requests per lane are
+// in flight at once.
+template <int NW, bool NT, class T>
+__device__ __forceinline__ T nway_mean_fixed(const float *const (&sp)[NW], uint32_t i, float inv_n)
+{
+    T x[NW];
+#pragma unroll
+    for (int g = 0; g < NW; ++g) x[g] = ld<NT>(reinterpret_cast<const T *>(sp[g]) + i);
+    T acc = x[0];
+#pragma unroll
+    for (int g = 1; g < NW; ++g) acc = acc + x[g];
+    return acc * inv_n;
+}
+
+// Run-time N: `ptr(g)` yields worker g's base pointer; loads go out four at a time.
+template <bool NT, class T, class PtrFn>
+__device__ __forceinline__ T nway_mean_dyn(PtrFn ptr, int nw, uint32_t i, float inv_n)
+{
+    T acc = ld<NT>(reinterpret_cast<const T *>(ptr(0)) + i);
+    int g = 1;
+    for (; g + 4 <= nw; g += 4) {
+        const T a = ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
+        const T b = ld<NT>(reinterpret_cast<const T *>(ptr(g + 1)) + i);
+        const T c = ld<NT>(reinterpret_cast<const T *>(ptr(g + 2)) + i);
+        const T d = ld<NT>(reinterpret_cast<const T *>(ptr(g + 3)) + i);
+        acc = acc + a;
+        acc = acc + b;
+        acc = acc + c;
+        acc = acc + d;
+    }
+    for (; g < nw; ++g) acc = acc + ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
+    return acc * inv_n;
+}
+
+// Write the averaged value and, when STEP, apply the update.  Pointers are in units of float.
+template <bool STEP, bool NT, class T>
+__device__ __forceinline__ void finish(T avg, float *outp, float *wp, float *vp, uint32_t i,
+                                       float lr, float mu)
+{
+    if constexpr (STEP) {
+        T w = ld<NT>(reinterpret_cast<const T *>(wp) + i);
+        T v = ld<NT>(reinterpret_cast<const T *>(vp) + i);
+        sgd_momentum(avg, w, v, lr, mu);
+        st<NT>(reinterpret_cast<T *>(vp) + i, v);
+        st<NT>(reinterpret_cast<T *>(wp) + i, w);
+    }
+    if (outp) st<NT>(reinterpret_cast<T *>(outp) + i, avg);
+}
+
+// Offsets (relative to the tile start) of the segments a gather tile spans go to LDS; each
+// lane then finds the segment holding its element by binary search.
+__device__ __forceinline__ void stage_gather_offsets(const DeviceTables &dt, const TileDev &tl,
+                                                     uint32_t *s_rel)
+{
+    for (uint32_t k = threadIdx.x; k < tl.nseg; k += kBlock)
+        s_rel[k] = static_cast<uint32_t>(dt.segs[tl.seg + k].plan_off - tl.start);
+    __syncthreads();
+}
+
+__device__ __forceinline__ uint32_t find_segment(const uint32_t *s_rel, uint32_t nseg, uint32_t k)
+{
+    uint32_t lo = 0, hi = nseg - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (s_rel[mid] <= k) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Global -> LDS and LDS -> global copies of n floats whose global side has arbitrary 4-byte
+// alignment: a scalar head up to the next 16-byte boundary, a 128-bit body, a scalar tail.
+template <bool NT>
+__device__ __forceinline__ void global_to_lds(const float *src, float *lds, uint32_t n)
+{
+    uint32_t head = static_cast<uint32_t>((16u - (reinterpret_cast<uintptr_t>(src) & 15u)) & 15u) >> 2;
+    head = head < n ? head : n;
+    if (threadIdx.x < head) lds[threadIdx.x] = ld<NT>(src + threadIdx.x);
+    const uint32_t nb = (n - head) >> 2;
+    const v4f *s4 = reinterpret_cast<const v4f *>(src + head);
+    for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {
+        const v4f x = ld<NT>(s4 + i);
+        float *d = lds + head + 4 * i;
+        d[0] = x.x;
+        d[1] = x.y;
+        d[2] = x.z;
+        d[3] = x.w;
+    }
+    for (uint32_t i = head + 4 * nb + threadIdx.x; i < n; i += kBlock) lds[i] = ld<NT>(src + i);
+}
+
+template <bool NT>
+__device__ __forceinline__ void lds_to_global(const float *lds, float *dst, uint32_t n)
+{
+    uint32_t head = static_cast<uint32_t>((16u - (reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) >> 2;
+    head = head < n ? head : n;
+    if (threadIdx.x < head) st<NT>(dst + threadIdx.x, lds[threadIdx.x]);
+    const uint32_t nb = (n - head) >> 2;
+    v4f *d4 = reinterpret_cast<v4f *>(dst + head);
+    for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {
+        const float *s = lds + head + 4 * i;
+        v4f x;
+        x.x = s[0];
+        x.y = s[1];
+        x.z = s[2];
+        x.w = s[3];
+        st<NT>(d4 + i, x);
+    }
+    for (uint32_t i = head + 4 * nb + threadIdx.x; i < n; i += kBlock) st<NT>(dst + i, lds[i]);
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused single pass
+// ------------------------------------------------------------------------------------------
+template <int NW, bool STEP, bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu)
+{
+    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+
+    if (tl.nseg == 1) {
+        const uint32_t flags = dt.segs[tl.seg].flags;
+        const float *const *sp_tbl = dt.src + static_cast<size_t>(tl.seg) * nw;
+        float *outp = dt.out ? dt.out[tl.seg] + tl.start : nullptr;
+        float *wp = STEP ? dt.w[tl.seg] + tl.start : nullptr;
+        float *vp = STEP ? dt.v[tl.seg] + tl.start : nullptr;
+        const uint32_t n = tl.n;
+        const bool vec = (flags & (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
+                         (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
+        const uint32_t n4 = vec ? (n >> 2) : 0;
+        if constexpr (NW > 0) {
+            // per-worker base pointers of this tile (uniform over the workgroup)
+            const float *sp[NW];
+#pragma unroll
+            for (int g = 0; g < NW; ++g) sp[g] = sp_tbl[g] + tl.start;
+            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
+                const v4f avg = nway_mean_fixed<NW, NT, v4f>(sp, i, inv_n);
+                finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
+            }
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) {
+                const float avg = nway_mean_fixed<NW, NT, float>(sp, i, inv_n);
+                finish<STEP, NT, float>(avg, outp, wp, vp, i, lr, mu);
+            }
+        } else {
+            const uint64_t start = tl.start;
+            auto ptr = [sp_tbl, start](int g) { return sp_tbl[g] + start; };
+            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
+                const v4f avg = nway_mean_dyn<NT, v4f>(ptr, nw, i, inv_n);
+                finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
+            }
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) {
+                const float avg = nway_mean_dyn<NT, float>(ptr, nw, i, inv_n);
+                finish<STEP, NT, float>(avg, outp, wp, vp, i, lr, mu);
+            }
+        }
+    } else {
+        stage_gather_offsets(dt, tl, s_rel);
+        for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
+            const uint32_t s = find_segment(s_rel, tl.nseg, k);
+            const uint32_t si = tl.seg + s;
+            const uint32_t i = k - s_rel[s];
+            const float *const *sp_tbl = dt.src + static_cast<size_t>(si) * nw;
+            const float avg = nway_mean_dyn<NT, float>([sp_tbl](int g) { return sp_tbl[g]; }, nw, i, inv_n);
+            finish<STEP, NT, float>(avg, dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
+                                    STEP ? dt.v[si] : nullptr, i, lr, mu);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Materialised path
+// ------------------------------------------------------------------------------------------
+// Workspace: N packed replica buffers of `epad` floats each, then the reduced buffer.
+// `base_off` is the plan offset of the scope's first element (0 for the whole plan).
+
+template <bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, uint64_t base_off)
+{
+    extern __shared__ float lds[];
+    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+    const uint32_t g = blockIdx.y;
+    float *merged = ws + static_cast<uint64_t>(g) * epad;
+
+    if (tl.nseg == 1) {
+        const SegDev sg = dt.segs[tl.seg];
+        const float *src = dt.src[static_cast<size_t>(tl.seg) * nw + g] + tl.start;
+        const uint64_t moff = sg.plan_off - base_off + tl.start;
+        float *dst = merged + moff;
+        const uint32_t n = tl.n;
+        if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3)) {
+            const uint32_t n4 = n >> 2;
+            const v4f *s4 = reinterpret_cast<const v4f *>(src);
+            v4f *d4 = reinterpret_cast<v4f *>(dst);
+            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) st<NT>(d4 + i, ld<NT>(s4 + i));
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) st<NT>(dst + i, ld<NT>(src + i));
+        } else {
+            // the two sides disagree on 16-byte alignment: realign through LDS so that both
+            // the loads and the stores are 128 bits wide
+            global_to_lds<NT>(src, lds, n);
+            __syncthreads();
+            lds_to_global<NT>(lds, dst, n);
+        }
+    } else {
+        // many short layers: gather them into LDS, then one coalesced write of the run
+        stage_gather_offsets(dt, tl, s_rel);
+        for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
+            const uint32_t s = find_segment(s_rel, tl.nseg, k);
+            const float *src = dt.src[static_cast<size_t>(tl.seg + s) * nw + g];
+            lds[k] = ld<NT>(src + (k - s_rel[s]));
+        }
+        __syncthreads();
+        lds_to_global<NT>(lds, merged + (tl.start - base_off), tl.n);
+    }
+}
+
+template <int NW, bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float inv_n)
+{
+    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * tile;
+    const uint32_t n = static_cast<uint32_t>(elems - t0 < tile ? elems - t0 : tile);
+    float *outp = ws + static_cast<uint64_t>(nw) * epad + t0;
+    const uint32_t n4 = n >> 2;  // workspace and epad keep every buffer 16-byte aligned
+    if constexpr (NW > 0) {
+        const float *sp[NW];
+#pragma unroll
+        for (int g = 0; g < NW; ++g) sp[g] = ws + static_cast<uint64_t>(g) * epad + t0;
+        for (uint32_t i = threadIdx.x; i < n4; i += kBlock)
+            st<NT>(reinterpret_cast<v4f *>(outp) + i, nway_mean_fixed<NW, NT, v4f>(sp, i, inv_n));
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
+            st<NT>(outp + i, nway_mean_fixed<NW, NT, float>(sp, i, inv_n));
+    } else {
+        auto ptr = [ws, epad, t0](int g) { return ws + static_cast<uint64_t>(g) * epad + t0; };
+        for (uint32_t i = threadIdx.x; i < n4; i += kBlock)
+            st<NT>(reinterpret_cast<v4f *>(outp) + i, nway_mean_dyn<NT, v4f>(ptr, nw, i, inv_n));
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
+            st<NT>(outp + i, nway_mean_dyn<NT, float>(ptr, nw, i, inv_n));
+    }
+}
+
+template <bool STEP, bool NT>
+__global__ void __launch_bounds__(kBlock)
+k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t base_off, float lr,
+         float mu)
+{
+    extern __shared__ float lds[];
+    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+
+    if (tl.nseg == 1) {
+        const SegDev sg = dt.segs[tl.seg];
+        const uint64_t moff = sg.plan_off - base_off + tl.start;
+        const float *src = reduced + moff;
+        float *outp = dt.out ? dt.out[tl.seg] + tl.start : nullptr;
+        float *wp = STEP ? dt.w[tl.seg] + tl.start : nullptr;
+        float *vp = STEP ? dt.v[tl.seg] + tl.start : nullptr;
+        const uint32_t n = tl.n;
+        const bool tensors_al = (sg.flags & (SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
+                                (SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
+        if (tensors_al && !(moff & 3)) {
+            const uint32_t n4 = n >> 2;
+            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
+                const v4f avg = ld<NT>(reinterpret_cast<const v4f *>(src) + i);
+                finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
+            }
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
+                finish<STEP, NT, float>(ld<NT>(src + i), outp, wp, vp, i, lr, mu);
+        } else {
+            global_to_lds<NT>(src, lds, n);
+            __syncthreads();
+            uint32_t done = 0;
+            if (tensors_al) {
+                const uint32_t n4 = n >> 2;
+                for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
+                    const v4f avg = *reinterpret_cast<const v4f *>(lds + 4 * i);
+                    finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
+                }
+                done = n4 << 2;
+            }
+            for (uint32_t i = done + threadIdx.x; i < n; i += kBlock)
+                finish<STEP, NT, float>(lds[i], outp, wp, vp, i, lr, mu);
+        }
+    } else {
+        stage_gather_offsets(dt, tl, s_rel);
+        global_to_lds<NT>(reduced + (tl.start - base_off), lds, tl.n);
+        __syncthreads();
+        for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
+            const uint32_t s = find_segment(s_rel, tl.nseg, k);
+            const uint32_t si = tl.seg + s;
+            finish<STEP, NT, float>(lds[k], dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
+                                    STEP ? dt.v[si] : nullptr, k - s_rel[s], lr, mu);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Bandwidth probes
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kProbeTile = 8192;
+
+__global__ void __launch_bounds__(kBlock) k_probe_copy(const float *src, float *dst, uint64_t n)
+{
+    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * kProbeTile;
+    const uint32_t cnt = static_cast<uint32_t>(n - t0 < kProbeTile ? n - t0 : kProbeTile) >> 2;
+    const v4f *s4 = reinterpret_cast<const v4f *>(src + t0);
+    v4f *d4 = reinterpret_cast<v4f *>(dst + t0);
+    for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) st<true>(d4 + i, ld<true>(s4 + i));
+}
+
+template <int NW>
+__global__ void __launch_bounds__(kBlock)
+k_probe_streams(const float *src, uint64_t stride, uint64_t n, float *dst, float inv_n)
+{
+    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * kProbeTile;
+    const uint32_t cnt = static_cast<uint32_t>(n - t0 < kProbeTile ? n - t0 : kProbeTile) >> 2;
+    const float *sp[NW];
+#pragma unroll
+    for (int g = 0; g < NW; ++g) sp[g] = src + static_cast<uint64_t>(g) * stride + t0;
+    for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) {
+        const v4f avg = nway_mean_fixed<NW, true, v4f>(sp, i, inv_n);
+        st<true>(reinterpret_cast<v4f *>(dst + t0) + i, avg);
+    }
+}
+
+int check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error(std::string(what) + ": " + hipGetErrorString(e));
+        return MGWFBP_EHIP;
+    }
+    return MGWFBP_OK;
+}
+
+template <bool STEP, bool NT>
+void fused_dispatch(int nw, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
+                    float inv_n, float lr, float mu)
+{
+    switch (nw) {
+    case 1: k_fused<1, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    case 2: k_fused<2, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    case 4: k_fused<4, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    case 8: k_fused<8, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    case 16: k_fused<16, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    default: k_fused<0, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    }
+}
+
+template <bool NT>
+void reduce_dispatch(int nw, dim3 grid, hipStream_t s, float *ws, uint64_t epad, uint64_t elems,
+                     uint32_t tile, float inv_n)
+{
+    switch (nw) {
+    case 1: k_reduce<1, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    case 2: k_reduce<2, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    case 4: k_reduce<4, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    case 8: k_reduce<8, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    case 16: k_reduce<16, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    default: k_reduce<0, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    }
+}
+
+}  // namespace
+
+int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
+                 void *stream)
+{
+    if (sc.n_tiles == 0) return MGWFBP_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(sc.n_tiles);
+    const float inv_n = 1.0f / static_cast<float>(pl.N);
+    const bool nt = pl.opt.nontemporal != 0;
+    if (step) {
+        if (nt) fused_dispatch<true, true>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        else fused_dispatch<true, false>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+    } else {
+        if (nt) fused_dispatch<false, true>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        else fused_dispatch<false, false>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+    }
+    return check_launch("fused kernel launch");
+}
+
+int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                void *stream)
+{
+    if (sc.n_tiles == 0) return MGWFBP_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(sc.n_tiles, static_cast<uint32_t>(pl.N));
+    const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
+    if (pl.opt.nontemporal) k_pack<true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off);
+    else k_pack<false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off);
+    return check_launch("pack kernel launch");
+}
+
+int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                  void *stream)
+{
+    if (sc.elems == 0) return MGWFBP_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t tile = pl.opt.tile_elems;
+    const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
+    const float inv_n = 1.0f / static_cast<float>(pl.N);
+    if (pl.opt.nontemporal) reduce_dispatch<true>(pl.N, grid, s, ws, epad, sc.elems, tile, inv_n);
+    else reduce_dispatch<false>(pl.N, grid, s, ws, epad, sc.elems, tile, inv_n);
+    return check_launch("reduce kernel launch");
+}
+
+int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                  bool step, float lr, float mu, void *stream)
+{
+    if (sc.n_tiles == 0) return MGWFBP_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(sc.n_tiles);
+    const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
+    const float *reduced = ws + static_cast<uint64_t>(pl.N) * epad;
+    const bool nt = pl.opt.nontemporal != 0;
+    if (step) {
+        if (nt) k_unpack<true, true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+        else k_unpack<true, false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+    } else {
+        if (nt) k_unpack<false, true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+        else k_unpack<false, false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+    }
+    return check_launch("unpack kernel launch");
+}
+
+int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream)
+{
+    if (n == 0) return MGWFBP_OK;
+    const dim3 grid(static_cast<uint32_t>((n + kProbeTile - 1) / kProbeTile));
+    k_probe_copy<<<grid, kBlock, 0, static_cast<hipStream_t>(stream)>>>(src, dst, n);
+    return check_launch("probe copy launch");
+}
+
+int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
+                         float *dst, void *stream)
+{
+    if (n == 0) return MGWFBP_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(static_cast<uint32_t>((n + kProbeTile - 1) / kProbeTile));
+    const float inv_n = 1.0f / static_cast<float>(n_streams);
+    switch (n_streams) {
+    case 1: k_probe_streams<1><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
+    case 2: k_probe_streams<2><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
+    case 4: k_probe_streams<4><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
+    case 8: k_probe_streams<8><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
+    case 16: k_probe_streams<16><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
+    default:
+        set_error("probe_streams: n_streams must be 1, 2, 4, 8 or 16");
+        return MGWFBP_EINVAL;
+    }
+    return check_launch("probe streams launch");
+}
+
+}  // namespace mgwfbp

@@ -1,0 +1,137 @@
+// Internal data structures of libmgwfbp: the host-side plan and the device tables the
+// kernels walk.  Not part of the public ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/mgwfbp.h"
+
+namespace mgwfbp {
+
+// One layer's gradient inside the plan.  Segments are stored in communication order:
+// group 0 first, and inside a group the highest layer first (the order Algorithm 2's
+// layer buffer receives them).
+struct SegDev {
+    uint64_t n;          // elements p_l
+    uint64_t plan_off;   // offset in plan-wide merged coordinates (groups laid end to end)
+    uint64_t group_off;  // offset inside its own group's merged buffer
+    uint32_t layer;      // 0-based layer index
+    uint32_t group;
+    uint32_t flags;      // SEG_* bits
+    uint32_t pad;
+};
+static_assert(sizeof(SegDev) == 40, "SegDev layout");
+
+enum : uint32_t {
+    SEG_SRC_ALIGNED = 1u,  // all N gradient pointers of the layer are 16-byte aligned
+    SEG_OUT_ALIGNED = 2u,  // out pointer (if bound) is 16-byte aligned
+    SEG_WV_ALIGNED = 4u,   // w and v pointers (if bound) are 16-byte aligned
+};
+
+// Unit of work of one workgroup.
+//   nseg == 1 : "direct" tile, elements [start, start+n) of segment `seg`
+//   nseg  > 1 : "gather" tile, plan-wide merged coordinates [start, start+n), covering the
+//               whole of segments seg .. seg+nseg-1 (all of them short)
+struct TileDev {
+    uint64_t start;
+    uint32_t seg;
+    uint32_t nseg;
+    uint32_t n;
+    uint32_t pad;
+};
+static_assert(sizeof(TileDev) == 24, "TileDev layout");
+
+constexpr uint32_t kMaxGatherSegs = 256;  // segments one gather tile may span
+
+struct DeviceTables {
+    const SegDev *segs = nullptr;
+    const TileDev *tiles = nullptr;
+    const float *const *src = nullptr;  // [n_segs * N], segment-major
+    float *const *out = nullptr;        // [n_segs] or null
+    float *const *w = nullptr;          // [n_segs] or null
+    float *const *v = nullptr;          // [n_segs] or null
+};
+
+struct Options {
+    uint32_t tile_elems = 8192;
+    uint32_t small_elems = 2048;
+    int nontemporal = 1;
+};
+
+struct GroupInfo {
+    std::vector<int32_t> layers;  // arrival order (highest first)
+    uint64_t elems = 0;
+    uint64_t plan_off = 0;
+    uint32_t seg_begin = 0, seg_end = 0;
+    uint32_t tile_begin = 0, tile_end = 0;
+    bool needs_lds = false;  // a gather tile or a misaligned copy exists in this group
+    double start_ms = 0, finish_ms = 0;
+};
+
+}  // namespace mgwfbp
+
+struct mgwfbp_plan_s {
+    int32_t L = 0, N = 0;
+    std::vector<uint64_t> p;
+    std::vector<double> tb;
+    double tf = 0, a = 0, b = 0;
+    std::vector<uint8_t> merged;  // merged[l] != 0: layer l rides with layer l-1
+    std::vector<double> mu_b;
+    std::vector<int32_t> group_of_layer;
+    std::vector<uint64_t> off_in_group;
+    std::vector<mgwfbp::GroupInfo> groups;
+    double t_iter = 0, t_iter_wfbp = 0;
+    uint64_t total_elems = 0;
+
+    mgwfbp::Options opt;
+
+    // binding
+    bool bound = false, has_out = false, has_wv = false;
+    int device = -1;
+    bool all_needs_lds = false;
+    std::vector<mgwfbp::SegDev> segs;
+    std::vector<mgwfbp::TileDev> tiles;
+    void *d_blob = nullptr;  // one device allocation holding every table
+    mgwfbp::DeviceTables dt;
+};
+
+namespace mgwfbp {
+
+void set_error(const std::string &msg);
+
+// planner.cpp
+double simulate(const mgwfbp_plan_t &pl, const std::vector<uint8_t> &merged,
+                std::vector<double> *group_start, std::vector<double> *group_finish);
+void plan_optimal(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged);
+void plan_paper_greedy(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged);
+void finish_plan(mgwfbp_plan_t &pl);
+
+// tables.cpp
+void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
+                  float *const *w, float *const *v, std::vector<const float *> &src_tbl,
+                  std::vector<float *> &out_tbl, std::vector<float *> &w_tbl,
+                  std::vector<float *> &v_tbl);
+
+// kernels.hip
+struct LaunchScope {
+    uint32_t tile_begin, n_tiles;
+    uint64_t elems;       // elements in scope (one group or the whole plan)
+    uint64_t base_off;    // plan_off of the scope's first element
+    bool needs_lds;
+};
+int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
+                 void *stream);
+int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                void *stream);
+int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                  void *stream);
+int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
+                  bool step, float lr, float mu, void *stream);
+int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
+int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
+                         float *dst, void *stream);
+
+}  // namespace mgwfbp

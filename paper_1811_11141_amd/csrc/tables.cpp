@@ -1,0 +1,114 @@
+// Builds the flat tables the kernels walk: one segment per layer in communication order
+// (the order Algorithm 2's layer buffer is filled), and the tile list that cuts the plan
+// into equal pieces of work for the workgroups.
+#include "plan.hpp"
+
+#include <algorithm>
+
+namespace mgwfbp {
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
+                  float *const *w, float *const *v, std::vector<const float *> &src_tbl,
+                  std::vector<float *> &out_tbl, std::vector<float *> &w_tbl,
+                  std::vector<float *> &v_tbl)
+{
+    const int32_t L = pl.L, N = pl.N;
+    const uint32_t tile = pl.opt.tile_elems;
+    const uint32_t small = std::min(pl.opt.small_elems, tile);
+
+    pl.segs.clear();
+    pl.tiles.clear();
+    src_tbl.clear();
+    out_tbl.clear();
+    w_tbl.clear();
+    v_tbl.clear();
+    pl.all_needs_lds = false;
+
+    for (size_t k = 0; k < pl.groups.size(); ++k) {
+        GroupInfo &g = pl.groups[k];
+        g.seg_begin = static_cast<uint32_t>(pl.segs.size());
+        g.needs_lds = false;
+        for (int32_t l : g.layers) {
+            SegDev s{};
+            s.n = pl.p[l];
+            s.group_off = pl.off_in_group[l];
+            s.plan_off = g.plan_off + s.group_off;
+            s.layer = static_cast<uint32_t>(l);
+            s.group = static_cast<uint32_t>(k);
+            bool src_al = true;
+            for (int32_t r = 0; r < N; ++r) {
+                const float *ptr = grads[static_cast<size_t>(r) * L + l];
+                src_al = src_al && aligned16(ptr);
+                src_tbl.push_back(ptr);
+            }
+            if (src_al) s.flags |= SEG_SRC_ALIGNED;
+            if (out) {
+                out_tbl.push_back(out[l]);
+                if (aligned16(out[l])) s.flags |= SEG_OUT_ALIGNED;
+            } else {
+                s.flags |= SEG_OUT_ALIGNED;
+            }
+            if (w) {
+                w_tbl.push_back(w[l]);
+                v_tbl.push_back(v[l]);
+                if (aligned16(w[l]) && aligned16(v[l])) s.flags |= SEG_WV_ALIGNED;
+            } else {
+                s.flags |= SEG_WV_ALIGNED;
+            }
+            // A copy between the tensor and a merged buffer is a plain 128-bit copy only when
+            // both sides agree on 16-byte alignment, for the group-relative and the
+            // plan-relative merged layout alike.
+            const uint32_t all = SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED;
+            if ((s.flags & all) != all || (s.group_off & 3) || (s.plan_off & 3))
+                g.needs_lds = true;
+            pl.segs.push_back(s);
+        }
+        g.seg_end = static_cast<uint32_t>(pl.segs.size());
+
+        // Tiles of this group.  Long layers are cut into direct tiles; a run of short
+        // layers shares gather tiles so that tiny tensors cost no workgroup each.
+        g.tile_begin = static_cast<uint32_t>(pl.tiles.size());
+        uint32_t s = g.seg_begin;
+        while (s < g.seg_end) {
+            const SegDev &sd = pl.segs[s];
+            if (sd.n >= small) {
+                for (uint64_t st = 0; st < sd.n; st += tile) {
+                    TileDev t{};
+                    t.start = st;
+                    t.seg = s;
+                    t.nseg = 1;
+                    t.n = static_cast<uint32_t>(std::min<uint64_t>(tile, sd.n - st));
+                    pl.tiles.push_back(t);
+                }
+                ++s;
+                continue;
+            }
+            TileDev t{};
+            t.start = sd.plan_off;
+            t.seg = s;
+            uint64_t n = 0;
+            uint32_t cnt = 0;
+            while (s < g.seg_end && pl.segs[s].n < small && cnt < kMaxGatherSegs &&
+                   n + pl.segs[s].n <= tile) {
+                n += pl.segs[s].n;
+                ++cnt;
+                ++s;
+            }
+            t.nseg = cnt;
+            t.n = static_cast<uint32_t>(n);
+            if (cnt == 1) t.start = 0;  // a lone short layer is an ordinary direct tile
+            else g.needs_lds = true;
+            pl.tiles.push_back(t);
+        }
+        g.tile_end = static_cast<uint32_t>(pl.tiles.size());
+        pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
+    }
+}
+
+}  // namespace mgwfbp

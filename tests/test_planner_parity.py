@@ -1,0 +1,184 @@
+"""Host logic of the library (planner, plan tables, error paths) against the CPU oracle.
+No GPU is needed: nothing here launches a kernel."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import planner as op
+from paper_1811_11141_amd import binding as mg
+from paper_1811_11141_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def plan_for(w, mode, a=None, b=None, tf=0.0):
+    return mg.mgwfbp_plan(w.p, w.tb_ms, tf, w.a_ms if a is None else a,
+                          w.b_ms_per_byte if b is None else b, w.n_workers, mode)
+
+
+def oracle_args(w, a=None, b=None, tf=0.0):
+    return (w.p.tolist(), w.tb_ms.tolist(), tf, w.a_ms if a is None else a,
+            w.b_ms_per_byte if b is None else b)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mgwfbp.h")).read()
+    declared = set(re.findall(r"\b(mgwfbp_[a-z_]+)\s*\(", hdr))
+    assert declared == set(mg.EXPORTS)
+    lib = C.CDLL(mg.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_optimal_equals_brute_force_tiny_nets():
+    """Config 1: L = 8, all 128 partitions, many seeds; the optimum value is unique."""
+    mismatched_greedy = 0
+    for seed in range(120):
+        w = wl.tiny_workload(seed)
+        args = oracle_args(w)
+        t_best, _ = op.brute_force(*args)
+        pl = plan_for(w, mg.MODE_OPTIMAL)
+        inf = pl.info()
+        assert inf["t_iter_ms"] == t_best, seed
+        # the plan the library returns really has that cost under the oracle's evaluator
+        assert op.simulate(*args, pl.merged_layers()) == t_best
+        assert inf["t_iter_wfbp_ms"] == op.wfbp_timeline(*args)[1]
+        g = plan_for(w, mg.MODE_PAPER_GREEDY)
+        mismatched_greedy += g.info()["t_iter_ms"] > t_best
+    assert mismatched_greedy > 0        # Theorem 1's rule is not always optimal
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 5, 11])
+def test_optimal_equals_brute_force_other_sizes(L):
+    rng = np.random.default_rng(100 + L)
+    for _ in range(25 if L < 11 else 6):
+        w = wl.tiny_workload(int(rng.integers(1 << 30)), L=L)
+        a = float(rng.choice([0.0, 0.05, 0.5, 2.0, 20.0]))
+        b = float(rng.choice([0.0, 1e-6, 1e-4]))
+        tf = float(rng.uniform(0, 5))
+        args = oracle_args(w, a, b, tf)
+        pl = plan_for(w, mg.MODE_OPTIMAL, a, b, tf)
+        assert pl.info()["t_iter_ms"] == op.brute_force(*args)[0]
+
+
+def test_every_partition_evaluates_like_the_oracle():
+    w = wl.tiny_workload(5, L=6)
+    args = oracle_args(w)
+    for m in op.all_merge_sets(6):
+        pl = mg.mgwfbp_plan_explicit(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, 4, m)
+        assert pl.info()["t_iter_ms"] == op.simulate(*args, m)
+        assert pl.merged_layers() == sorted(m, reverse=True)
+        assert [[l + 1 for l in g] for g in pl.groups()] == op.groups_from_merged(6, m)
+
+
+def test_greedy_mode_is_algorithm1():
+    rng = np.random.default_rng(21)
+    for _ in range(300):
+        L = int(rng.integers(1, 14))
+        w = wl.tiny_workload(int(rng.integers(1 << 30)), L=L)
+        a = float(rng.choice([0.05, 0.5, 1.0, 2.0]))
+        pl = plan_for(w, mg.MODE_PAPER_GREEDY, a=a)
+        assert pl.merged_layers() == op.algorithm1(*oracle_args(w, a=a))
+
+
+def test_golden_cases_through_the_library(golden):
+    ex = golden["hand_worked_three_layers"]
+    mk = lambda mode: mg.mgwfbp_plan(ex["p"], ex["tb_ms"], 0.0, ex["a_ms"], ex["b_ms_per_byte"], 8, mode)
+    assert mk(mg.MODE_OPTIMAL).info()["t_iter_ms"] == pytest.approx(ex["optimum"], rel=1e-12)
+    assert mk(mg.MODE_OPTIMAL).merged_layers() == [2]
+    g = mk(mg.MODE_PAPER_GREEDY)
+    assert g.merged_layers() == ex["theorem1_merged"]
+    assert g.info()["t_iter_ms"] == pytest.approx(ex["t_iter"]["3,2"], rel=1e-12)
+    assert mk(mg.MODE_WFBP).info()["t_iter_ms"] == pytest.approx(ex["t_iter"][""], rel=1e-12)
+    assert mk(mg.MODE_SINGLE).info()["t_iter_ms"] == pytest.approx(ex["t_iter"]["3,2"], rel=1e-12)
+    for c in golden["hand_worked_traces"]["cases"]:
+        pl = mg.mgwfbp_plan(c["p"], c["tb_ms"], 0.0, c["a_ms"], c["b_ms_per_byte"], 8,
+                            mg.MODE_PAPER_GREEDY)
+        assert pl.merged_layers() == c["merged"]
+        assert pl.info()["t_iter_ms"] == pytest.approx(c["t_iter"], rel=1e-12)
+
+
+def test_modes_wfbp_and_single_and_offsets():
+    w = wl.tiny_workload(9)
+    L = w.L
+    wf = plan_for(w, mg.MODE_WFBP).info()
+    assert wf["n_groups"] == L
+    assert wf["group_of_layer"].tolist() == list(range(L - 1, -1, -1))
+    assert wf["group_elems"].tolist() == w.p[::-1].tolist()
+    assert wf["t_iter_ms"] == wf["t_iter_wfbp_ms"]
+    sg = plan_for(w, mg.MODE_SINGLE).info()
+    assert sg["n_groups"] == 1 and int(sg["group_elems"][0]) == w.P
+    # arrival order: the top layer sits at offset 0, no padding between layers
+    off = 0
+    for l in range(L - 1, -1, -1):
+        assert int(sg["offset_in_group"][l]) == off
+        off += int(w.p[l])
+    assert sg["t_iter_ms"] == pytest.approx(sum(w.tb_ms) + w.a_ms + w.b_ms_per_byte * 4 * w.P, rel=1e-12)
+
+
+def test_timeline_matches_eq6_to_8():
+    w = wl.tiny_workload(10)
+    pl = plan_for(w, mg.MODE_WFBP)
+    tl = pl.timeline()
+    args = oracle_args(w)
+    assert tl["mu_b"].tolist() == op.backward_finish(w.tb_ms.tolist(), 0.0)
+    tau_c, t_iter = op.wfbp_timeline(*args)
+    assert tl["group_start"].tolist() == tau_c[::-1]
+    assert tl["group_finish"][-1] == t_iter
+
+
+def test_cnn_plans_are_consistent():
+    for name in wl.CNN_WORKLOADS:
+        w = wl.cnn_workload(name)
+        args = oracle_args(w)
+        opt, gr = plan_for(w, mg.MODE_OPTIMAL), plan_for(w, mg.MODE_PAPER_GREEDY)
+        t_opt, t_gr = opt.info()["t_iter_ms"], gr.info()["t_iter_ms"]
+        t_wf = op.wfbp_timeline(*args)[1]
+        t_single = op.simulate(*args, range(2, w.L + 1))
+        assert t_opt == op.simulate(*args, opt.merged_layers())
+        assert gr.merged_layers() == op.algorithm1(*args)
+        assert t_opt <= t_gr <= t_wf * (1 + 1e-12)
+        assert t_opt <= t_single
+        inf = opt.info()
+        assert int(inf["group_elems"].sum()) == w.P
+
+
+def test_error_paths():
+    lib = mg.raw()
+    p = (C.c_uint64 * 3)(10, 20, 30)
+    tb = (C.c_double * 3)(1.0, 1.0, 1.0)
+    h = C.c_void_p()
+    call = lambda L=3, pp=p, tt=tb, tf=0.0, a=0.5, b=1e-6, N=4, mode=0, out=C.byref(h): \
+        lib.mgwfbp_plan(L, pp, tt, tf, a, b, N, mode, out)
+    assert call(L=0) == mg.EINVAL and "L" in mg.last_error()
+    assert call(N=0) == mg.EINVAL
+    assert call(pp=None) == mg.EINVAL
+    assert call(tt=None) == mg.EINVAL
+    assert call(a=-1.0) == mg.EINVAL
+    assert call(b=float("nan")) == mg.EINVAL
+    assert call(tf=float("inf")) == mg.EINVAL
+    assert call(mode=9) == mg.EINVAL
+    assert call(out=None) == mg.EINVAL
+    assert call(pp=(C.c_uint64 * 3)(10, 0, 30)) == mg.EINVAL and "p_elems[1]" in mg.last_error()
+    assert call(tt=(C.c_double * 3)(1.0, -2.0, 1.0)) == mg.EINVAL
+    assert h.value is None
+    assert call() == mg.OK and h.value
+    # launches before bind are a state error; no kernel is launched
+    assert lib.mgwfbp_pack_reduce_unpack(h, -1, None, 0, None) == mg.ESTATE
+    assert lib.mgwfbp_step(h, -1, 0.1, 0.9, None, 0, None) == mg.ESTATE
+    assert lib.mgwfbp_bind(h, None, None, None, None) == mg.EINVAL
+    n = C.c_size_t()
+    assert lib.mgwfbp_workspace_bytes(h, 7, C.byref(n)) == mg.EINVAL
+    assert lib.mgwfbp_workspace_bytes(h, -1, C.byref(n)) == mg.OK and n.value == 5 * 64 * 4
+    assert lib.mgwfbp_plan_set_option(h, mg.OPT_TILE_ELEMS, 1000) == mg.EINVAL
+    assert lib.mgwfbp_plan_set_option(h, mg.OPT_TILE_ELEMS, 4096) == mg.OK
+    assert lib.mgwfbp_plan_set_option(h, 99, 1) == mg.EINVAL
+    assert lib.mgwfbp_plan_info(None, None, None, None, None, None, None) == mg.EINVAL
+    merged = (C.c_uint8 * 3)(1, 0, 0)
+    h2 = C.c_void_p()
+    assert lib.mgwfbp_plan_explicit(3, p, tb, 0.0, 0.5, 1e-6, 4, merged, C.byref(h2)) == mg.EINVAL
+    lib.mgwfbp_plan_destroy(h)
+    lib.mgwfbp_plan_destroy(None)
