@@ -39,6 +39,10 @@ def _load() -> C.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_1811_11141_amd.build` "
             "(there is no fallback path)")
+    # PyTorch owns the device memory and streams this library works on, and ships its own
+    # HIP runtime.  Import it first so that libmgwfbp.so resolves libamdhip64 to that same
+    # already-loaded runtime: two HIP runtimes in one process do not share a device.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, u64, f64, f32, sz = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double,
                                        C.c_float, C.c_size_t)
