@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Throughput of the merged pack+reduce+unpack pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+
+A step is one pass of the whole hot path over one synthetic gradient set: all N workers'
+per-layer gradients are packed, summed in worker order, scaled by 1/N and written back to
+per-layer tensors, for every group of the merge plan, in one fused launch
+(mgwfbp_pack_reduce_unpack with group = -1).  Inputs are resident in HBM before the timed
+region.  Consecutive steps rotate over several independently allocated gradient sets so that
+no step finds its inputs in the 256 MB Infinity Cache.
+
+Prints one JSON line.  `value` = algorithmic bytes 4*(N+1)*P per step / wall time per step.
+`roofline.achieved` = the same bytes / average kernel duration from HIP events recorded
+around every launch on the launch stream.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by what the same counters read for the library's plain copy probe.  Filled from the
+# summaries under profiles/ (see profiles/README.md); None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "googlenet", "alexnet", "vgg16"])
+    ap.add_argument("--a-ms", type=float, default=0.5)
+    ap.add_argument("--mode", default="optimal", choices=["optimal", "greedy", "wfbp", "single"])
+    ap.add_argument("--sets", type=int, default=0, help="gradient sets to rotate over (0 = auto)")
+    ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--small", type=int, default=-1)
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--variant", default="fused", choices=["fused", "step", "materialised", "per_group"],
+                    help="what one step runs (the headline is 'fused')")
+    ap.add_argument("--extras", type=int, default=1, help="also time the other variants and the probes")
+    ap.add_argument("--cpu-baseline", type=int, default=1)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the other workers are "
+              "replicas in the same HBM); run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1811_11141_amd import binding as mg
+    from paper_1811_11141_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w = wl.cnn_workload(args.workload, a_ms=args.a_ms)
+    N, P, L = w.n_workers, w.P, w.L
+    mode = {"optimal": mg.MODE_OPTIMAL, "greedy": mg.MODE_PAPER_GREEDY, "wfbp": mg.MODE_WFBP,
+            "single": mg.MODE_SINGLE}[args.mode]
+
+    alg_bytes = {"fused": 4 * (N + 1) * P, "per_group": 4 * (N + 1) * P,
+                 "materialised": 4 * (N + 1) * P, "step": 4 * (N + 5) * P}
+    set_bytes = 4 * (N + 1) * P
+    n_sets = args.sets if args.sets > 0 else max(2, min(4, int(np.ceil(768e6 / set_bytes)) + 1))
+    if args.workload == "vgg16":
+        n_sets = args.sets if args.sets > 0 else 1  # 9.4 GB per pass evicts itself
+
+    def new_plan():
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, N, mode)
+        if args.tile:
+            pl.set_option(mg.OPT_TILE_ELEMS, args.tile)
+        if args.small >= 0:
+            pl.set_option(mg.OPT_SMALL_ELEMS, args.small)
+        if args.nontemporal >= 0:
+            pl.set_option(mg.OPT_NONTEMPORAL, args.nontemporal)
+        return pl
+
+    sets = []
+    for s in range(n_sets):
+        grads = wl.make_gradients(w, wl.BASE_SEED + 1000 * 2 + s, dev)
+        out = [torch.empty_like(t) for t in grads[0]]
+        wt, vt = wl.make_weights(w, wl.BASE_SEED + s, dev)
+        pl = new_plan()
+        pl.bind(grads, out, wt, vt)
+        sets.append({"plan": pl, "grads": grads, "out": out, "w": wt, "v": vt})
+    info = sets[0]["plan"].info()
+    n_groups = info["n_groups"]
+    ws = None
+    if args.variant == "materialised" or args.extras:
+        ws = torch.empty(sets[0]["plan"].workspace_bytes() // 4, dtype=torch.float32, device=dev)
+
+    stream = torch.cuda.Stream(device=dev)
+
+    def run_step(variant, i):
+        pl = sets[i % n_sets]["plan"]
+        if variant == "fused":
+            pl.pack_reduce_unpack(stream=stream)
+        elif variant == "step":
+            pl.step(0.1, 0.9, stream=stream)
+        elif variant == "materialised":
+            pl.pack_reduce_unpack(workspace=ws, stream=stream)
+        elif variant == "per_group":
+            for k in range(n_groups):
+                pl.pack_reduce_unpack(group=k, stream=stream)
+
+    def timed(variant, steps, warmup, launch_events):
+        for i in range(warmup):
+            run_step(variant, i)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(steps)] if launch_events else None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            if evs:
+                evs[i][0].record(stream)
+            run_step(variant, warmup + i)
+            if evs:
+                evs[i][1].record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms = (t1 - t0) * 1e3 / steps
+        kern = None
+        if evs:
+            d = np.array([a.elapsed_time(b) for a, b in evs])
+            kern = {"avg_ms": float(d.mean()), "median_ms": float(np.median(d)), "min_ms": float(d.min())}
+        return ms, kern
+
+    ms_per_step, kern = timed(args.variant, args.steps, args.warmup, launch_events=True)
+    bytes_step = alg_bytes[args.variant]
+    value = bytes_step / (ms_per_step * 1e-3) / 1e9
+    achieved = bytes_step / (kern["avg_ms"] * 1e-3) / 1e9
+
+    result = {
+        "metric": "merged pack+reduce+unpack HBM GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped gradient set", "tensors": L, "P": P,
+                   "n_workers": N, "plan": args.mode, "a_ms": w.a_ms, "b_ms_per_byte": w.b_ms_per_byte,
+                   "groups": n_groups, "variant": args.variant, "rotating_sets": n_sets,
+                   "algorithmic_bytes_per_step": bytes_step,
+                   "percent_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant)),
+                     "kernel": "k_fused" if args.variant in ("fused", "per_group", "step") else "k_pack+k_reduce+k_unpack",
+                     "kernel_avg_us": round(kern["avg_ms"] * 1e3, 2),
+                     "kernel_median_us": round(kern["median_ms"] * 1e3, 2),
+                     "kernel_min_us": round(kern["min_ms"] * 1e3, 2)},
+    }
+
+    if args.extras:
+        extra = {}
+        k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 4)
+        for variant in ("fused", "step", "materialised", "per_group"):
+            if variant == args.variant:
+                continue
+            ms, kk = timed(variant, k2, w2, launch_events=True)
+            extra[variant] = {"ms_per_step": round(ms, 5),
+                              "GBps_algorithmic": round(alg_bytes[variant] / (ms * 1e-3) / 1e9, 1),
+                              "event_avg_us": round(kk["avg_ms"] * 1e3, 2)}
+        # plain streaming ceilings: N reads + 1 write over contiguous buffers, and a copy
+        n_probe = (P + 3) // 4 * 4
+        src = torch.empty(N * n_probe, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty(n_probe, dtype=torch.float32, device=dev)
+        srcs = [src] + [torch.empty_like(src).normal_() for _ in range(n_sets - 1)]
+        for nm, fn, nbytes in (
+                ("probe_streams", lambda i: mg.mgwfbp_probe_streams(srcs[i % n_sets], N, n_probe, n_probe, dst, stream), 4 * (N + 1) * n_probe),
+                ("probe_copy", lambda i: mg.mgwfbp_probe_copy(srcs[i % n_sets], srcs[(i + 1) % n_sets], N * n_probe, stream), 8 * N * n_probe)):
+            for i in range(w2):
+                fn(i)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
+            for i in range(k2):
+                evs[i][0].record(stream)
+                fn(i)
+                evs[i][1].record(stream)
+            torch.cuda.synchronize()
+            d = np.array([a.elapsed_time(b) for a, b in evs])
+            extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
+                         "GBps": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1)}
+        del src, dst, srcs
+        result["extra"] = extra
+
+    if args.cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, sets[0], info, args.cpu_seconds)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, s, info, budget_s):
+    """The CPU oracle, as it stands, on the same gradient set: whole passes of
+    pack -> reduce -> unpack over host copies of set 0, single thread (the oracle's default)."""
+    import numpy as np
+
+    from oracle import datapath as od
+
+    N, P = w.n_workers, w.P
+    groups = s["plan"].groups()
+    g_np = [[t.cpu().numpy() for t in rep] for rep in s["grads"]]
+    od.merged_gradient_path([[a[:16].copy() for a in rep] for rep in g_np], groups)  # load + warm
+    passes, t0 = 0, time.perf_counter()
+    while True:
+        od.merged_gradient_path(g_np, groups, threads=1)
+        passes += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or passes >= 50:
+            break
+    sec = el / passes
+    nthreads = min(od.max_threads(), os.cpu_count() or 1)
+    t1 = time.perf_counter()
+    od.merged_gradient_path(g_np, groups, threads=nthreads)
+    sec_mt = time.perf_counter() - t1
+    return {"value": round(4 * (N + 1) * P / sec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{passes} whole passes of the oracle (pack, reduce, unpack per group) over "
+                      f"gradient set 0 of the same workload, {el:.1f} s",
+            "seconds_per_pass": round(sec, 4),
+            "all_threads": {"threads": nthreads, "value": round(4 * (N + 1) * P / sec_mt / 1e9, 3),
+                            "seconds_per_pass": round(sec_mt, 4),
+                            "note": "reduce loop split statically over threads; pack/unpack stay serial"}}
+
+
+if __name__ == "__main__":
+    main()

@@ -62,6 +62,8 @@ int make_plan(int32_t L, const uint64_t *p, const double *tb, double tf, double 
             pl->mu_b[l] = t;
         }
         pl->merged.assign(L, 0);
+        // default tile: 64 (N <= 8) or 32..64 (N = 16) 128-bit loads per lane in the fused kernel
+        pl->opt.tile_elems = N >= 16 ? 2048 : 4096;
     } catch (const std::bad_alloc &) {
         delete pl;
         return fail(MGWFBP_ENOMEM, "out of host memory");
@@ -89,8 +91,8 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
     if (group < -1 || group >= static_cast<int32_t>(pl->groups.size()))
         return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
     if (group < 0) {
-        sc.tile_begin = 0;
-        sc.n_tiles = static_cast<uint32_t>(pl->tiles.size());
+        sc.tile_begin = pl->all_tile_begin;
+        sc.n_tiles = pl->all_tile_count;
         sc.elems = pl->total_elems;
         sc.base_off = 0;
         sc.needs_lds = pl->all_needs_lds;

@@ -10,7 +10,7 @@
 //
 // The path is bound by HBM bandwidth (0.2-0.3 flop per byte), so the kernels are built
 // around 128-bit coalesced accesses with all N loads of a lane issued before the first add;
-// there is nothing for the matrix cores to do.  One workgroup of 256 lanes (4 wave64) owns
+// there is nothing for the matrix cores to do.  One workgroup of 128 lanes (2 wave64) owns
 // one tile.  Arithmetic order is fixed (worker 0 first, one rounding per operation; the file
 // is compiled with -ffp-contract=off) so results are reproducible bit for bit.
 #include <hip/hip_runtime.h>
@@ -22,7 +22,7 @@ namespace mgwfbp {
 
 namespace {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 128;  // 2 wave64 per workgroup
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -45,6 +45,31 @@ __device__ __forceinline__ void st(T *p, T x)
     MGWFBP_GLOBAL T *gp = (MGWFBP_GLOBAL T *)p;
     if constexpr (NT) __builtin_nontemporal_store(x, gp);
     else *gp = x;
+}
+
+// The plan tables (tiles, segments, pointer arrays) are written once by the host and never by
+// a kernel.  Reading them through the constant address space tells the compiler so, and a
+// load whose address is uniform over the wave then becomes a scalar load into SGPRs.
+#define MGWFBP_CONST __attribute__((address_space(4)))
+
+template <class T>
+__device__ __forceinline__ T table_load(const T *p)
+{
+    return *(const MGWFBP_CONST T *)p;
+}
+
+// A tile descriptor is three 64-bit words: start | seg, nseg | n, pad.
+__device__ __forceinline__ TileDev load_tile(const TileDev *p)
+{
+    const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
+    const uint64_t w1 = table_load(q + 1), w2 = table_load(q + 2);
+    TileDev t;
+    t.start = table_load(q);
+    t.seg = static_cast<uint32_t>(w1);
+    t.nseg = static_cast<uint32_t>(w1 >> 32);
+    t.n = static_cast<uint32_t>(w2);
+    t.pad = 0;
+    return t;
 }
 
 // v = mu*v + g ; w = w - lr*v with one rounding per operation.
@@ -173,32 +198,147 @@ __device__ __forceinline__ void lds_to_global(const float *lds, float *dst, uint
 // ------------------------------------------------------------------------------------------
 // Fused single pass
 // ------------------------------------------------------------------------------------------
-template <int NW, bool STEP, bool NT>
+
+// 128-bit streaming (non-temporal) accesses at (uniform base pointer) + (32-bit lane byte
+// offset): the form the hardware addresses with a scalar register pair plus one vector
+// register.  The loads of the fast path are written as instructions so that their order and
+// the number in flight are exactly what the code says: left to itself the compiler hoists all
+// N*U loads of a tile to the top, which costs ~270 registers and drops the occupancy to one
+// wave per SIMD.  Such a load is invisible to the compiler's own wait-count bookkeeping, so
+// every value is passed through wait_loads<K>() before its first use.
+__device__ __forceinline__ v4f ld_stream(const char *base, uint32_t voff)
+{
+    v4f r;
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(r) : "v"(voff), "s"(base));
+    return r;
+}
+
+// Same load, ordered after the computation of `dep` (an in/out operand that is not touched).
+__device__ __forceinline__ v4f ld_stream_after(const char *base, uint32_t voff, v4f &dep)
+{
+    v4f r;
+    asm volatile("global_load_dwordx4 %0, %2, %3 nt" : "=v"(r), "+v"(dep) : "v"(voff), "s"(base));
+    return r;
+}
+
+// Block until at most K of this wave's vector-memory loads are still outstanding.  Loads
+// complete in issue order, so "all but the newest K" covers x when K loads were issued after
+// it.  x is an in/out operand only to pin the wait between the load and the use of x.
+template <int K>
+__device__ __forceinline__ void wait_loads(v4f &x)
+{
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(x) : "n"(K));
+}
+
+__device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
+{
+    __builtin_nontemporal_store(x, (MGWFBP_GLOBAL v4f *)(base + voff));
+}
+
+// A full tile of U*kBlock float4 per worker, every pointer 16-byte aligned.  Each lane owns U
+// float4 (lane-interleaved, so every wave access is one contiguous KiB).  The whole tile is
+// read before anything is written: HBM runs best when reads and writes come in separate
+// bursts, and mixing the stores into the load stream costs 10-15 % of the bandwidth.  Loads
+// are kept D deep in flight through a small register ring; the adds consume them in issue
+// order, so worker g is always added after worker g-1.
+template <int NW, int U, bool STEP>
+__device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t start, float *outp,
+                                          float *wp, float *vp, float inv_n, float lr, float mu)
+{
+    constexpr int T = NW * U;
+    constexpr int D = T < 4 ? T : 4;
+    const char *sb[NW];
+#pragma unroll
+    for (int g = 0; g < NW; ++g) sb[g] = reinterpret_cast<const char *>(table_load(sp_tbl + g) + start);
+    uint32_t vo[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) vo[u] = threadIdx.x * 16u + u * (kBlock * 16u);
+    v4f x[D];
+    v4f res[U];
+#pragma unroll
+    for (int j = 0; j < D; ++j) x[j] = ld_stream(sb[j % NW], vo[j / NW]);
+#pragma unroll
+    for (int j = 0; j < T; ++j) {
+        const int g = j % NW, u = j / NW;
+        // loads j+1 .. min(j+D, T)-1 were issued after load j
+        constexpr int kAll = D - 1;
+        if (T - 1 - j >= kAll) wait_loads<kAll>(x[j % D]);
+        else if (T - 1 - j == 2) wait_loads<2>(x[j % D]);
+        else if (T - 1 - j == 1) wait_loads<1>(x[j % D]);
+        else wait_loads<0>(x[j % D]);
+        if (g == 0) res[u] = x[j % D];
+        else res[u] = res[u] + x[j % D];
+        if (g == NW - 1) res[u] = res[u] * inv_n;
+        // the next load re-uses the slot just consumed; naming res[u] as an operand keeps the
+        // add above ahead of it, so no more than D loaded values are ever live
+        if (j + D < T) x[j % D] = ld_stream_after(sb[(j + D) % NW], vo[(j + D) / NW], res[u]);
+    }
+    if constexpr (STEP) {
+        // weights and momentum: read a batch, update, write the batch
+        char *wb = reinterpret_cast<char *>(wp);
+        char *vb = reinterpret_cast<char *>(vp);
+        constexpr int UB = U < 4 ? U : 4;  // float4 of w and of v held at once
+#pragma unroll
+        for (int u0 = 0; u0 < U; u0 += UB) {
+            v4f w[UB], v[UB];
+#pragma unroll
+            for (int k = 0; k < UB; ++k) {
+                w[k] = __builtin_nontemporal_load((const MGWFBP_GLOBAL v4f *)(wb + vo[u0 + k]));
+                v[k] = __builtin_nontemporal_load((const MGWFBP_GLOBAL v4f *)(vb + vo[u0 + k]));
+            }
+#pragma unroll
+            for (int k = 0; k < UB; ++k) sgd_momentum(res[u0 + k], w[k], v[k], lr, mu);
+#pragma unroll
+            for (int k = 0; k < UB; ++k) {
+                st_stream(vb, vo[u0 + k], v[k]);
+                st_stream(wb, vo[u0 + k], w[k]);
+            }
+        }
+    }
+    // without the update the averaged gradient is the only output, so out[] is always bound
+    if (!STEP || outp) {
+        char *ob = reinterpret_cast<char *>(outp);
+#pragma unroll
+        for (int u = 0; u < U; ++u) st_stream(ob, vo[u], res[u]);
+    }
+}
+
+// U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
+// misaligned tensors, gather tiles, run-time N) takes the general path below.
+template <int NW, int U, bool STEP, bool NT>
 __global__ void __launch_bounds__(kBlock)
 k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu)
 {
     __shared__ uint32_t s_rel[kMaxGatherSegs];
-    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
-        const uint32_t flags = dt.segs[tl.seg].flags;
+        const uint32_t flags = table_load(&dt.segs[tl.seg].flags);
         const float *const *sp_tbl = dt.src + static_cast<size_t>(tl.seg) * nw;
-        float *outp = dt.out ? dt.out[tl.seg] + tl.start : nullptr;
-        float *wp = STEP ? dt.w[tl.seg] + tl.start : nullptr;
-        float *vp = STEP ? dt.v[tl.seg] + tl.start : nullptr;
+        float *outp = dt.out ? table_load(dt.out + tl.seg) + tl.start : nullptr;
+        float *wp = STEP ? table_load(dt.w + tl.seg) + tl.start : nullptr;
+        float *vp = STEP ? table_load(dt.v + tl.seg) + tl.start : nullptr;
         const uint32_t n = tl.n;
         const bool vec = (flags & (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
                          (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
+        if constexpr (NW > 0 && U > 0) {
+            if (vec && n == U * kBlock * 4) {
+                fast_tile<NW, U, STEP>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu);
+                return;
+            }
+        }
         const uint32_t n4 = vec ? (n >> 2) : 0;
         if constexpr (NW > 0) {
             // per-worker base pointers of this tile (uniform over the workgroup)
             const float *sp[NW];
 #pragma unroll
-            for (int g = 0; g < NW; ++g) sp[g] = sp_tbl[g] + tl.start;
+            for (int g = 0; g < NW; ++g) sp[g] = table_load(sp_tbl + g) + tl.start;
+#pragma unroll 1
             for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
                 const v4f avg = nway_mean_fixed<NW, NT, v4f>(sp, i, inv_n);
                 finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
             }
+#pragma unroll 1
             for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) {
                 const float avg = nway_mean_fixed<NW, NT, float>(sp, i, inv_n);
                 finish<STEP, NT, float>(avg, outp, wp, vp, i, lr, mu);
@@ -206,10 +346,12 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
         } else {
             const uint64_t start = tl.start;
             auto ptr = [sp_tbl, start](int g) { return sp_tbl[g] + start; };
+#pragma unroll 1
             for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
                 const v4f avg = nway_mean_dyn<NT, v4f>(ptr, nw, i, inv_n);
                 finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
             }
+#pragma unroll 1
             for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) {
                 const float avg = nway_mean_dyn<NT, float>(ptr, nw, i, inv_n);
                 finish<STEP, NT, float>(avg, outp, wp, vp, i, lr, mu);
@@ -217,6 +359,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
         }
     } else {
         stage_gather_offsets(dt, tl, s_rel);
+#pragma unroll 1
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
             const uint32_t s = find_segment(s_rel, tl.nseg, k);
             const uint32_t si = tl.seg + s;
@@ -241,7 +384,7 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
 {
     extern __shared__ float lds[];
     __shared__ uint32_t s_rel[kMaxGatherSegs];
-    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
     const uint32_t g = blockIdx.y;
     float *merged = ws + static_cast<uint64_t>(g) * epad;
 
@@ -309,7 +452,7 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
 {
     extern __shared__ float lds[];
     __shared__ uint32_t s_rel[kMaxGatherSegs];
-    const TileDev tl = dt.tiles[tile_begin + blockIdx.x];
+    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
         const SegDev sg = dt.segs[tl.seg];
@@ -396,17 +539,38 @@ int check_launch(const char *what)
     return MGWFBP_OK;
 }
 
+// The fast path exists for tiles of U*kBlock float4 with NW*U <= 64 loads per lane.
+template <int NW, bool STEP, bool NT>
+void fused_launch_u(int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb, int nw,
+                    float inv_n, float lr, float mu)
+{
+#define MGWFBP_LAUNCH(UU)                                                                      \
+    k_fused<NW, UU, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu)
+    if constexpr (NW > 0) {
+        if (NT && u == 2) { MGWFBP_LAUNCH(2); return; }
+        if (NT && u == 4) { MGWFBP_LAUNCH(4); return; }
+        if constexpr (NW <= 8) {
+            if (NT && u == 8) { MGWFBP_LAUNCH(8); return; }
+        }
+        if constexpr (NW <= 4) {
+            if (NT && u == 16) { MGWFBP_LAUNCH(16); return; }
+        }
+    }
+    MGWFBP_LAUNCH(0);
+#undef MGWFBP_LAUNCH
+}
+
 template <bool STEP, bool NT>
-void fused_dispatch(int nw, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
+void fused_dispatch(int nw, int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
                     float inv_n, float lr, float mu)
 {
     switch (nw) {
-    case 1: k_fused<1, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
-    case 2: k_fused<2, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
-    case 4: k_fused<4, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
-    case 8: k_fused<8, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
-    case 16: k_fused<16, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
-    default: k_fused<0, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu); break;
+    case 1: fused_launch_u<1, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    case 2: fused_launch_u<2, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    case 4: fused_launch_u<4, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    case 8: fused_launch_u<8, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    case 16: fused_launch_u<16, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    default: fused_launch_u<0, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
     }
 }
 
@@ -434,12 +598,13 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const dim3 grid(sc.n_tiles);
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const bool nt = pl.opt.nontemporal != 0;
+    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));  // float4 per lane per worker
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
-        else fused_dispatch<true, false>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        if (nt) fused_dispatch<true, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        else fused_dispatch<true, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
-        else fused_dispatch<false, false>(pl.N, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        if (nt) fused_dispatch<false, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        else fused_dispatch<false, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
     }
     return check_launch("fused kernel launch");
 }

@@ -56,8 +56,8 @@ struct DeviceTables {
 };
 
 struct Options {
-    uint32_t tile_elems = 8192;
-    uint32_t small_elems = 2048;
+    uint32_t tile_elems = 4096;
+    uint32_t small_elems = 512;
     int nontemporal = 1;
 };
 
@@ -92,6 +92,7 @@ struct mgwfbp_plan_s {
     bool bound = false, has_out = false, has_wv = false;
     int device = -1;
     bool all_needs_lds = false;
+    uint32_t all_tile_begin = 0, all_tile_count = 0;  // whole-plan ordering of the tiles
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table

@@ -21,6 +21,9 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     const int32_t L = pl.L, N = pl.N;
     const uint32_t tile = pl.opt.tile_elems;
     const uint32_t small = std::min(pl.opt.small_elems, tile);
+    // elements one gather tile may hold: a few per lane, since each costs a table search
+    const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
+    std::vector<TileDev> all_slow, all_full;
 
     pl.segs.clear();
     pl.tiles.clear();
@@ -72,8 +75,10 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         g.seg_end = static_cast<uint32_t>(pl.segs.size());
 
         // Tiles of this group.  Long layers are cut into direct tiles; a run of short
-        // layers shares gather tiles so that tiny tensors cost no workgroup each.
-        g.tile_begin = static_cast<uint32_t>(pl.tiles.size());
+        // layers shares gather tiles so that tiny tensors cost no workgroup each.  Gather
+        // tiles and ragged tails run the general (slower) code path, so they are listed first:
+        // workgroups are dispatched in order and the slow ones then overlap with the bulk.
+        std::vector<TileDev> slow, full;
         uint32_t s = g.seg_begin;
         while (s < g.seg_end) {
             const SegDev &sd = pl.segs[s];
@@ -84,7 +89,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                     t.seg = s;
                     t.nseg = 1;
                     t.n = static_cast<uint32_t>(std::min<uint64_t>(tile, sd.n - st));
-                    pl.tiles.push_back(t);
+                    (t.n == tile ? full : slow).push_back(t);
                 }
                 ++s;
                 continue;
@@ -95,7 +100,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             uint64_t n = 0;
             uint32_t cnt = 0;
             while (s < g.seg_end && pl.segs[s].n < small && cnt < kMaxGatherSegs &&
-                   n + pl.segs[s].n <= tile) {
+                   n + pl.segs[s].n <= gather_cap) {
                 n += pl.segs[s].n;
                 ++cnt;
                 ++s;
@@ -104,11 +109,22 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             t.n = static_cast<uint32_t>(n);
             if (cnt == 1) t.start = 0;  // a lone short layer is an ordinary direct tile
             else g.needs_lds = true;
-            pl.tiles.push_back(t);
+            slow.push_back(t);
         }
+        g.tile_begin = static_cast<uint32_t>(pl.tiles.size());
+        pl.tiles.insert(pl.tiles.end(), slow.begin(), slow.end());
+        pl.tiles.insert(pl.tiles.end(), full.begin(), full.end());
+        all_slow.insert(all_slow.end(), slow.begin(), slow.end());
+        all_full.insert(all_full.end(), full.begin(), full.end());
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
         pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
     }
+    // A second copy of the tile list for whole-plan launches: every slow tile of every group
+    // first, then the full tiles.
+    pl.all_tile_begin = static_cast<uint32_t>(pl.tiles.size());
+    pl.tiles.insert(pl.tiles.end(), all_slow.begin(), all_slow.end());
+    pl.tiles.insert(pl.tiles.end(), all_full.begin(), all_full.end());
+    pl.all_tile_count = static_cast<uint32_t>(all_slow.size() + all_full.size());
 }
 
 }  // namespace mgwfbp
