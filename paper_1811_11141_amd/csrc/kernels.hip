@@ -199,13 +199,13 @@ __device__ __forceinline__ void lds_to_global(const float *lds, float *dst, uint
 // Fused single pass
 // ------------------------------------------------------------------------------------------
 
-// 128-bit streaming (non-temporal) accesses at (uniform base pointer) + (32-bit lane byte
-// offset): the form the hardware addresses with a scalar register pair plus one vector
-// register.  The loads of the fast path are written as instructions so that their order and
-// the number in flight are exactly what the code says: left to itself the compiler hoists all
-// N*U loads of a tile to the top, which costs ~270 registers and drops the occupancy to one
-// wave per SIMD.  Such a load is invisible to the compiler's own wait-count bookkeeping, so
-// every value is passed through wait_loads<K>() before its first use.
+// 128-bit streaming (non-temporal) load at (uniform base pointer) + (32-bit lane byte offset):
+// the form the hardware addresses with a scalar register pair plus one vector register.  The
+// loads of the fast path are written as instructions so that their order and the number in
+// flight are exactly what the code says (left to itself the compiler hoists all N*U loads of
+// a tile to the top, ~270 registers, one wave per SIMD).  Such a load is invisible to the
+// compiler's own wait-count bookkeeping, so its result is passed through wait_all_loads()
+// before the first use.
 __device__ __forceinline__ v4f ld_stream(const char *base, uint32_t voff)
 {
     v4f r;
@@ -221,13 +221,11 @@ __device__ __forceinline__ v4f ld_stream_after(const char *base, uint32_t voff, 
     return r;
 }
 
-// Block until at most K of this wave's vector-memory loads are still outstanding.  Loads
-// complete in issue order, so "all but the newest K" covers x when K loads were issued after
-// it.  x is an in/out operand only to pin the wait between the load and the use of x.
-template <int K>
-__device__ __forceinline__ void wait_loads(v4f &x)
+// Block until none of this wave's vector-memory loads is outstanding.  x is an in/out operand
+// only to pin the wait between the load and the first use of x.
+__device__ __forceinline__ void wait_all_loads(v4f &x)
 {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(x) : "n"(K));
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(x));
 }
 
 __device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
@@ -235,63 +233,80 @@ __device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
     __builtin_nontemporal_store(x, (MGWFBP_GLOBAL v4f *)(base + voff));
 }
 
+// A uniform pointer moved into scalar registers whatever the compiler thought of it.
+__device__ __forceinline__ const char *scalar_ptr(const void *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// Short pause between two loads of a wave (units of ~64 clocks).
+__device__ __forceinline__ void pace_wave(int pace)
+{
+    for (int k = 0; k < pace; ++k) __builtin_amdgcn_s_sleep(1);
+}
+
 // A full tile of U*kBlock float4 per worker, every pointer 16-byte aligned.  Each lane owns U
-// float4 (lane-interleaved, so every wave access is one contiguous KiB).  The whole tile is
-// read before anything is written: HBM runs best when reads and writes come in separate
-// bursts, and mixing the stores into the load stream costs 10-15 % of the bandwidth.  Loads
-// are kept D deep in flight through a small register ring; the adds consume them in issue
-// order, so worker g is always added after worker g-1.
+// float4 (lane-interleaved, so every wave access is one contiguous KiB).  What measurement on
+// MI355X says about streaming N buffers into one:
+//   * one load in flight per wave, at full occupancy (8 waves per SIMD), beats any deeper
+//     pipelining: a second outstanding load of the same wave costs 5-10 % of the bandwidth,
+//     more when it goes to another worker's buffer (loads of a wave must return in order);
+//   * visit one worker's buffer for all U pieces before moving to the next worker;
+//   * read the whole tile before writing anything: stores mixed into the load stream cost
+//     another 10-15 %;
+//   * a pause of ~64 clocks between loads gains a further 1-2 %.
+// So: U accumulators in registers, worker-major loop (which is also the fixed summation
+// order: worker g is added after worker g-1), every load waited for before the next is
+// issued, all stores at the end.
 template <int NW, int U, bool STEP>
 __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t start, float *outp,
-                                          float *wp, float *vp, float inv_n, float lr, float mu)
+                                          float *wp, float *vp, float inv_n, float lr, float mu,
+                                          int pace)
 {
-    constexpr int T = NW * U;
-    constexpr int D = T < 4 ? T : 4;
-    const char *sb[NW];
-#pragma unroll
-    for (int g = 0; g < NW; ++g) sb[g] = reinterpret_cast<const char *>(table_load(sp_tbl + g) + start);
     uint32_t vo[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) vo[u] = threadIdx.x * 16u + u * (kBlock * 16u);
-    v4f x[D];
     v4f res[U];
 #pragma unroll
-    for (int j = 0; j < D; ++j) x[j] = ld_stream(sb[j % NW], vo[j / NW]);
+    for (int g = 0; g < NW; ++g) {
+        const char *sb = scalar_ptr(table_load(sp_tbl + g) + start);
 #pragma unroll
-    for (int j = 0; j < T; ++j) {
-        const int g = j % NW, u = j / NW;
-        // loads j+1 .. min(j+D, T)-1 were issued after load j
-        constexpr int kAll = D - 1;
-        if (T - 1 - j >= kAll) wait_loads<kAll>(x[j % D]);
-        else if (T - 1 - j == 2) wait_loads<2>(x[j % D]);
-        else if (T - 1 - j == 1) wait_loads<1>(x[j % D]);
-        else wait_loads<0>(x[j % D]);
-        if (g == 0) res[u] = x[j % D];
-        else res[u] = res[u] + x[j % D];
-        if (g == NW - 1) res[u] = res[u] * inv_n;
-        // the next load re-uses the slot just consumed; naming res[u] as an operand keeps the
-        // add above ahead of it, so no more than D loaded values are ever live
-        if (j + D < T) x[j % D] = ld_stream_after(sb[(j + D) % NW], vo[(j + D) / NW], res[u]);
+        for (int u = 0; u < U; ++u) {
+            // the load is ordered after the previous add through its operand res[..]
+            v4f x = (g == 0 && u == 0) ? ld_stream(sb, vo[u])
+                                       : ld_stream_after(sb, vo[u], res[u == 0 ? U - 1 : u - 1]);
+            wait_all_loads(x);
+            if (g == 0) res[u] = x;
+            else res[u] = res[u] + x;
+            pace_wave(pace);
+        }
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) res[u] = res[u] * inv_n;
     if constexpr (STEP) {
         // weights and momentum: read a batch, update, write the batch
-        char *wb = reinterpret_cast<char *>(wp);
-        char *vb = reinterpret_cast<char *>(vp);
-        constexpr int UB = U < 4 ? U : 4;  // float4 of w and of v held at once
+        const char *wb = scalar_ptr(wp);
+        const char *vb = scalar_ptr(vp);
+        constexpr int UB = U < 2 ? U : 2;  // float4 of w and of v held at once
 #pragma unroll
         for (int u0 = 0; u0 < U; u0 += UB) {
             v4f w[UB], v[UB];
 #pragma unroll
             for (int k = 0; k < UB; ++k) {
-                w[k] = __builtin_nontemporal_load((const MGWFBP_GLOBAL v4f *)(wb + vo[u0 + k]));
-                v[k] = __builtin_nontemporal_load((const MGWFBP_GLOBAL v4f *)(vb + vo[u0 + k]));
+                w[k] = ld_stream_after(wb, vo[u0 + k], res[u0 + k]);
+                wait_all_loads(w[k]);
+                v[k] = ld_stream_after(vb, vo[u0 + k], w[k]);
+                wait_all_loads(v[k]);
             }
 #pragma unroll
             for (int k = 0; k < UB; ++k) sgd_momentum(res[u0 + k], w[k], v[k], lr, mu);
 #pragma unroll
             for (int k = 0; k < UB; ++k) {
-                st_stream(vb, vo[u0 + k], v[k]);
-                st_stream(wb, vo[u0 + k], w[k]);
+                st_stream(const_cast<char *>(vb), vo[u0 + k], v[k]);
+                st_stream(const_cast<char *>(wb), vo[u0 + k], w[k]);
             }
         }
     }
@@ -307,7 +322,7 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
 // misaligned tensors, gather tiles, run-time N) takes the general path below.
 template <int NW, int U, bool STEP, bool NT>
 __global__ void __launch_bounds__(kBlock)
-k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu)
+k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace)
 {
     __shared__ uint32_t s_rel[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
@@ -323,7 +338,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
                          (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
         if constexpr (NW > 0 && U > 0) {
             if (vec && n == U * kBlock * 4) {
-                fast_tile<NW, U, STEP>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu);
+                fast_tile<NW, U, STEP>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu, pace);
                 return;
             }
         }
@@ -539,22 +554,17 @@ int check_launch(const char *what)
     return MGWFBP_OK;
 }
 
-// The fast path exists for tiles of U*kBlock float4 with NW*U <= 64 loads per lane.
+// The fast path exists for tiles of U*kBlock float4, U = 2, 4 or 8 (1024, 2048, 4096 elements).
 template <int NW, bool STEP, bool NT>
 void fused_launch_u(int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb, int nw,
-                    float inv_n, float lr, float mu)
+                    float inv_n, float lr, float mu, int pace)
 {
 #define MGWFBP_LAUNCH(UU)                                                                      \
-    k_fused<NW, UU, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu)
+    k_fused<NW, UU, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace)
     if constexpr (NW > 0) {
         if (NT && u == 2) { MGWFBP_LAUNCH(2); return; }
         if (NT && u == 4) { MGWFBP_LAUNCH(4); return; }
-        if constexpr (NW <= 8) {
-            if (NT && u == 8) { MGWFBP_LAUNCH(8); return; }
-        }
-        if constexpr (NW <= 4) {
-            if (NT && u == 16) { MGWFBP_LAUNCH(16); return; }
-        }
+        if (NT && u == 8) { MGWFBP_LAUNCH(8); return; }
     }
     MGWFBP_LAUNCH(0);
 #undef MGWFBP_LAUNCH
@@ -562,15 +572,15 @@ void fused_launch_u(int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uin
 
 template <bool STEP, bool NT>
 void fused_dispatch(int nw, int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
-                    float inv_n, float lr, float mu)
+                    float inv_n, float lr, float mu, int pace)
 {
     switch (nw) {
-    case 1: fused_launch_u<1, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
-    case 2: fused_launch_u<2, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
-    case 4: fused_launch_u<4, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
-    case 8: fused_launch_u<8, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
-    case 16: fused_launch_u<16, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
-    default: fused_launch_u<0, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu); break;
+    case 1: fused_launch_u<1, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 2: fused_launch_u<2, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 4: fused_launch_u<4, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 8: fused_launch_u<8, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 16: fused_launch_u<16, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    default: fused_launch_u<0, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
     }
 }
 
@@ -600,11 +610,11 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const bool nt = pl.opt.nontemporal != 0;
     const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));  // float4 per lane per worker
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
-        else fused_dispatch<true, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        if (nt) fused_dispatch<true, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        else fused_dispatch<true, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
-        else fused_dispatch<false, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu);
+        if (nt) fused_dispatch<false, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        else fused_dispatch<false, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
     }
     return check_launch("fused kernel launch");
 }
