@@ -15,6 +15,8 @@
 // is compiled with -ffp-contract=off) so results are reproducible bit for bit.
 #include <hip/hip_runtime.h>
 
+#include <utility>
+
 #include "../../include/mgwfbp.h"
 #include "plan.hpp"
 
@@ -221,12 +223,29 @@ __device__ __forceinline__ v4f ld_stream_after(const char *base, uint32_t voff, 
     return r;
 }
 
-// Block until none of this wave's vector-memory loads is outstanding.  x is an in/out operand
-// only to pin the wait between the load and the first use of x.
-__device__ __forceinline__ void wait_all_loads(v4f &x)
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a
+// compile-time constant in every iteration.
+template <int... J, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, J...>, F f)
 {
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(x));
+    (f(std::integral_constant<int, J>{}), ...);
 }
+
+template <int N, class F>
+__device__ __forceinline__ void static_for(F f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Block until at most K of this wave's vector-memory loads are outstanding.  Loads return in issue order, so this covers x when k loads were issued
+// after it.  x is an in/out operand only to pin the wait between the load and its first use.
+template <int K>
+__device__ __forceinline__ void wait_loads(v4f &x)
+{
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(x) : "n"(K));
+}
+
+__device__ __forceinline__ void wait_all_loads(v4f &x) { wait_loads<0>(x); }
 
 __device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
 {
@@ -261,7 +280,7 @@ __device__ __forceinline__ void pace_wave(int pace)
 // So: U accumulators in registers, worker-major loop (which is also the fixed summation
 // order: worker g is added after worker g-1), every load waited for before the next is
 // issued, all stores at the end.
-template <int NW, int U, bool STEP>
+template <int NW, int U, bool STEP, int D>
 __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t start, float *outp,
                                           float *wp, float *vp, float inv_n, float lr, float mu,
                                           int pace)
@@ -270,19 +289,46 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
 #pragma unroll
     for (int u = 0; u < U; ++u) vo[u] = threadIdx.x * 16u + u * (kBlock * 16u);
     v4f res[U];
+    if constexpr (D == 1) {
 #pragma unroll
-    for (int g = 0; g < NW; ++g) {
-        const char *sb = scalar_ptr(table_load(sp_tbl + g) + start);
+        for (int g = 0; g < NW; ++g) {
+            const char *sb = scalar_ptr(table_load(sp_tbl + g) + start);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            // the load is ordered after the previous add through its operand res[..]
-            v4f x = (g == 0 && u == 0) ? ld_stream(sb, vo[u])
-                                       : ld_stream_after(sb, vo[u], res[u == 0 ? U - 1 : u - 1]);
-            wait_all_loads(x);
-            if (g == 0) res[u] = x;
-            else res[u] = res[u] + x;
-            pace_wave(pace);
+            for (int u = 0; u < U; ++u) {
+                // the load is ordered after the previous add through its operand res[..]
+                v4f x = (g == 0 && u == 0) ? ld_stream(sb, vo[u])
+                                           : ld_stream_after(sb, vo[u], res[u == 0 ? U - 1 : u - 1]);
+                wait_all_loads(x);
+                if (g == 0) res[u] = x;
+                else res[u] = res[u] + x;
+                pace_wave(pace);
+            }
         }
+    } else {
+        // Launches too small to fill the chip are bound by latency, not bandwidth: keep D
+        // loads in flight through a register ring (same visiting and summation order).
+        constexpr int T = NW * U;
+        constexpr int DD = D < T ? D : T;
+        const char *sb[NW];
+#pragma unroll
+        for (int g = 0; g < NW; ++g) sb[g] = scalar_ptr(table_load(sp_tbl + g) + start);
+        v4f x[DD];
+        static_for<DD>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            x[j] = ld_stream(sb[j / U], vo[j % U]);
+        });
+        static_for<T>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            constexpr int g = j / U, u = j % U;
+            constexpr int newer = T - 1 - j < DD - 1 ? T - 1 - j : DD - 1;  // loads issued after load j
+            wait_loads<newer>(x[j % DD]);
+            if constexpr (g == 0) res[u] = x[j % DD];
+            else res[u] = res[u] + x[j % DD];
+            // the next load re-uses the slot just consumed; naming res[u] as an operand keeps
+            // the add above ahead of it, so no more than DD loaded values are ever live
+            if constexpr (j + DD < T)
+                x[j % DD] = ld_stream_after(sb[(j + DD) / U], vo[(j + DD) % U], res[u]);
+        });
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) res[u] = res[u] * inv_n;
@@ -320,7 +366,7 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
 
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
 // misaligned tensors, gather tiles, run-time N) takes the general path below.
-template <int NW, int U, bool STEP, bool NT>
+template <int NW, int U, bool STEP, bool NT, int D>
 __global__ void __launch_bounds__(kBlock)
 k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace)
 {
@@ -338,7 +384,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
                          (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
         if constexpr (NW > 0 && U > 0) {
             if (vec && n == U * kBlock * 4) {
-                fast_tile<NW, U, STEP>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu, pace);
+                fast_tile<NW, U, STEP, D>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu, pace);
                 return;
             }
         }
@@ -555,32 +601,33 @@ int check_launch(const char *what)
 }
 
 // The fast path exists for tiles of U*kBlock float4, U = 2, 4 or 8 (1024, 2048, 4096 elements).
+// deep = launch too small to fill the chip (latency-bound): 8 loads in flight per wave.
 template <int NW, bool STEP, bool NT>
-void fused_launch_u(int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb, int nw,
-                    float inv_n, float lr, float mu, int pace)
+void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
+                    int nw, float inv_n, float lr, float mu, int pace)
 {
-#define MGWFBP_LAUNCH(UU)                                                                      \
-    k_fused<NW, UU, STEP, NT><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace)
-    if constexpr (NW > 0) {
-        if (NT && u == 2) { MGWFBP_LAUNCH(2); return; }
-        if (NT && u == 4) { MGWFBP_LAUNCH(4); return; }
-        if (NT && u == 8) { MGWFBP_LAUNCH(8); return; }
+#define MGWFBP_LAUNCH(UU, DD)                                                                  \
+    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace)
+    if constexpr (NW > 0 && NT) {
+        if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
+        if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
+        if (u == 8) { if (deep) MGWFBP_LAUNCH(8, 8); else MGWFBP_LAUNCH(8, 1); return; }
     }
-    MGWFBP_LAUNCH(0);
+    MGWFBP_LAUNCH(0, 1);
 #undef MGWFBP_LAUNCH
 }
 
 template <bool STEP, bool NT>
-void fused_dispatch(int nw, int u, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
-                    float inv_n, float lr, float mu, int pace)
+void fused_dispatch(int nw, int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt,
+                    uint32_t tb, float inv_n, float lr, float mu, int pace)
 {
     switch (nw) {
-    case 1: fused_launch_u<1, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 2: fused_launch_u<2, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 4: fused_launch_u<4, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 8: fused_launch_u<8, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 16: fused_launch_u<16, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    default: fused_launch_u<0, STEP, NT>(u, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 1: fused_launch_u<1, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 2: fused_launch_u<2, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 4: fused_launch_u<4, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 8: fused_launch_u<8, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 16: fused_launch_u<16, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    default: fused_launch_u<0, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
     }
 }
 
@@ -609,12 +656,15 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const bool nt = pl.opt.nontemporal != 0;
     const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));  // float4 per lane per worker
+    // 256 CUs x 4 SIMDs x 8 waves = 8192 wave slots = 4096 workgroups; below about half of that
+    // the launch cannot saturate HBM with one load per wave and is bound by latency instead
+    const bool deep = sc.n_tiles < 2048;
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
-        else fused_dispatch<true, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
-        else fused_dispatch<false, false>(pl.N, u, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
     }
     return check_launch("fused kernel launch");
 }
