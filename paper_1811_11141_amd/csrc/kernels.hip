@@ -74,6 +74,15 @@ __device__ __forceinline__ TileDev load_tile(const TileDev *p)
     return t;
 }
 
+// The fields of a segment descriptor the kernels need (plan offset and flags).
+__device__ __forceinline__ SegDev load_seg(const SegDev *p)
+{
+    SegDev sg{};
+    sg.plan_off = table_load(&p->plan_off);
+    sg.flags = table_load(&p->flags);
+    return sg;
+}
+
 // v = mu*v + g ; w = w - lr*v with one rounding per operation.
 template <class T>
 __device__ __forceinline__ void sgd_momentum(T g, T &w, T &v, float lr, float mu)
@@ -253,11 +262,16 @@ __device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
 }
 
 // A uniform pointer moved into scalar registers whatever the compiler thought of it.
+// An SGPR written by a vector instruction (v_readfirstlane) must not be read by a vector
+// memory instruction for 5 wait states.  The compiler pads its own memory instructions, but it
+// does not look inside the hand-written loads, so the padding is done here: the s_nop takes
+// both halves as operands, which places it after the readfirstlanes and before any use.
 __device__ __forceinline__ const char *scalar_ptr(const void *p)
 {
     const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    asm volatile("s_nop 4" : "+s"(lo), "+s"(hi));
     return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
@@ -280,10 +294,13 @@ __device__ __forceinline__ void pace_wave(int pace)
 // So: U accumulators in registers, worker-major loop (which is also the fixed summation
 // order: worker g is added after worker g-1), every load waited for before the next is
 // issued, all stores at the end.
-template <int NW, int U, bool STEP, int D>
-__device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t start, float *outp,
-                                          float *wp, float *vp, float inv_n, float lr, float mu,
-                                          int pace)
+//
+// src(g) yields worker g's tile base pointer (uniform over the workgroup).  SCALE = false
+// skips the multiplication by 1/N: with NW = 1 the tile is then moved bit for bit, which is
+// what pack and unpack need.
+template <int NW, int U, bool STEP, int D, bool SCALE, class SrcFn>
+__device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, float *vp,
+                                          float inv_n, float lr, float mu, int pace)
 {
     uint32_t vo[U];
 #pragma unroll
@@ -292,7 +309,7 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
     if constexpr (D == 1) {
 #pragma unroll
         for (int g = 0; g < NW; ++g) {
-            const char *sb = scalar_ptr(table_load(sp_tbl + g) + start);
+            const char *sb = scalar_ptr(src(g));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // the load is ordered after the previous add through its operand res[..]
@@ -311,7 +328,7 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
         constexpr int DD = D < T ? D : T;
         const char *sb[NW];
 #pragma unroll
-        for (int g = 0; g < NW; ++g) sb[g] = scalar_ptr(table_load(sp_tbl + g) + start);
+        for (int g = 0; g < NW; ++g) sb[g] = scalar_ptr(src(g));
         v4f x[DD];
         static_for<DD>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -330,8 +347,10 @@ __device__ __forceinline__ void fast_tile(const float *const *sp_tbl, uint64_t s
                 x[j % DD] = ld_stream_after(sb[(j + DD) / U], vo[(j + DD) % U], res[u]);
         });
     }
+    if constexpr (SCALE) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) res[u] = res[u] * inv_n;
+        for (int u = 0; u < U; ++u) res[u] = res[u] * inv_n;
+    }
     if constexpr (STEP) {
         // weights and momentum: read a batch, update, write the batch
         const char *wb = scalar_ptr(wp);
@@ -384,7 +403,10 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
                          (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
         if constexpr (NW > 0 && U > 0) {
             if (vec && n == U * kBlock * 4) {
-                fast_tile<NW, U, STEP, D>(sp_tbl, tl.start, outp, wp, vp, inv_n, lr, mu, pace);
+                const uint64_t start = tl.start;
+                fast_tile<NW, U, STEP, D, true>(
+                    [sp_tbl, start](int g) { return table_load(sp_tbl + g) + start; }, outp, wp, vp,
+                    inv_n, lr, mu, pace);
                 return;
             }
         }
@@ -439,9 +461,10 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
 // Workspace: N packed replica buffers of `epad` floats each, then the reduced buffer.
 // `base_off` is the plan offset of the scope's first element (0 for the whole plan).
 
-template <bool NT>
+template <bool NT, int U, int D>
 __global__ void __launch_bounds__(kBlock)
-k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, uint64_t base_off)
+k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, uint64_t base_off,
+       int pace)
 {
     extern __shared__ float lds[];
     __shared__ uint32_t s_rel[kMaxGatherSegs];
@@ -450,11 +473,18 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
     float *merged = ws + static_cast<uint64_t>(g) * epad;
 
     if (tl.nseg == 1) {
-        const SegDev sg = dt.segs[tl.seg];
-        const float *src = dt.src[static_cast<size_t>(tl.seg) * nw + g] + tl.start;
+        const SegDev sg = load_seg(dt.segs + tl.seg);
+        const float *src = table_load(dt.src + static_cast<size_t>(tl.seg) * nw + g) + tl.start;
         const uint64_t moff = sg.plan_off - base_off + tl.start;
         float *dst = merged + moff;
         const uint32_t n = tl.n;
+        if constexpr (U > 0) {
+            if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3) && n == U * kBlock * 4) {
+                fast_tile<1, U, false, D, false>([src](int) { return src; }, dst, nullptr, nullptr,
+                                                 1.0f, 0.0f, 0.0f, pace);
+                return;
+            }
+        }
         if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3)) {
             const uint32_t n4 = n >> 2;
             const v4f *s4 = reinterpret_cast<const v4f *>(src);
@@ -481,24 +511,34 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
     }
 }
 
-template <int NW, bool NT>
+template <int NW, bool NT, int U, int D>
 __global__ void __launch_bounds__(kBlock)
-k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float inv_n)
+k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float inv_n, int pace)
 {
     const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * tile;
     const uint32_t n = static_cast<uint32_t>(elems - t0 < tile ? elems - t0 : tile);
     float *outp = ws + static_cast<uint64_t>(nw) * epad + t0;
+    if constexpr (NW > 0 && U > 0) {
+        if (n == U * kBlock * 4) {
+            fast_tile<NW, U, false, D, true>(
+                [ws, epad, t0](int g) { return ws + static_cast<uint64_t>(g) * epad + t0; }, outp,
+                nullptr, nullptr, inv_n, 0.0f, 0.0f, pace);
+            return;
+        }
+    }
     const uint32_t n4 = n >> 2;  // workspace and epad keep every buffer 16-byte aligned
     if constexpr (NW > 0) {
         const float *sp[NW];
 #pragma unroll
         for (int g = 0; g < NW; ++g) sp[g] = ws + static_cast<uint64_t>(g) * epad + t0;
+#pragma unroll 1
         for (uint32_t i = threadIdx.x; i < n4; i += kBlock)
             st<NT>(reinterpret_cast<v4f *>(outp) + i, nway_mean_fixed<NW, NT, v4f>(sp, i, inv_n));
         for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
             st<NT>(outp + i, nway_mean_fixed<NW, NT, float>(sp, i, inv_n));
     } else {
         auto ptr = [ws, epad, t0](int g) { return ws + static_cast<uint64_t>(g) * epad + t0; };
+#pragma unroll 1
         for (uint32_t i = threadIdx.x; i < n4; i += kBlock)
             st<NT>(reinterpret_cast<v4f *>(outp) + i, nway_mean_dyn<NT, v4f>(ptr, nw, i, inv_n));
         for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
@@ -506,25 +546,32 @@ k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float 
     }
 }
 
-template <bool STEP, bool NT>
+template <bool STEP, bool NT, int U, int D>
 __global__ void __launch_bounds__(kBlock)
 k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t base_off, float lr,
-         float mu)
+         float mu, int pace)
 {
     extern __shared__ float lds[];
     __shared__ uint32_t s_rel[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
-        const SegDev sg = dt.segs[tl.seg];
+        const SegDev sg = load_seg(dt.segs + tl.seg);
         const uint64_t moff = sg.plan_off - base_off + tl.start;
         const float *src = reduced + moff;
-        float *outp = dt.out ? dt.out[tl.seg] + tl.start : nullptr;
-        float *wp = STEP ? dt.w[tl.seg] + tl.start : nullptr;
-        float *vp = STEP ? dt.v[tl.seg] + tl.start : nullptr;
+        float *outp = dt.out ? table_load(dt.out + tl.seg) + tl.start : nullptr;
+        float *wp = STEP ? table_load(dt.w + tl.seg) + tl.start : nullptr;
+        float *vp = STEP ? table_load(dt.v + tl.seg) + tl.start : nullptr;
         const uint32_t n = tl.n;
         const bool tensors_al = (sg.flags & (SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
                                 (SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
+        if constexpr (U > 0) {
+            if (tensors_al && !(moff & 3) && n == U * kBlock * 4) {
+                fast_tile<1, U, STEP, D, false>([src](int) { return src; }, outp, wp, vp, 1.0f, lr,
+                                                mu, pace);
+                return;
+            }
+        }
         if (tensors_al && !(moff & 3)) {
             const uint32_t n4 = n >> 2;
             for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
@@ -631,18 +678,30 @@ void fused_dispatch(int nw, int u, bool deep, dim3 grid, hipStream_t s, const De
     }
 }
 
-template <bool NT>
-void reduce_dispatch(int nw, dim3 grid, hipStream_t s, float *ws, uint64_t epad, uint64_t elems,
-                     uint32_t tile, float inv_n)
+// Run fn(U_const, D_const) for the (U, deep) pair chosen at run time; U = 0 selects the general
+// code only.
+template <class Fn>
+void with_shape(bool fast, int u, bool deep, Fn fn)
 {
-    switch (nw) {
-    case 1: k_reduce<1, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
-    case 2: k_reduce<2, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
-    case 4: k_reduce<4, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
-    case 8: k_reduce<8, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
-    case 16: k_reduce<16, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
-    default: k_reduce<0, NT><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n); break;
+    using std::integral_constant;
+    if (fast && u == 2) { if (deep) fn(integral_constant<int, 2>{}, integral_constant<int, 8>{}); else fn(integral_constant<int, 2>{}, integral_constant<int, 1>{}); return; }
+    if (fast && u == 4) { if (deep) fn(integral_constant<int, 4>{}, integral_constant<int, 8>{}); else fn(integral_constant<int, 4>{}, integral_constant<int, 1>{}); return; }
+    if (fast && u == 8) { if (deep) fn(integral_constant<int, 8>{}, integral_constant<int, 8>{}); else fn(integral_constant<int, 8>{}, integral_constant<int, 1>{}); return; }
+    fn(integral_constant<int, 0>{}, integral_constant<int, 1>{});
+}
+
+template <int NW>
+void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *ws, uint64_t epad,
+                   uint64_t elems, uint32_t tile, int nw, float inv_n, int pace)
+{
+    if (!nt) {
+        k_reduce<NW, false, 0, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
+        return;
     }
+    with_shape(NW > 0, u, deep, [&](auto uc, auto dc) {
+        k_reduce<NW, true, decltype(uc)::value, decltype(dc)::value>
+            <<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
+    });
 }
 
 }  // namespace
@@ -676,8 +735,17 @@ int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint6
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(sc.n_tiles, static_cast<uint32_t>(pl.N));
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    if (pl.opt.nontemporal) k_pack<true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off);
-    else k_pack<false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off);
+    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));
+    const bool deep = static_cast<uint64_t>(sc.n_tiles) * pl.N < 2048;
+    const int pace = pl.opt.pace;
+    if (!pl.opt.nontemporal) {
+        k_pack<false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off, pace);
+    } else {
+        with_shape(true, u, deep, [&](auto uc, auto dc) {
+            k_pack<true, decltype(uc)::value, decltype(dc)::value>
+                <<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off, pace);
+        });
+    }
     return check_launch("pack kernel launch");
 }
 
@@ -689,8 +757,17 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
     const uint32_t tile = pl.opt.tile_elems;
     const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
     const float inv_n = 1.0f / static_cast<float>(pl.N);
-    if (pl.opt.nontemporal) reduce_dispatch<true>(pl.N, grid, s, ws, epad, sc.elems, tile, inv_n);
-    else reduce_dispatch<false>(pl.N, grid, s, ws, epad, sc.elems, tile, inv_n);
+    const int u = static_cast<int>(tile / (kBlock * 4));
+    const bool deep = grid.x < 2048;
+    const bool nt = pl.opt.nontemporal != 0;
+    switch (pl.N) {
+    case 1: reduce_launch<1>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    case 2: reduce_launch<2>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    case 4: reduce_launch<4>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    case 8: reduce_launch<8>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    case 16: reduce_launch<16>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    default: reduce_launch<0>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    }
     return check_launch("reduce kernel launch");
 }
 
@@ -702,13 +779,18 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
     const dim3 grid(sc.n_tiles);
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
     const float *reduced = ws + static_cast<uint64_t>(pl.N) * epad;
-    const bool nt = pl.opt.nontemporal != 0;
-    if (step) {
-        if (nt) k_unpack<true, true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
-        else k_unpack<true, false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));
+    const bool deep = sc.n_tiles < 2048;
+    const int pace = pl.opt.pace;
+    if (!pl.opt.nontemporal) {
+        if (step) k_unpack<true, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
+        else k_unpack<false, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
     } else {
-        if (nt) k_unpack<false, true><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
-        else k_unpack<false, false><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu);
+        with_shape(true, u, deep, [&](auto uc, auto dc) {
+            constexpr int U = decltype(uc)::value, D = decltype(dc)::value;
+            if (step) k_unpack<true, true, U, D><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
+            else k_unpack<false, true, U, D><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
+        });
     }
     return check_launch("unpack kernel launch");
 }

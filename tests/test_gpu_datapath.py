@@ -154,6 +154,22 @@ def test_fused_tilings(mg, tile, small):
         assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
 
 
+@pytest.mark.parametrize("nt,pace", [(0, 0), (1, 0), (1, 3)])
+def test_fused_options_do_not_change_results(mg, nt, pace):
+    """Non-temporal on/off and the pacing of loads are performance knobs only."""
+    w = wl.custom_workload([300000, 4096, 513, 8192 * 3 + 5], 8, sigma=1e-3)
+    pl = make_plan(mg, w, [4, 2], tile=4096, nt=nt)
+    pl.set_option(mg.OPT_PACE, pace)
+    grads = wl.make_gradients(w, 61, "cuda")
+    out = [torch.empty_like(t) for t in grads[0]]
+    pl.bind(grads, out)
+    pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    exp = od.merged_gradient_path([to_np(r) for r in grads], groups0(w.L, [4, 2]))
+    for l in range(w.L):
+        assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
+
+
 def test_fused_many_tiny_layers_exceeding_one_gather_tile(mg):
     sizes = [3] * 700 + [70000] + [1] * 50
     w = wl.custom_workload(sizes, 2, sigma=1.0)
@@ -382,14 +398,20 @@ def window_starts(n, rng, width):
     return [(s, width) for s in picks]
 
 
-@pytest.mark.parametrize("name,a_ms", [("resnet50", 0.5), ("googlenet", 0.5), ("alexnet", 0.5),
-                                        ("vgg16", 0.1), ("vgg16", 2.0)])
-def test_full_size_sets_sampled(mg, name, a_ms):
+@pytest.mark.parametrize("name,a_ms,tile,per_group", [
+    ("resnet50", 0.5, None, False), ("googlenet", 0.5, None, False), ("alexnet", 0.5, None, False),
+    ("vgg16", 0.1, None, False), ("vgg16", 2.0, None, False),
+    ("resnet50", 0.5, None, True),       # one launch per group, as Algorithm 2 would issue them
+    ("googlenet", 0.5, 1024, False), ("googlenet", 0.5, 2048, False), ("alexnet", 0.5, 8192, False)])
+def test_full_size_sets_sampled(mg, name, a_ms, tile, per_group):
     """The ResNet-50 / GoogLeNet / AlexNet / VGG-16 shaped sets at full size and worker count,
-    with the default launch configuration.  The oracle recomputes sampled windows of every
-    layer (whole layers when short); for the update, the same windows of w and v."""
+    in the launch configuration bench.py times (default tile, whole plan in one launch), plus
+    the other tile sizes and the launch-per-group sequence.  The oracle recomputes sampled
+    windows of every layer (whole layers when short); for the update, the same windows of w, v."""
     w = wl.cnn_workload(name, a_ms=a_ms)
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    if tile is not None:
+        pl.set_option(mg.OPT_TILE_ELEMS, tile)
     grads = wl.make_gradients(w, wl.BASE_SEED, "cuda")
     out = [torch.full_like(t, float("nan")) for t in grads[0]]
     wt, vt = wl.make_weights(w, wl.BASE_SEED, "cuda")
@@ -400,8 +422,13 @@ def test_full_size_sets_sampled(mg, name, a_ms):
     w0 = {(l, s): wt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
     v0 = {(l, s): vt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
     pl.bind(grads, out, wt, vt)
-    pl.pack_reduce_unpack()
-    pl.step(0.1, 0.9)
+    if per_group:
+        for k in range(pl.info()["n_groups"]):
+            pl.pack_reduce_unpack(group=k)
+            pl.step(0.1, 0.9, group=k)
+    else:
+        pl.pack_reduce_unpack()
+        pl.step(0.1, 0.9)
     torch.cuda.synchronize()
     for l in windows:
         for s, c in windows[l]:

@@ -1,0 +1,82 @@
+"""Static checks of the generated gfx950 code (no GPU needed): the device code is compiled to
+assembly with the library's own flags and scanned.
+
+1. fp32 arithmetic is one rounding per operation: no fused multiply-add, no packed fp32.
+2. Hazard check for the hand-written loads of the fast path.  On gfx9-class hardware an SGPR
+   written by a vector instruction (v_readfirstlane, v_readlane, a carry-out ...) must not be
+   read by a vector memory instruction within 5 wait states.  The compiler pads its own memory
+   instructions but does not look inside inline assembly, so a base pointer that reaches an
+   inline-asm global_load through v_readfirstlane without padding makes the load use a stale
+   address.  The kernels read their pointer tables with scalar loads and pad in scalar_ptr();
+   this test keeps it that way.
+"""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+from paper_1811_11141_amd import build as libbuild
+
+SRC = os.path.join(libbuild.CSRC, "kernels.hip")
+
+
+@pytest.fixture(scope="module")
+def isa_lines():
+    flags = [f for f in libbuild.FLAGS if f not in ("-shared", "-fPIC")]
+    with tempfile.TemporaryDirectory() as td:
+        out = os.path.join(td, "kernels.s")
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        res = subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", "-o", out, SRC],
+                             capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-2000:]
+        with open(out) as f:
+            lines = [l.rstrip() for l in f if l.startswith("\t") and not l.strip().startswith((";", "."))]
+    assert len(lines) > 10000
+    return lines
+
+
+def test_no_fused_or_packed_fp32(isa_lines):
+    bad = [l for l in isa_lines if re.match(r"\s*(v_fma_f32|v_fmac_f32|v_mad_f32|v_mac_f32|v_pk_(add|mul|fma)_f32)", l)]
+    assert not bad, bad[:5]
+    assert any("v_add_f32" in l for l in isa_lines) and any("v_mul_f32" in l for l in isa_lines)
+
+
+def _sgpr_dests(line):
+    mn, _, rest = line.strip().partition(" ")
+    if not mn.startswith("v_"):
+        return []
+    ops = [o.strip() for o in rest.split(",")]
+    dsts = ops[:1]
+    if "_co_" in mn or mn.startswith(("v_addc", "v_subb", "v_div_scale", "v_mad_u64", "v_mad_i64")):
+        dsts = ops[:2]
+    regs = []
+    for d in dsts:
+        m = re.match(r"s\[(\d+):(\d+)\]$", d) or re.match(r"s(\d+)$", d)
+        if m:
+            regs += list(range(int(m.group(1)), int(m.group(m.lastindex)) + 1))
+    return regs
+
+
+def test_hand_written_loads_respect_the_sgpr_hazard(isa_lines):
+    pat = re.compile(r"global_load_dwordx4 v\[\d+:\d+\], v\d+, s\[(\d+):(\d+)\].* nt")
+    checked, bad = 0, []
+    for i, l in enumerate(isa_lines):
+        m = pat.search(l)
+        if not m:
+            continue
+        checked += 1
+        base = {int(m.group(1)), int(m.group(2))}
+        waited, k = 0, i - 1
+        while waited < 5 and k >= 0:
+            p = isa_lines[k].strip()
+            if base & set(_sgpr_dests(p)):
+                bad.append((p, l.strip()))
+                break
+            nop = re.match(r"s_nop (\d+)", p)
+            waited += int(nop.group(1)) + 1 if nop else 1
+            k -= 1
+    assert checked > 1000          # the fast paths are there
+    assert not bad, bad[:5]
+    assert not any("v_readfirstlane" in l or "v_readlane" in l for l in isa_lines)

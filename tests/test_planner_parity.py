@@ -64,6 +64,46 @@ def test_optimal_equals_brute_force_other_sizes(L):
         assert pl.info()["t_iter_ms"] == op.brute_force(*args)[0]
 
 
+def test_optimal_equals_brute_force_twelve_layers():
+    """L = 12: 2048 partitions, the largest size the brute force is asked for."""
+    for seed in (1, 2, 3):
+        w = wl.tiny_workload(seed, L=12)
+        for a in (0.1, 0.5, 2.0):
+            pl = plan_for(w, mg.MODE_OPTIMAL, a=a)
+            assert pl.info()["t_iter_ms"] == op.brute_force(*oracle_args(w, a=a))[0]
+
+
+def test_plan_properties_hypothesis():
+    """Random shapes and cost constants: optimal <= rule of Theorem 1 <= WFBP, optimal <= single,
+    the returned plan costs what it claims under the oracle's evaluator, groups are contiguous."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=150, deadline=None)
+    @given(st.lists(st.tuples(st.integers(1, 10**7), st.floats(0.0, 5.0)), min_size=1, max_size=40),
+           st.floats(0.0, 3.0), st.floats(0.0, 1e-5), st.floats(0.0, 10.0))
+    def check(layers, a, b, tf):
+        p = [x[0] for x in layers]
+        tb = [x[1] for x in layers]
+        L = len(p)
+        args = (p, tb, tf, a, b)
+        res = {}
+        for mode in (mg.MODE_OPTIMAL, mg.MODE_PAPER_GREEDY, mg.MODE_WFBP, mg.MODE_SINGLE):
+            pl = mg.mgwfbp_plan(p, tb, tf, a, b, 8, mode)
+            inf = pl.info()
+            assert inf["t_iter_ms"] == op.simulate(*args, pl.merged_layers())
+            gol = inf["group_of_layer"].tolist()
+            assert gol[L - 1] == 0 and all(gol[l] - gol[l + 1] in (0, 1) for l in range(L - 1))
+            assert int(inf["group_elems"].sum()) == sum(p)
+            res[mode] = inf["t_iter_ms"]
+        tol = 1e-12 * max(1.0, res[mg.MODE_WFBP])
+        assert res[mg.MODE_OPTIMAL] <= res[mg.MODE_PAPER_GREEDY] + tol
+        assert res[mg.MODE_PAPER_GREEDY] <= res[mg.MODE_WFBP] + tol
+        assert res[mg.MODE_OPTIMAL] <= res[mg.MODE_SINGLE] + tol
+        assert mg.mgwfbp_plan(p, tb, tf, a, b, 8, mg.MODE_PAPER_GREEDY).merged_layers() == op.algorithm1(*args)
+
+    check()
+
+
 def test_every_partition_evaluates_like_the_oracle():
     w = wl.tiny_workload(5, L=6)
     args = oracle_args(w)
