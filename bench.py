@@ -194,6 +194,24 @@ def main():
             extra[variant] = {"ms_per_step": round(ms, 5),
                               "GBps_algorithmic": round(alg_bytes[variant] / (ms * 1e-3) / 1e9, 1),
                               "event_avg_us": round(kk["avg_ms"] * 1e3, 2)}
+        # the three materialised kernels one by one (actual bytes: pack 8NP, reduce 4(N+1)P, unpack 8P)
+        pl0 = sets[0]["plan"]
+        for nm, fn, nbytes in (("k_pack", lambda: pl0.pack(ws, stream=stream), 8 * N * P),
+                               ("k_reduce", lambda: pl0.reduce(ws, stream=stream), 4 * (N + 1) * P),
+                               ("k_unpack", lambda: pl0.unpack(ws, stream=stream), 8 * P)):
+            for _ in range(w2):
+                fn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
+            for a, b in evs:
+                a.record(stream)
+                fn()
+                b.record(stream)
+            torch.cuda.synchronize()
+            d = np.array([a.elapsed_time(b) for a, b in evs])
+            extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
+                         "GBps_actual": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1),
+                         "frac_of_peak": round(nbytes / (float(d.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         # plain streaming ceilings: N reads + 1 write over contiguous buffers, and a copy
         n_probe = (P + 3) // 4 * 4
         src = torch.empty(N * n_probe, dtype=torch.float32, device=dev).normal_()

@@ -172,6 +172,30 @@ int mgwfbp_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t wo
                   void *hip_stream);
 
 /*
+ * One iteration of Algorithm 2 (MG-WFBP S-SGD) on two HIP streams, driven by events.
+ *
+ * The computation thread of Algorithm 2 is played by `compute_stream`: a stand-in backward
+ * pass, one kernel per layer from layer L-1 down to layer 0 that occupies one wave for
+ * tb_ms[l] milliseconds and touches no memory.  The communication thread is played by
+ * `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
+ * mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
+ * layer has finished its backward kernel, which is the start rule of Eq. 7 / Condition 2;
+ * groups follow each other in communication order.  The call blocks until both streams are
+ * idle and reports the measured timeline, in milliseconds from the start of the backward pass:
+ *   tb_ms           host [L] or NULL (NULL = the backward times the plan was made with)
+ *   layer_ready_ms  host [L] out or NULL: when layer l's backward kernel ended (mu_b)
+ *   group_start_ms  host [n_groups] out or NULL: when group k's kernel could start (tau_c)
+ *   group_finish_ms host [n_groups] out or NULL
+ *   t_iter_ms       out or NULL: end of the last group
+ * Streams: hipStream_t handles at default priority; NULL = the default stream (using one
+ * stream for both serialises everything).  Creates and destroys HIP events internally.
+ */
+int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
+                         float momentum, void *compute_stream, void *comm_stream,
+                         double *layer_ready_ms, double *group_start_ms,
+                         double *group_finish_ms, double *t_iter_ms);
+
+/*
  * Bandwidth probes used to calibrate measurements; they are not part of the method.
  *   mgwfbp_probe_copy    dst[i] = src[i]                              (1 read + 1 write stream)
  *   mgwfbp_probe_streams dst[i] = sum_g src[g*stride_elems + i] / n   (n read + 1 write streams)

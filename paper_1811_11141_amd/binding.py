@@ -24,7 +24,8 @@ EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
     "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
-    "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy", "mgwfbp_last_error",
+    "mgwfbp_run_iteration", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
+    "mgwfbp_last_error",
 ]
 
 
@@ -58,6 +59,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_step.argtypes = [vp, i32, f32, f32, vp, sz, vp]
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
         getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
+    lib.mgwfbp_run_iteration.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(f64), P(f64), P(f64), P(f64)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_streams.argtypes = [vp, i32, u64, u64, vp, vp]
     lib.mgwfbp_plan_destroy.argtypes = [vp]
@@ -208,6 +210,22 @@ class Plan:
     def unpack(self, workspace, group: int = -1, stream=None) -> None:
         ws, nb = self._ws(workspace)
         _check(_lib.mgwfbp_unpack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def run_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
+                      lr: float = 0.0, momentum: float = 0.0) -> dict:
+        """One event-driven iteration (see mgwfbp_run_iteration); returns the measured timeline."""
+        ng = self.info()["n_groups"]
+        ready, gs, gf = np.zeros(self.L), np.zeros(ng), np.zeros(ng)
+        t_iter = C.c_double()
+        dp = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+        tb = None if tb_ms is None else np.ascontiguousarray(tb_ms, dtype=np.float64)
+        if tb is not None and tb.shape != (self.L,):
+            raise ValueError("tb_ms must have L entries")
+        _check(_lib.mgwfbp_run_iteration(self._h, None if tb is None else dp(tb), int(update), lr, momentum,
+                                         C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)),
+                                         dp(ready), dp(gs), dp(gf), C.byref(t_iter)))
+        return {"layer_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
+                "t_iter_ms": t_iter.value}
 
     def destroy(self) -> None:
         if self._h:

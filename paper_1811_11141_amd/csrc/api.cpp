@@ -129,8 +129,10 @@ int check_bound(const mgwfbp_plan_t *pl, bool need_out, bool need_wv)
     return MGWFBP_OK;
 }
 
-int run(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws, size_t bytes,
-        void *stream)
+}  // namespace
+
+int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws,
+              size_t bytes, void *stream)
 {
     int rc = check_bound(pl, !step, step);
     if (rc) return rc;
@@ -150,7 +152,6 @@ int run(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *w
     return launch_unpack(*pl, sc, w, epad, step, lr, mu, stream);
 }
 
-}  // namespace
 }  // namespace mgwfbp
 
 using namespace mgwfbp;
@@ -358,13 +359,13 @@ int mgwfbp_workspace_bytes(const mgwfbp_plan_t *pl, int32_t group, size_t *bytes
 int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace,
                               size_t workspace_bytes, void *hip_stream)
 {
-    return run(pl, group, false, 0.0f, 0.0f, workspace, workspace_bytes, hip_stream);
+    return run_scope(pl, group, false, 0.0f, 0.0f, workspace, workspace_bytes, hip_stream);
 }
 
 int mgwfbp_step(mgwfbp_plan_t *pl, int32_t group, float lr, float momentum, void *workspace,
                 size_t workspace_bytes, void *hip_stream)
 {
-    return run(pl, group, true, lr, momentum, workspace, workspace_bytes, hip_stream);
+    return run_scope(pl, group, true, lr, momentum, workspace, workspace_bytes, hip_stream);
 }
 
 int mgwfbp_pack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,

@@ -1,0 +1,151 @@
+// Event-driven MG-WFBP iteration: Algorithm 2's two threads mapped onto two HIP streams.
+//
+// Algorithm 2 runs a computation thread (backward pass, pushing each finished layer into a
+// queue) and a communication thread (popping layers into the layer buffer and all-reducing it
+// whenever a layer that is not merged arrives).  On the GPU the queue becomes a HIP event per
+// group: the backward stand-in of the group's lowest layer is followed by an event record on
+// the compute stream, and the communication stream waits for that event before it runs the
+// group's reduction.  The host enqueues everything up front and only waits at the end, so the
+// start rule of Eq. 7 (a group starts when the channel is free and its gradients exist) is
+// enforced by the hardware queues, not by host threads.
+#include <hip/hip_runtime_api.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/mgwfbp.h"
+#include "plan.hpp"
+
+using namespace mgwfbp;
+
+namespace {
+
+struct Events {
+    std::vector<hipEvent_t> ev;
+    ~Events()
+    {
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    }
+    int make(hipEvent_t *out)
+    {
+        const hipError_t e = hipEventCreate(out);
+        if (e != hipSuccess) {
+            set_error(std::string("hipEventCreate: ") + hipGetErrorString(e));
+            return MGWFBP_EHIP;
+        }
+        ev.push_back(*out);
+        return MGWFBP_OK;
+    }
+};
+
+int hip_fail(const char *what, hipError_t e)
+{
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return MGWFBP_EHIP;
+}
+
+}  // namespace
+
+extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                    float momentum, void *compute_stream, void *comm_stream,
+                                    double *layer_ready_ms, double *group_start_ms,
+                                    double *group_finish_ms, double *t_iter_ms)
+{
+    if (!pl) {
+        set_error("plan is NULL");
+        return MGWFBP_EINVAL;
+    }
+    if (!pl->bound) {
+        set_error("mgwfbp_bind has not been called");
+        return MGWFBP_ESTATE;
+    }
+    if (update ? !pl->has_wv : !pl->has_out) {
+        set_error(update ? "w[] and v[] are not bound" : "out[] is not bound");
+        return MGWFBP_ESTATE;
+    }
+    const int32_t L = pl->L;
+    const size_t G = pl->groups.size();
+    const double *tb = tb_ms ? tb_ms : pl->tb.data();
+    for (int32_t l = 0; l < L; ++l) {
+        if (!(tb[l] >= 0.0) || tb[l] > 1.0e4) {
+            set_error("tb_ms[" + std::to_string(l) + "] must be in [0, 10000] ms");
+            return MGWFBP_EINVAL;
+        }
+    }
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    hipStream_t ms = static_cast<hipStream_t>(comm_stream);
+
+    Events pool;
+    hipEvent_t base;
+    std::vector<hipEvent_t> layer_done(L), g_start(G), g_finish(G);
+    int rc = pool.make(&base);
+    for (int32_t l = 0; l < L && !rc; ++l) rc = pool.make(&layer_done[l]);
+    for (size_t k = 0; k < G && !rc; ++k) {
+        rc = pool.make(&g_start[k]);
+        if (!rc) rc = pool.make(&g_finish[k]);
+    }
+    if (rc) return rc;
+
+    // a zero-length stand-in first: the first launch of a kernel loads its code, which would
+    // otherwise show up as a gap at the start of the measured timeline
+    if ((rc = launch_spin(0.0, cs))) return rc;
+    // the communication stream must not start before the backward pass does
+    hipError_t e = hipEventRecord(base, cs);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    if ((e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+
+    for (int32_t l = L - 1; l >= 0; --l) {
+        if ((rc = launch_spin(tb[l], cs))) break;
+        if ((e = hipEventRecord(layer_done[l], cs)) != hipSuccess) {
+            rc = hip_fail("hipEventRecord", e);
+            break;
+        }
+        if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
+        // layer l is the lowest layer of its group: the group's gradients are complete
+        const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
+        if ((e = hipStreamWaitEvent(ms, layer_done[l], 0)) != hipSuccess) {
+            rc = hip_fail("hipStreamWaitEvent", e);
+            break;
+        }
+        if ((e = hipEventRecord(g_start[k], ms)) != hipSuccess) {
+            rc = hip_fail("hipEventRecord", e);
+            break;
+        }
+        if ((rc = run_scope(pl, static_cast<int32_t>(k), update != 0, lr, momentum, nullptr, 0, ms)))
+            break;
+        if ((e = hipEventRecord(g_finish[k], ms)) != hipSuccess) {
+            rc = hip_fail("hipEventRecord", e);
+            break;
+        }
+    }
+    // whatever was enqueued must drain before the events are destroyed or read
+    const hipError_t e1 = hipStreamSynchronize(cs);
+    const hipError_t e2 = hipStreamSynchronize(ms);
+    if (rc) return rc;
+    if (e1 != hipSuccess) return hip_fail("hipStreamSynchronize(compute)", e1);
+    if (e2 != hipSuccess) return hip_fail("hipStreamSynchronize(comm)", e2);
+
+    auto since_base = [&](hipEvent_t ev, double *out) -> int {
+        float t = 0.0f;
+        const hipError_t er = hipEventElapsedTime(&t, base, ev);
+        if (er != hipSuccess) return hip_fail("hipEventElapsedTime", er);
+        *out = static_cast<double>(t);
+        return MGWFBP_OK;
+    };
+    double last = 0.0;
+    for (int32_t l = 0; l < L; ++l) {
+        double t;
+        if ((rc = since_base(layer_done[l], &t))) return rc;
+        if (layer_ready_ms) layer_ready_ms[l] = t;
+    }
+    for (size_t k = 0; k < G; ++k) {
+        double ts, tf;
+        if ((rc = since_base(g_start[k], &ts))) return rc;
+        if ((rc = since_base(g_finish[k], &tf))) return rc;
+        if (group_start_ms) group_start_ms[k] = ts;
+        if (group_finish_ms) group_finish_ms[k] = tf;
+        if (tf > last) last = tf;
+    }
+    if (t_iter_ms) *t_iter_ms = last;
+    return MGWFBP_OK;
+}

@@ -609,6 +609,20 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
 }
 
 // ------------------------------------------------------------------------------------------
+// Stand-in for one layer's backward computation: one wave that waits until `ticks` of the
+// constant-rate real-time counter have passed.  It touches no memory.  The loop ends when the
+// counter has advanced far enough; the iteration cap is a second, independent exit.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls)
+{
+    const uint64_t t0 = __builtin_amdgcn_s_memrealtime();
+    for (uint64_t i = 0; i < max_polls; ++i) {
+        if (__builtin_amdgcn_s_memrealtime() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(32);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Bandwidth probes
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kProbeTile = 8192;
@@ -793,6 +807,26 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
         });
     }
     return check_launch("unpack kernel launch");
+}
+
+int launch_spin(double ms, void *stream)
+{
+    // s_memrealtime counts at a constant 100 MHz on this family; ask the runtime to be sure
+    static int khz = 0;
+    if (khz == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeWallClockRate, dev) == hipSuccess && v > 0)
+            khz = v;
+        else
+            khz = 100000;
+    }
+    if (!(ms > 0.0)) ms = 0.0;
+    const uint64_t ticks = static_cast<uint64_t>(ms * khz);
+    // one poll takes at least ~2048 clocks of sleep (~1 us); cap generously at 50x the target
+    const uint64_t max_polls = 1000 + static_cast<uint64_t>(ms * 1000.0 * 50.0);
+    k_spin<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(ticks, max_polls);
+    return check_launch("backward stand-in launch");
 }
 
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream)

@@ -111,6 +111,10 @@ void plan_optimal(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged);
 void plan_paper_greedy(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged);
 void finish_plan(mgwfbp_plan_t &pl);
 
+// api.cpp
+int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws,
+              size_t bytes, void *stream);
+
 // tables.cpp
 void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
                   float *const *w, float *const *v, std::vector<const float *> &src_tbl,
@@ -132,6 +136,7 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
                   void *stream);
 int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
                   bool step, float lr, float mu, void *stream);
+int launch_spin(double ms, void *stream);
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
 int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
                          float *dst, void *stream);

@@ -1,0 +1,79 @@
+"""Event-driven iteration (Algorithm 2 on two HIP streams): results equal the oracle's, and the
+measured timeline obeys the start rule of Eq. 7 / Condition 2."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import datapath as od
+from oracle import planner as op
+from paper_1811_11141_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mg():
+    assert torch.cuda.is_available()
+    from paper_1811_11141_amd import binding
+    return binding
+
+
+def to_np(ts):
+    return [t.detach().cpu().numpy().copy() for t in ts]
+
+
+@pytest.mark.parametrize("seed,update", [(0, False), (1, True), (2, True)])
+def test_iteration_results_and_timeline(mg, seed, update):
+    w = wl.tiny_workload(seed)
+    tb = w.tb_ms * 0.5                      # 0.05 .. 1 ms per layer keeps the test short
+    pl = mg.mgwfbp_plan(w.p, tb, 0.0, 0.2, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    grads = wl.make_gradients(w, seed, "cuda")
+    out = [torch.zeros_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, seed, "cuda")
+    g_np, w_np, v_np = [to_np(r) for r in grads], to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    s_comp, s_comm = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    tl = pl.run_iteration(s_comp, s_comm, update=update, lr=0.1, momentum=0.9)
+    groups = pl.groups()
+    # results
+    if update:
+        od.merged_gradient_path(g_np, groups, w_np, v_np, lr=0.1, mu=0.9)
+        for l in range(w.L):
+            assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32))
+            assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32))
+    exp = od.merged_gradient_path(g_np, groups)
+    for l in range(w.L):
+        assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
+    # timeline: backward stand-ins take about t_b each (Eq. 6)
+    ready, gs, gf = tl["layer_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
+    mu_b = np.array(op.backward_finish(tb.tolist(), 0.0))
+    assert np.all(ready >= mu_b - 1e-3)                       # never early
+    assert np.all(ready <= mu_b * 1.10 + 0.15)                # launch gaps only
+    eps = 0.02
+    for k, grp in enumerate(groups):
+        lowest = grp[-1]
+        assert gs[k] >= ready[lowest] - eps                   # gradients exist (Condition 2)
+        if k:
+            assert gs[k] >= gf[k - 1] - eps                   # channel free (Eq. 7)
+        assert gf[k] >= gs[k]
+    assert tl["t_iter_ms"] == pytest.approx(gf.max())
+    # the reductions overlap the backward pass: every group but the last ends before the
+    # backward pass does
+    assert np.all(gf[:-1] <= ready[0] + eps) or len(groups) == 1
+
+
+def test_iteration_needs_binding(mg):
+    w = wl.custom_workload([100, 200], 2)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, 0.5, 1e-6, 2, mg.MODE_WFBP)
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream())
+    assert ei.value.code == mg.ESTATE
+    grads = wl.make_gradients(w, 1, "cuda")
+    pl.bind(grads, [torch.empty_like(t) for t in grads[0]])
+    with pytest.raises(mg.MgwfbpError):
+        pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream(), update=True)     # no w, v
+    with pytest.raises(mg.MgwfbpError):
+        pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream(), tb_ms=[-1.0, 1.0])
+    tl = pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream(), tb_ms=[0.05, 0.05])
+    assert tl["t_iter_ms"] > 0.09
