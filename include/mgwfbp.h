@@ -172,18 +172,39 @@ int mgwfbp_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t wo
                   void *hip_stream);
 
 /*
+ * Fit the all-reduce cost model T_ar(M) = a + b*M (Eq. 9) to measured (message size, time)
+ * pairs by ordinary least squares, the way Section V-A obtains a and b from benchmarks.
+ *   n            number of measurements (>= 2, with at least two distinct sizes)
+ *   bytes, ms    host [n]
+ *   a_ms, b_ms_per_byte   out.  The fitted intercept is clamped at 0 (a negative start-up time
+ *                has no meaning in the model); the slope is then refitted through the origin.
+ */
+int mgwfbp_fit_cost(int32_t n, const double *bytes, const double *ms, double *a_ms,
+                    double *b_ms_per_byte);
+
+/*
+ * (a, b) of Table II for an all-reduce algorithm on N workers:
+ *   algorithm  0 binary tree, 1 recursive doubling, 2 recursive halving and doubling, 3 ring
+ *   alpha_ms, beta_ms_per_byte, gamma_ms_per_byte   latency, per-byte transfer, per-byte sum
+ */
+int mgwfbp_table2_cost(int32_t algorithm, int32_t N, double alpha_ms, double beta_ms_per_byte,
+                       double gamma_ms_per_byte, double *a_ms, double *b_ms_per_byte);
+
+/*
  * One iteration of Algorithm 2 (MG-WFBP S-SGD) on two HIP streams, driven by events.
  *
  * The computation thread of Algorithm 2 is played by `compute_stream`: a stand-in backward
- * pass, one kernel per layer from layer L-1 down to layer 0 that occupies one wave for
- * tb_ms[l] milliseconds and touches no memory.  The communication thread is played by
+ * pass from layer L-1 down to layer 0, one kernel per group that occupies one wave for the
+ * sum of its layers' tb_ms and touches no memory (only the moment a group's lowest layer is
+ * done matters to the communication side).  The communication thread is played by
  * `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
  * mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
  * layer has finished its backward kernel, which is the start rule of Eq. 7 / Condition 2;
  * groups follow each other in communication order.  The call blocks until both streams are
  * idle and reports the measured timeline, in milliseconds from the start of the backward pass:
  *   tb_ms           host [L] or NULL (NULL = the backward times the plan was made with)
- *   layer_ready_ms  host [L] out or NULL: when layer l's backward kernel ended (mu_b)
+ *   group_ready_ms  host [n_groups] out or NULL: when the backward pass of group k's lowest
+ *                   layer ended (mu_b of that layer)
  *   group_start_ms  host [n_groups] out or NULL: when group k's kernel could start (tau_c)
  *   group_finish_ms host [n_groups] out or NULL
  *   t_iter_ms       out or NULL: end of the last group
@@ -192,7 +213,7 @@ int mgwfbp_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t wo
  */
 int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                          float momentum, void *compute_stream, void *comm_stream,
-                         double *layer_ready_ms, double *group_start_ms,
+                         double *group_ready_ms, double *group_start_ms,
                          double *group_finish_ms, double *t_iter_ms);
 
 /*

@@ -186,3 +186,22 @@ def table2_cost(algorithm: str, n: int, alpha: float, beta: float, gamma: float
     if algorithm == "ring":
         return 2 * (n - 1) * alpha, 2 * (n - 1) / n * beta + (n - 1) / n * gamma
     raise ValueError(algorithm)
+
+
+# ---- fitting Eq. 9 to measurements (Section V-A) ---------------------------------------------
+
+def fit_cost(nbytes: Sequence[float], ms: Sequence[float]) -> Tuple[float, float]:
+    """Ordinary least squares of ms = a + b*bytes via the normal equations.
+
+    A negative intercept is clamped to 0 and the slope refitted through the origin.
+    """
+    n = len(nbytes)
+    sx, sy = sum(nbytes), sum(ms)
+    sxx = sum(x * x for x in nbytes)
+    sxy = sum(x * y for x, y in zip(nbytes, ms))
+    det = n * sxx - sx * sx
+    b = (n * sxy - sx * sy) / det
+    a = (sy - b * sx) / n
+    if a < 0:
+        a, b = 0.0, sxy / sxx
+    return a, max(b, 0.0)

@@ -24,7 +24,7 @@ EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
     "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
-    "mgwfbp_run_iteration", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
+    "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
 
@@ -60,6 +60,8 @@ def _load() -> C.CDLL:
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
         getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
     lib.mgwfbp_run_iteration.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(f64), P(f64), P(f64), P(f64)]
+    lib.mgwfbp_fit_cost.argtypes = [i32, P(f64), P(f64), P(f64), P(f64)]
+    lib.mgwfbp_table2_cost.argtypes = [i32, i32, f64, f64, f64, P(f64), P(f64)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_streams.argtypes = [vp, i32, u64, u64, vp, vp]
     lib.mgwfbp_plan_destroy.argtypes = [vp]
@@ -215,7 +217,7 @@ class Plan:
                       lr: float = 0.0, momentum: float = 0.0) -> dict:
         """One event-driven iteration (see mgwfbp_run_iteration); returns the measured timeline."""
         ng = self.info()["n_groups"]
-        ready, gs, gf = np.zeros(self.L), np.zeros(ng), np.zeros(ng)
+        ready, gs, gf = np.zeros(ng), np.zeros(ng), np.zeros(ng)
         t_iter = C.c_double()
         dp = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
         tb = None if tb_ms is None else np.ascontiguousarray(tb_ms, dtype=np.float64)
@@ -224,7 +226,7 @@ class Plan:
         _check(_lib.mgwfbp_run_iteration(self._h, None if tb is None else dp(tb), int(update), lr, momentum,
                                          C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)),
                                          dp(ready), dp(gs), dp(gf), C.byref(t_iter)))
-        return {"layer_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
+        return {"group_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
                 "t_iter_ms": t_iter.value}
 
     def destroy(self) -> None:
@@ -280,6 +282,27 @@ def mgwfbp_pack_reduce_unpack(plan: Plan, group: int = -1, workspace=None, strea
 def mgwfbp_step(plan: Plan, lr: float, momentum: float, group: int = -1, workspace=None,
                 stream=None) -> None:
     plan.step(lr, momentum, group, workspace, stream)
+
+
+TABLE2 = {"binary_tree": 0, "recursive_doubling": 1, "recursive_halving_doubling": 2, "ring": 3}
+
+
+def mgwfbp_fit_cost(nbytes, ms):
+    """Least-squares (a_ms, b_ms_per_byte) of T_ar(M) = a + b*M."""
+    x = np.ascontiguousarray(nbytes, dtype=np.float64)
+    y = np.ascontiguousarray(ms, dtype=np.float64)
+    if x.shape != y.shape or x.ndim != 1:
+        raise ValueError("nbytes and ms must be 1-D arrays of the same length")
+    a, b = C.c_double(), C.c_double()
+    dp = lambda v: v.ctypes.data_as(C.POINTER(C.c_double))
+    _check(_lib.mgwfbp_fit_cost(len(x), dp(x), dp(y), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def mgwfbp_table2_cost(algorithm: str, N: int, alpha_ms: float, beta: float, gamma: float):
+    a, b = C.c_double(), C.c_double()
+    _check(_lib.mgwfbp_table2_cost(TABLE2[algorithm], N, alpha_ms, beta, gamma, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def mgwfbp_probe_copy(src, dst, n_elems: int, stream=None) -> None:

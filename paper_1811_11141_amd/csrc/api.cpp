@@ -420,6 +420,57 @@ int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_el
     return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
 }
 
+int mgwfbp_fit_cost(int32_t n, const double *bytes, const double *ms, double *a_ms,
+                    double *b_ms_per_byte)
+{
+    if (!bytes || !ms || !a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
+    if (n < 2) return fail(MGWFBP_EINVAL, "need at least two measurements");
+    double sx = 0, sy = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (!std::isfinite(bytes[i]) || !std::isfinite(ms[i]) || bytes[i] < 0)
+            return fail(MGWFBP_EINVAL, "measurements must be finite, sizes >= 0");
+        sx += bytes[i];
+        sy += ms[i];
+    }
+    const double mx = sx / n, my = sy / n;
+    double sxx = 0, sxy = 0, sxx0 = 0, sxy0 = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        sxx += (bytes[i] - mx) * (bytes[i] - mx);
+        sxy += (bytes[i] - mx) * (ms[i] - my);
+        sxx0 += bytes[i] * bytes[i];
+        sxy0 += bytes[i] * ms[i];
+    }
+    if (!(sxx > 0)) return fail(MGWFBP_EINVAL, "need at least two distinct message sizes");
+    double b = sxy / sxx;
+    double a = my - b * mx;
+    if (a < 0) {  // refit through the origin
+        a = 0;
+        b = sxy0 / sxx0;
+    }
+    if (b < 0) b = 0;
+    *a_ms = a;
+    *b_ms_per_byte = b;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_table2_cost(int32_t algorithm, int32_t N, double alpha, double beta, double gamma,
+                       double *a_ms, double *b_ms_per_byte)
+{
+    if (!a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
+    if (N < 1) return fail(MGWFBP_EINVAL, "N must be >= 1");
+    if (!good_time(alpha) || !good_time(beta) || !good_time(gamma))
+        return fail(MGWFBP_EINVAL, "alpha, beta, gamma must be finite and >= 0");
+    const double n = static_cast<double>(N), lg = std::log2(n);
+    switch (algorithm) {
+    case 0: *a_ms = 2 * alpha * lg; *b_ms_per_byte = (2 * beta + gamma) * lg; break;
+    case 1: *a_ms = alpha * lg; *b_ms_per_byte = (beta + gamma) * lg; break;
+    case 2: *a_ms = 2 * alpha * lg; *b_ms_per_byte = 2 * beta - (2 * beta + gamma) / n + gamma; break;
+    case 3: *a_ms = 2 * (n - 1) * alpha; *b_ms_per_byte = 2 * (n - 1) / n * beta + (n - 1) / n * gamma; break;
+    default: return fail(MGWFBP_EINVAL, "algorithm must be 0..3");
+    }
+    return MGWFBP_OK;
+}
+
 void mgwfbp_plan_destroy(mgwfbp_plan_t *pl)
 {
     if (!pl) return;

@@ -48,7 +48,7 @@ int hip_fail(const char *what, hipError_t e)
 
 extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
                                     float momentum, void *compute_stream, void *comm_stream,
-                                    double *layer_ready_ms, double *group_start_ms,
+                                    double *group_ready_ms, double *group_start_ms,
                                     double *group_finish_ms, double *t_iter_ms)
 {
     if (!pl) {
@@ -77,33 +77,43 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
 
     Events pool;
     hipEvent_t base;
-    std::vector<hipEvent_t> layer_done(L), g_start(G), g_finish(G);
+    std::vector<hipEvent_t> g_ready(G), g_start(G), g_finish(G);
     int rc = pool.make(&base);
-    for (int32_t l = 0; l < L && !rc; ++l) rc = pool.make(&layer_done[l]);
     for (size_t k = 0; k < G && !rc; ++k) {
-        rc = pool.make(&g_start[k]);
+        rc = pool.make(&g_ready[k]);
+        if (!rc) rc = pool.make(&g_start[k]);
         if (!rc) rc = pool.make(&g_finish[k]);
     }
     if (rc) return rc;
 
-    // a zero-length stand-in first: the first launch of a kernel loads its code, which would
-    // otherwise show up as a gap at the start of the measured timeline
+    // A zero-length stand-in first: the first launch of a kernel loads its code.  Then a gate:
+    // the host needs tens of microseconds per group to enqueue kernels, event records and
+    // waits, far more than a short group takes to run, so without a head start the measured
+    // timeline would show the host's enqueue rate.  The gate keeps the compute stream busy
+    // while everything behind it is being queued; time zero is the end of the gate.
     if ((rc = launch_spin(0.0, cs))) return rc;
+    if ((rc = launch_spin(1.0 + 0.06 * static_cast<double>(G), cs))) return rc;
     // the communication stream must not start before the backward pass does
     hipError_t e = hipEventRecord(base, cs);
     if (e != hipSuccess) return hip_fail("hipEventRecord", e);
     if ((e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
 
+    // Backward pass, highest layer first.  Only the moment a group's lowest layer finishes
+    // matters to the communication side, so the layers of a group share one stand-in kernel
+    // whose duration is the sum of their backward times.
+    double pending_ms = 0.0;
     for (int32_t l = L - 1; l >= 0; --l) {
-        if ((rc = launch_spin(tb[l], cs))) break;
-        if ((e = hipEventRecord(layer_done[l], cs)) != hipSuccess) {
-            rc = hip_fail("hipEventRecord", e);
-            break;
-        }
+        pending_ms += tb[l];
         if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
         // layer l is the lowest layer of its group: the group's gradients are complete
         const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
-        if ((e = hipStreamWaitEvent(ms, layer_done[l], 0)) != hipSuccess) {
+        if ((rc = launch_spin(pending_ms, cs))) break;
+        pending_ms = 0.0;
+        if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) {
+            rc = hip_fail("hipEventRecord", e);
+            break;
+        }
+        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess) {
             rc = hip_fail("hipStreamWaitEvent", e);
             break;
         }
@@ -133,13 +143,10 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
         return MGWFBP_OK;
     };
     double last = 0.0;
-    for (int32_t l = 0; l < L; ++l) {
-        double t;
-        if ((rc = since_base(layer_done[l], &t))) return rc;
-        if (layer_ready_ms) layer_ready_ms[l] = t;
-    }
     for (size_t k = 0; k < G; ++k) {
-        double ts, tf;
+        double tr, ts, tf;
+        if ((rc = since_base(g_ready[k], &tr))) return rc;
+        if (group_ready_ms) group_ready_ms[k] = tr;
         if ((rc = since_base(g_start[k], &ts))) return rc;
         if ((rc = since_base(g_finish[k], &tf))) return rc;
         if (group_start_ms) group_start_ms[k] = ts;

@@ -1,0 +1,156 @@
+"""Measurements around the hot path: cost-model calibration and the event-driven schedule.
+
+    python -m paper_1811_11141_amd.experiments --workload resnet50
+
+1. Calibration (what Section V-A does for the network): time every group of a plan alone,
+   as a function of its message size M = 4 * (parameters in the group), and fit
+   T(M) = a + b*M by least squares (mgwfbp_fit_cost).  Here the "all-reduce" of a group is the
+   fused N-way reduction kernel on this GPU, so a is the cost of one launch and 1/b the
+   effective reduction rate per message byte.
+2. Schedule: plan with the fitted (a, b), run one event-driven iteration (mgwfbp_run_iteration,
+   Algorithm 2 on two streams with timed stand-ins for the backward pass) for the no-merging,
+   single-group, Theorem-1 and optimal plans, and compare the measured end of the last group
+   with the iteration time the model predicts (Eq. 8).
+
+Only argument marshalling and timing happen here; all device work is in the library.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+
+import numpy as np
+
+
+def _bound_plans(mg, wl, w, mode, a, b, tb, n_sets, dev, seed=7):
+    import torch
+
+    plans = []
+    for s in range(n_sets):
+        grads = wl.make_gradients(w, seed + s, dev)
+        out = [torch.empty_like(t) for t in grads[0]]
+        pl = mg.mgwfbp_plan(w.p, tb, 0.0, a, b, w.n_workers, mode)
+        pl.bind(grads, out)
+        plans.append(pl)
+    return plans
+
+
+def measure_group_times(plans, stream, reps: int = 30, warmup: int = 3):
+    """Average time of each group's fused launch, rotating over the bound plans (one per
+    independently allocated gradient set) so that repeats do not hit in cache.
+    Returns (message bytes per group, milliseconds per group)."""
+    import torch
+
+    info = plans[0].info()
+    ng = info["n_groups"]
+    nbytes = info["group_elems"].astype(np.float64) * 4.0
+    ms = np.zeros(ng)
+    for k in range(ng):
+        for i in range(warmup):
+            plans[i % len(plans)].pack_reduce_unpack(group=k, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(reps):
+            plans[i % len(plans)].pack_reduce_unpack(group=k, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms[k] = e0.elapsed_time(e1) / reps
+    return nbytes, ms
+
+
+def calibrate(workload: str = "resnet50", n_sets: int = 3, device: str = "cuda:0"):
+    """Fit (a_ms, b_ms_per_byte) from the per-layer groups of the no-merging plan."""
+    import torch
+
+    from . import binding as mg
+    from . import workloads as wl
+
+    w = wl.cnn_workload(workload)
+    plans = _bound_plans(mg, wl, w, mg.MODE_WFBP, w.a_ms, w.b_ms_per_byte, w.tb_ms, n_sets, device)
+    stream = torch.cuda.Stream(device=device)
+    nbytes, ms = measure_group_times(plans, stream)
+    a, b = mg.mgwfbp_fit_cost(nbytes, ms)
+    resid = ms - (a + b * nbytes)
+    big = np.argsort(nbytes)[-4:]
+    return {"a_ms": a, "b_ms_per_byte": b, "samples": int(len(ms)),
+            "largest_messages": [[float(nbytes[i]), float(ms[i])] for i in big],
+            "bytes_min": float(nbytes.min()), "bytes_max": float(nbytes.max()),
+            "rms_residual_ms": float(np.sqrt(np.mean(resid ** 2))),
+            "max_residual_ms": float(np.abs(resid).max())}
+
+
+def calibrate_in_schedule(workload: str = "resnet50", device: str = "cuda:0", reps: int = 5):
+    """Fit (a, b) from the event-driven schedule itself: with zero backward time the groups of
+    the no-merging plan run back to back on the communication stream, and the interval between
+    the ends of consecutive groups is the whole per-message cost of this transport (kernel,
+    launch, event record and wait), which is what Eq. 9 models."""
+    import torch
+
+    from . import binding as mg
+    from . import workloads as wl
+
+    w = wl.cnn_workload(workload)
+    pl = _bound_plans(mg, wl, w, mg.MODE_WFBP, w.a_ms, w.b_ms_per_byte, w.tb_ms, 1, device)[0]
+    s_comp, s_comm = torch.cuda.Stream(device=device), torch.cuda.Stream(device=device)
+    zeros = np.zeros(w.L)
+    pl.run_iteration(s_comp, s_comm, tb_ms=zeros)
+    inter = []
+    for _ in range(reps):
+        t = pl.run_iteration(s_comp, s_comm, tb_ms=zeros)
+        gf = t["group_finish_ms"]
+        inter.append(np.diff(gf))
+    inter = np.median(np.array(inter), axis=0)
+    nbytes = pl.info()["group_elems"].astype(np.float64)[1:] * 4.0
+    a, b = mg.mgwfbp_fit_cost(nbytes, inter)
+    resid = inter - (a + b * nbytes)
+    pl.destroy()
+    return {"a_ms": a, "b_ms_per_byte": b, "samples": int(len(inter)),
+            "rms_residual_ms": float(np.sqrt(np.mean(resid ** 2)))}
+
+
+def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: float = 5.0,
+             device: str = "cuda:0", reps: int = 5):
+    """Predicted (Eq. 8 with the given a, b) and measured iteration times of four plans.
+
+    The backward times are the workload's FLOP-proportional t_b rescaled to sum to
+    `backward_ms`, so that the reductions matter next to the backward pass."""
+    import torch
+
+    from . import binding as mg
+    from . import workloads as wl
+
+    w = wl.cnn_workload(workload)
+    tb = w.tb_ms * (backward_ms / w.tb_ms.sum())
+    s_comp, s_comm = torch.cuda.Stream(device=device), torch.cuda.Stream(device=device)
+    out = {"workload": workload, "a_ms": a_ms, "b_ms_per_byte": b_ms_per_byte,
+           "backward_ms": backward_ms, "plans": {}}
+    for name, mode in (("wfbp", mg.MODE_WFBP), ("single", mg.MODE_SINGLE),
+                       ("theorem1", mg.MODE_PAPER_GREEDY), ("optimal", mg.MODE_OPTIMAL)):
+        pl = _bound_plans(mg, wl, w, mode, a_ms, b_ms_per_byte, tb, 1, device)[0]
+        pl.run_iteration(s_comp, s_comm)                      # warm-up
+        t = [pl.run_iteration(s_comp, s_comm) for _ in range(reps)]
+        meas = np.array([x["t_iter_ms"] for x in t])
+        bwd = np.array([x["group_ready_ms"][-1] for x in t])
+        inf = pl.info()
+        out["plans"][name] = {"groups": inf["n_groups"], "predicted_t_iter_ms": inf["t_iter_ms"],
+                              "measured_t_iter_ms": float(np.median(meas)),
+                              "measured_backward_ms": float(np.median(bwd)),
+                              "not_overlapped_ms": float(np.median(meas - bwd))}
+        pl.destroy()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "googlenet", "alexnet", "vgg16"])
+    ap.add_argument("--backward-ms", type=float, nargs="+", default=[5.0, 1.0])
+    args = ap.parse_args()
+    cal = calibrate(args.workload)
+    cal2 = calibrate_in_schedule(args.workload)
+    sched = [schedule(args.workload, cal2["a_ms"], cal2["b_ms_per_byte"], t) for t in args.backward_ms]
+    print(json.dumps({"calibration_back_to_back": cal, "calibration_in_schedule": cal2, "schedule": sched}))
+
+
+if __name__ == "__main__":
+    main()

@@ -46,21 +46,21 @@ def test_iteration_results_and_timeline(mg, seed, update):
     for l in range(w.L):
         assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
     # timeline: backward stand-ins take about t_b each (Eq. 6)
-    ready, gs, gf = tl["layer_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
+    ready, gs, gf = tl["group_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
     mu_b = np.array(op.backward_finish(tb.tolist(), 0.0))
-    assert np.all(ready >= mu_b - 1e-3)                       # never early
-    assert np.all(ready <= mu_b * 1.10 + 0.15)                # launch gaps only
+    mu_low = np.array([mu_b[grp[-1]] for grp in groups])      # mu_b of each group's lowest layer
+    assert np.all(ready >= mu_low - 1e-3)                     # never early
+    assert np.all(ready <= mu_low * 1.10 + 0.15)              # launch gaps only
     eps = 0.02
     for k, grp in enumerate(groups):
-        lowest = grp[-1]
-        assert gs[k] >= ready[lowest] - eps                   # gradients exist (Condition 2)
+        assert gs[k] >= ready[k] - eps                        # gradients exist (Condition 2)
         if k:
             assert gs[k] >= gf[k - 1] - eps                   # channel free (Eq. 7)
         assert gf[k] >= gs[k]
     assert tl["t_iter_ms"] == pytest.approx(gf.max())
     # the reductions overlap the backward pass: every group but the last ends before the
     # backward pass does
-    assert np.all(gf[:-1] <= ready[0] + eps) or len(groups) == 1
+    assert np.all(gf[:-1] <= ready[-1] + eps) or len(groups) == 1
 
 
 def test_iteration_needs_binding(mg):
@@ -77,3 +77,21 @@ def test_iteration_needs_binding(mg):
         pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream(), tb_ms=[-1.0, 1.0])
     tl = pl.run_iteration(torch.cuda.Stream(), torch.cuda.Stream(), tb_ms=[0.05, 0.05])
     assert tl["t_iter_ms"] > 0.09
+
+
+def test_calibrated_schedule_ranks_plans_like_the_model(mg):
+    """Fit (a, b) on this machine from the schedule itself, then run the four plans with a short
+    backward pass: no merging must be the slowest by far, and the model must rank the optimal
+    plan first, as measured."""
+    from paper_1811_11141_amd import experiments as ex
+
+    cal = ex.calibrate_in_schedule("googlenet", reps=3)
+    assert 1e-3 < cal["a_ms"] < 0.2 and 0 < cal["b_ms_per_byte"] < 1e-7
+    res = ex.schedule("googlenet", cal["a_ms"], cal["b_ms_per_byte"], backward_ms=0.3, reps=3)["plans"]
+    assert res["optimal"]["predicted_t_iter_ms"] <= res["theorem1"]["predicted_t_iter_ms"] + 1e-12
+    assert res["optimal"]["predicted_t_iter_ms"] <= res["wfbp"]["predicted_t_iter_ms"] + 1e-12
+    assert res["wfbp"]["measured_t_iter_ms"] > 2.0 * res["optimal"]["measured_t_iter_ms"]
+    assert res["optimal"]["measured_t_iter_ms"] <= 1.15 * min(res["single"]["measured_t_iter_ms"],
+                                                              res["theorem1"]["measured_t_iter_ms"])
+    # the model tracks the measurement for the communication-bound plan
+    assert res["wfbp"]["measured_t_iter_ms"] == pytest.approx(res["wfbp"]["predicted_t_iter_ms"], rel=0.2)

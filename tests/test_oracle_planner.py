@@ -259,3 +259,19 @@ def test_groups_from_merged():
     assert op.groups_from_merged(5, [5, 3, 2]) == [[5, 4], [3, 2, 1]]
     assert op.groups_from_merged(3, []) == [[3], [2], [1]]
     assert op.groups_from_merged(1, []) == [[1]]
+
+
+def test_fit_cost_pins(golden):
+    """The two printed points of Section I determine the line exactly; noisy data agree with
+    numpy's polynomial fit; a negative intercept is clamped."""
+    ex = golden["allreduce_example"]
+    a, b = op.fit_cost(ex["bytes"], ex["ms"])
+    assert a == pytest.approx(ex["implied_a_ms"], rel=1e-9) and b == pytest.approx(ex["implied_b_ms_per_byte"], rel=1e-9)
+    rng = np.random.default_rng(30)
+    x = rng.uniform(1e3, 1e8, size=50)
+    y = 0.37 + 2.5e-7 * x + rng.normal(0, 0.01, size=50)
+    a, b = op.fit_cost(x.tolist(), y.tolist())
+    b_np, a_np = np.polyfit(x, y, 1)
+    assert a == pytest.approx(a_np, rel=1e-6) and b == pytest.approx(b_np, rel=1e-6)
+    a, b = op.fit_cost([1e6, 2e6, 3e6], [0.9, 2.1, 3.0])
+    assert a == 0.0 and b == pytest.approx(np.sum(np.array([1e6, 2e6, 3e6]) * [0.9, 2.1, 3.0]) / np.sum(np.square([1e6, 2e6, 3e6])))

@@ -26,7 +26,7 @@ def oracle_args(w, a=None, b=None, tf=0.0):
 
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "mgwfbp.h")).read()
-    declared = set(re.findall(r"\b(mgwfbp_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(mgwfbp_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(mg.EXPORTS)
     lib = C.CDLL(mg.LIB_PATH)
     for name in declared:
@@ -222,3 +222,27 @@ def test_error_paths():
     assert lib.mgwfbp_plan_explicit(3, p, tb, 0.0, 0.5, 1e-6, 4, merged, C.byref(h2)) == mg.EINVAL
     lib.mgwfbp_plan_destroy(h)
     lib.mgwfbp_plan_destroy(None)
+
+
+def test_fit_cost_and_table2_match_oracle(golden):
+    ex = golden["allreduce_example"]
+    a, b = mg.mgwfbp_fit_cost(ex["bytes"], ex["ms"])
+    assert a == pytest.approx(1.2, rel=1e-9) and b == pytest.approx(1.5e-6, rel=1e-9)
+    rng = np.random.default_rng(31)
+    for _ in range(20):
+        n = int(rng.integers(2, 40))
+        x = rng.uniform(1e2, 1e9, size=n)
+        y = rng.uniform(0, 2) + rng.uniform(1e-9, 1e-5) * x + rng.normal(0, 0.02, size=n)
+        a_o, b_o = op.fit_cost(x.tolist(), y.tolist())
+        a_l, b_l = mg.mgwfbp_fit_cost(x, y)
+        assert a_l == pytest.approx(a_o, rel=1e-7, abs=1e-9) and b_l == pytest.approx(b_o, rel=1e-7)
+    with pytest.raises(mg.MgwfbpError):
+        mg.mgwfbp_fit_cost([5.0, 5.0], [1.0, 2.0])
+    for name in mg.TABLE2:
+        for n in (2, 4, 8, 64):
+            a_l, b_l = mg.mgwfbp_table2_cost(name, n, 0.04526, 8e-7, 1e-8)
+            a_o, b_o = op.table2_cost(name, n, 0.04526, 8e-7, 1e-8)
+            assert a_l == pytest.approx(a_o, rel=1e-12) and b_l == pytest.approx(b_o, rel=1e-12)
+    rs = golden["ring_startup"]
+    for n, us in zip(rs["nodes"], rs["startup_us"]):
+        assert mg.mgwfbp_table2_cost("ring", n, rs["alpha_us"], 0.0, 0.0)[0] == pytest.approx(us, abs=5e-3)
