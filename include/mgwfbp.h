@@ -191,6 +191,20 @@ int mgwfbp_table2_cost(int32_t algorithm, int32_t N, double alpha_ms, double bet
                        double gamma_ms_per_byte, double *a_ms, double *b_ms_per_byte);
 
 /*
+ * Predicted weak-scaling curve (the trace-based simulation of Section V-C): for each worker
+ * count the all-reduce cost (a, b) follows Table II, the layers are planned in `mode`, and the
+ * iteration time follows Eq. 8.  Speedup over one worker is Eq. 4: N * (t_f + t_b) / t_iter.
+ *   tb_ms, tf_ms   the per-layer backward trace and forward time of ONE worker (host [L])
+ *   algorithm      Table II row, as for mgwfbp_table2_cost
+ *   n_workers      host [n_points] worker counts (each >= 1)
+ *   t_iter_ms, speedup   host [n_points] out, either may be NULL
+ */
+int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                         int32_t algorithm, double alpha_ms, double beta_ms_per_byte,
+                         double gamma_ms_per_byte, int32_t n_points, const int32_t *n_workers,
+                         int32_t mode, double *t_iter_ms, double *speedup);
+
+/*
  * One iteration of Algorithm 2 (MG-WFBP S-SGD) on two HIP streams, driven by events.
  *
  * The computation thread of Algorithm 2 is played by `compute_stream`: a stand-in backward

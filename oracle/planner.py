@@ -205,3 +205,10 @@ def fit_cost(nbytes: Sequence[float], ms: Sequence[float]) -> Tuple[float, float
     if a < 0:
         a, b = 0.0, sxy / sxx
     return a, max(b, 0.0)
+
+
+# ---- weak-scaling speedup (Eq. 4-5) and the trace-based simulation of Section V-C ------------
+
+def speedup(n: int, tf: float, tb_total: float, t_iter: float) -> float:
+    """Eq. 4: throughput of N workers over one worker = N (t_f + t_b) / t_iter."""
+    return n * (tf + tb_total) / t_iter

@@ -24,7 +24,7 @@ EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
     "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
-    "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
+    "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
 
@@ -62,6 +62,8 @@ def _load() -> C.CDLL:
     lib.mgwfbp_run_iteration.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(f64), P(f64), P(f64), P(f64)]
     lib.mgwfbp_fit_cost.argtypes = [i32, P(f64), P(f64), P(f64), P(f64)]
     lib.mgwfbp_table2_cost.argtypes = [i32, i32, f64, f64, f64, P(f64), P(f64)]
+    lib.mgwfbp_scaling_curve.argtypes = [i32, P(u64), P(f64), f64, i32, f64, f64, f64, i32, P(i32), i32,
+                                         P(f64), P(f64)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_streams.argtypes = [vp, i32, u64, u64, vp, vp]
     lib.mgwfbp_plan_destroy.argtypes = [vp]
@@ -303,6 +305,19 @@ def mgwfbp_table2_cost(algorithm: str, N: int, alpha_ms: float, beta: float, gam
     a, b = C.c_double(), C.c_double()
     _check(_lib.mgwfbp_table2_cost(TABLE2[algorithm], N, alpha_ms, beta, gamma, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def mgwfbp_scaling_curve(p, tb_ms, tf_ms: float, algorithm: str, alpha_ms: float, beta: float,
+                         gamma: float, n_workers: Sequence[int], mode: int = MODE_OPTIMAL):
+    """(t_iter_ms[], speedup[]) predicted for each worker count."""
+    p_arr, tb = _plan_args(p, tb_ms)
+    nw = np.ascontiguousarray(n_workers, dtype=np.int32)
+    t, s = np.zeros(len(nw)), np.zeros(len(nw))
+    dp = lambda v: v.ctypes.data_as(C.POINTER(C.c_double))
+    _check(_lib.mgwfbp_scaling_curve(len(p_arr), p_arr.ctypes.data_as(C.POINTER(C.c_uint64)), dp(tb), tf_ms,
+                                     TABLE2[algorithm], alpha_ms, beta, gamma, len(nw),
+                                     nw.ctypes.data_as(C.POINTER(C.c_int32)), mode, dp(t), dp(s)))
+    return t, s
 
 
 def mgwfbp_probe_copy(src, dst, n_elems: int, stream=None) -> None:

@@ -471,6 +471,28 @@ int mgwfbp_table2_cost(int32_t algorithm, int32_t N, double alpha, double beta, 
     return MGWFBP_OK;
 }
 
+int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                         int32_t algorithm, double alpha_ms, double beta, double gamma,
+                         int32_t n_points, const int32_t *n_workers, int32_t mode,
+                         double *t_iter_ms, double *speedup)
+{
+    if (n_points < 0 || (n_points > 0 && !n_workers)) return fail(MGWFBP_EINVAL, "bad n_points / n_workers");
+    for (int32_t i = 0; i < n_points; ++i) {
+        double a = 0, b = 0;
+        int rc = mgwfbp_table2_cost(algorithm, n_workers[i], alpha_ms, beta, gamma, &a, &b);
+        if (rc) return rc;
+        mgwfbp_plan_t *pl = nullptr;
+        if ((rc = mgwfbp_plan(L, p_elems, tb_ms, tf_ms, a, b, n_workers[i], mode, &pl))) return rc;
+        const double t = pl->t_iter;
+        double compute = tf_ms;  // t_f + t_b of one worker
+        for (int32_t l = 0; l < L; ++l) compute += tb_ms[l];
+        mgwfbp_plan_destroy(pl);
+        if (t_iter_ms) t_iter_ms[i] = t;
+        if (speedup) speedup[i] = t > 0 ? static_cast<double>(n_workers[i]) * compute / t : 0.0;
+    }
+    return MGWFBP_OK;
+}
+
 void mgwfbp_plan_destroy(mgwfbp_plan_t *pl)
 {
     if (!pl) return;

@@ -275,3 +275,10 @@ def test_fit_cost_pins(golden):
     assert a == pytest.approx(a_np, rel=1e-6) and b == pytest.approx(b_np, rel=1e-6)
     a, b = op.fit_cost([1e6, 2e6, 3e6], [0.9, 2.1, 3.0])
     assert a == 0.0 and b == pytest.approx(np.sum(np.array([1e6, 2e6, 3e6]) * [0.9, 2.1, 3.0]) / np.sum(np.square([1e6, 2e6, 3e6])))
+
+
+def test_speedup_eq4_eq5():
+    """Eq. 5: S(N) = N / (1 + r), r = t_c / (t_f + t_b) for the naive scheme of Eq. 3."""
+    tf, tb, tc = 1.5, 6.5, 2.0
+    assert op.speedup(8, tf, tb, tf + tb + tc) == pytest.approx(8 / (1 + tc / (tf + tb)), rel=1e-12)
+    assert op.speedup(16, tf, tb, tf + tb) == 16.0

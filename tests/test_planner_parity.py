@@ -246,3 +246,41 @@ def test_fit_cost_and_table2_match_oracle(golden):
     rs = golden["ring_startup"]
     for n, us in zip(rs["nodes"], rs["startup_us"]):
         assert mg.mgwfbp_table2_cost("ring", n, rs["alpha_us"], 0.0, 0.0)[0] == pytest.approx(us, abs=5e-3)
+
+
+def test_scaling_curve_matches_oracle():
+    """Section V-C style simulation on the ResNet-50 / GoogLeNet shaped traces, 10GbE constants of
+    Section V-A (alpha = 45.26 us, 10 Gb/s): the library's curve equals the oracle's plan-by-plan
+    evaluation, merging never loses to either baseline, and no latency and infinite bandwidth
+    give linear speedup."""
+    alpha, beta, gamma = 0.04526, 8e-7, 0.0
+    nodes = [1, 2, 4, 8, 16, 32, 64]
+    for name in ("resnet50", "googlenet"):
+        w = wl.cnn_workload(name)
+        p, tb = w.p.tolist(), w.tb_ms.tolist()
+        tf = 0.5 * sum(tb)
+        curves = {}
+        for label, mode in (("wfbp", mg.MODE_WFBP), ("single", mg.MODE_SINGLE),
+                            ("theorem1", mg.MODE_PAPER_GREEDY), ("optimal", mg.MODE_OPTIMAL)):
+            t, s = mg.mgwfbp_scaling_curve(w.p, w.tb_ms, tf, "ring", alpha, beta, gamma, nodes, mode)
+            curves[label] = (t, s)
+            for i, n in enumerate(nodes):
+                a, b = op.table2_cost("ring", n, alpha, beta, gamma)
+                if label == "wfbp":
+                    m = []
+                elif label == "single":
+                    m = range(2, w.L + 1)
+                elif label == "theorem1":
+                    m = op.algorithm1(p, tb, tf, a, b)
+                else:
+                    m = mg.mgwfbp_plan(w.p, w.tb_ms, tf, a, b, n, mg.MODE_OPTIMAL).merged_layers()
+                t_o = op.simulate(p, tb, tf, a, b, m)
+                assert t[i] == pytest.approx(t_o, rel=1e-12)
+                assert s[i] == pytest.approx(op.speedup(n, tf, sum(tb), t_o), rel=1e-12)
+        for i in range(len(nodes)):
+            assert curves["optimal"][1][i] >= curves["wfbp"][1][i] * (1 - 1e-12)
+            assert curves["optimal"][1][i] >= curves["single"][1][i] * (1 - 1e-12)
+            assert curves["optimal"][1][i] >= curves["theorem1"][1][i] * (1 - 1e-12)
+        assert curves["optimal"][1][0] == pytest.approx(1.0, rel=1e-12)      # one worker: a = b = 0
+        _, s_free = mg.mgwfbp_scaling_curve(w.p, w.tb_ms, tf, "ring", 0.0, 0.0, 0.0, nodes, mg.MODE_OPTIMAL)
+        assert np.allclose(s_free, nodes, rtol=1e-12)
