@@ -212,6 +212,27 @@ def main():
             extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
                          "GBps_actual": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(nbytes / (float(d.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # the two halves a transport calls: sources -> merged buffer (N+1 units), merged buffer ->
+        # out (2 units) or -> w, v, out (6 units); rotating over the gradient sets
+        mb = torch.empty((P + 63) // 64 * 64, dtype=torch.float32, device=dev)
+        for nm, fn, nbytes in (
+                ("pack_reduce", lambda i: sets[i % n_sets]["plan"].pack_reduce(mb, stream=stream), 4 * (N + 1) * P),
+                ("unpack_only", lambda i: sets[i % n_sets]["plan"].unpack_update(mb, stream=stream), 8 * P),
+                ("unpack_update", lambda i: sets[i % n_sets]["plan"].unpack_update(mb, update=True, lr=0.1, momentum=0.9, stream=stream), 24 * P)):
+            for i in range(w2):
+                fn(i)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
+            for i in range(k2):
+                evs[i][0].record(stream)
+                fn(i)
+                evs[i][1].record(stream)
+            torch.cuda.synchronize()
+            d = np.array([a.elapsed_time(b) for a, b in evs])
+            extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
+                         "GBps_actual": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1),
+                         "frac_of_peak": round(nbytes / (float(d.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del mb
         # plain streaming ceilings: N reads + 1 write over contiguous buffers, and a copy
         n_probe = (P + 3) // 4 * 4
         src = torch.empty(N * n_probe, dtype=torch.float32, device=dev).normal_()

@@ -172,6 +172,26 @@ int mgwfbp_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t wo
                   void *hip_stream);
 
 /*
+ * The two halves of the path as a real transport would call them (Algorithm 2 with the
+ * all-reduce in between): N + 1 and 2 (5 with the update) units of traffic instead of the
+ * 3N + 3 of the three materialised steps.
+ *   mgwfbp_pack_reduce    reads the N workers' layers of the group and writes the group's
+ *                         merged buffer already reduced: merged[j] = (1/N) sum_g x_g[j], packed
+ *                         in arrival order without padding (this GPU's share of the all-reduce
+ *                         arithmetic applied to the layer buffer).
+ *   mgwfbp_unpack_update  scatters a merged buffer back to out[] (update = 0) or applies
+ *                         v = momentum*v + merged; w = w - lr*v on w[], v[] and also writes
+ *                         out[] when bound (update != 0).
+ *   merged  device pointer, 256-byte aligned, at least 4 * (elements of the group, or of the
+ *           whole plan for group = -1) bytes.
+ */
+int mgwfbp_pack_reduce(mgwfbp_plan_t *plan, int32_t group, void *merged, size_t merged_bytes,
+                       void *hip_stream);
+int mgwfbp_unpack_update(mgwfbp_plan_t *plan, int32_t group, const void *merged,
+                         size_t merged_bytes, int32_t update, float lr, float momentum,
+                         void *hip_stream);
+
+/*
  * Fit the all-reduce cost model T_ar(M) = a + b*M (Eq. 9) to measured (message size, time)
  * pairs by ordinary least squares, the way Section V-A obtains a and b from benchmarks.
  *   n            number of measurements (>= 2, with at least two distinct sizes)

@@ -24,6 +24,7 @@ EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
     "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
+    "mgwfbp_pack_reduce", "mgwfbp_unpack_update",
     "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
@@ -60,6 +61,8 @@ def _load() -> C.CDLL:
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
         getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
     lib.mgwfbp_run_iteration.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(f64), P(f64), P(f64), P(f64)]
+    lib.mgwfbp_pack_reduce.argtypes = [vp, i32, vp, sz, vp]
+    lib.mgwfbp_unpack_update.argtypes = [vp, i32, vp, sz, i32, f32, f32, vp]
     lib.mgwfbp_fit_cost.argtypes = [i32, P(f64), P(f64), P(f64), P(f64)]
     lib.mgwfbp_table2_cost.argtypes = [i32, i32, f64, f64, f64, P(f64), P(f64)]
     lib.mgwfbp_scaling_curve.argtypes = [i32, P(u64), P(f64), f64, i32, f64, f64, f64, i32, P(i32), i32,
@@ -214,6 +217,16 @@ class Plan:
     def unpack(self, workspace, group: int = -1, stream=None) -> None:
         ws, nb = self._ws(workspace)
         _check(_lib.mgwfbp_unpack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def pack_reduce(self, merged, group: int = -1, stream=None) -> None:
+        ws, nb = self._ws(merged)
+        _check(_lib.mgwfbp_pack_reduce(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def unpack_update(self, merged, group: int = -1, update: bool = False, lr: float = 0.0,
+                      momentum: float = 0.0, stream=None) -> None:
+        ws, nb = self._ws(merged)
+        _check(_lib.mgwfbp_unpack_update(self._h, group, ws, nb, int(update), lr, momentum,
+                                         C.c_void_p(_stream(stream))))
 
     def run_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
                       lr: float = 0.0, momentum: float = 0.0) -> dict:

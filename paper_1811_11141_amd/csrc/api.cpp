@@ -149,7 +149,7 @@ int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, v
     const uint64_t epad = padded(sc.elems);
     if ((rc = launch_pack(*pl, sc, w, epad, stream))) return rc;
     if ((rc = launch_reduce(*pl, sc, w, epad, stream))) return rc;
-    return launch_unpack(*pl, sc, w, epad, step, lr, mu, stream);
+    return launch_unpack(*pl, sc, w + static_cast<uint64_t>(pl->N) * epad, step, lr, mu, stream);
 }
 
 }  // namespace mgwfbp
@@ -398,8 +398,43 @@ int mgwfbp_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t work
     LaunchScope sc{};
     if ((rc = scope_of(pl, group, sc))) return rc;
     if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
-    return launch_unpack(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), false, 0.0f,
-                         0.0f, hip_stream);
+    const float *reduced = static_cast<float *>(workspace) + static_cast<uint64_t>(pl->N) * padded(sc.elems);
+    return launch_unpack(*pl, sc, reduced, false, 0.0f, 0.0f, hip_stream);
+}
+
+namespace {
+int check_merged(const LaunchScope &sc, void *merged, size_t bytes)
+{
+    if (!merged) return fail(MGWFBP_EINVAL, "merged is NULL");
+    if (reinterpret_cast<uintptr_t>(merged) & 255u) return fail(MGWFBP_EINVAL, "merged must be 256-byte aligned");
+    if (bytes < sc.elems * sizeof(float))
+        return fail(MGWFBP_EINVAL, "merged buffer too small: need " + std::to_string(sc.elems * sizeof(float)) + " bytes");
+    return MGWFBP_OK;
+}
+}  // namespace
+
+int mgwfbp_pack_reduce(mgwfbp_plan_t *pl, int32_t group, void *merged, size_t merged_bytes,
+                       void *hip_stream)
+{
+    int rc = check_bound(pl, false, false);
+    if (rc) return rc;
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = check_merged(sc, merged, merged_bytes))) return rc;
+    return launch_fused(*pl, sc, false, 0.0f, 0.0f, hip_stream, static_cast<float *>(merged));
+}
+
+int mgwfbp_unpack_update(mgwfbp_plan_t *pl, int32_t group, const void *merged, size_t merged_bytes,
+                         int32_t update, float lr, float momentum, void *hip_stream)
+{
+    int rc = check_bound(pl, !update, update != 0);
+    if (rc) return rc;
+    if (update && (!std::isfinite(lr) || !std::isfinite(momentum)))
+        return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = check_merged(sc, const_cast<void *>(merged), merged_bytes))) return rc;
+    return launch_unpack(*pl, sc, static_cast<const float *>(merged), update != 0, lr, momentum, hip_stream);
 }
 
 int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream)

@@ -387,20 +387,32 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
 // misaligned tensors, gather tiles, run-time N) takes the general path below.
 template <int NW, int U, bool STEP, bool NT, int D>
 __global__ void __launch_bounds__(kBlock)
-k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace)
+k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace,
+        float *merged_out, uint64_t base_off)
 {
+    // merged_out != nullptr: the averaged values go to a merged buffer (the layer buffer of
+    // Algorithm 2, already reduced) at their packed position instead of the per-layer out[].
     __shared__ uint32_t s_rel[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
         const uint32_t flags = table_load(&dt.segs[tl.seg].flags);
         const float *const *sp_tbl = dt.src + static_cast<size_t>(tl.seg) * nw;
-        float *outp = dt.out ? table_load(dt.out + tl.seg) + tl.start : nullptr;
+        float *outp;
+        uint32_t need = SEG_SRC_ALIGNED | SEG_WV_ALIGNED;
+        bool merged_al = true;
+        if (!STEP && merged_out) {  // the update never targets a merged buffer
+            const uint64_t moff = table_load(&dt.segs[tl.seg].plan_off) - base_off + tl.start;
+            outp = merged_out + moff;
+            merged_al = !(moff & 3);
+        } else {
+            outp = dt.out ? table_load(dt.out + tl.seg) + tl.start : nullptr;
+            need |= SEG_OUT_ALIGNED;
+        }
         float *wp = STEP ? table_load(dt.w + tl.seg) + tl.start : nullptr;
         float *vp = STEP ? table_load(dt.v + tl.seg) + tl.start : nullptr;
         const uint32_t n = tl.n;
-        const bool vec = (flags & (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
-                         (SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
+        const bool vec = (flags & need) == need && merged_al;
         if constexpr (NW > 0 && U > 0) {
             if (vec && n == U * kBlock * 4) {
                 const uint64_t start = tl.start;
@@ -449,8 +461,11 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
             const uint32_t i = k - s_rel[s];
             const float *const *sp_tbl = dt.src + static_cast<size_t>(si) * nw;
             const float avg = nway_mean_dyn<NT, float>([sp_tbl](int g) { return sp_tbl[g]; }, nw, i, inv_n);
-            finish<STEP, NT, float>(avg, dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
-                                    STEP ? dt.v[si] : nullptr, i, lr, mu);
+            if (!STEP && merged_out)  // a gather tile is one contiguous run of the merged buffer
+                st<NT>(merged_out + (tl.start - base_off) + k, avg);
+            else
+                finish<STEP, NT, float>(avg, dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
+                                        STEP ? dt.v[si] : nullptr, i, lr, mu);
         }
     }
 }
@@ -665,10 +680,11 @@ int check_launch(const char *what)
 // deep = launch too small to fill the chip (latency-bound): 8 loads in flight per wave.
 template <int NW, bool STEP, bool NT>
 void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
-                    int nw, float inv_n, float lr, float mu, int pace)
+                    int nw, float inv_n, float lr, float mu, int pace, float *merged_out,
+                    uint64_t base_off)
 {
 #define MGWFBP_LAUNCH(UU, DD)                                                                  \
-    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace)
+    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off)
     if constexpr (NW > 0 && NT) {
         if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
@@ -680,15 +696,16 @@ void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTabl
 
 template <bool STEP, bool NT>
 void fused_dispatch(int nw, int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt,
-                    uint32_t tb, float inv_n, float lr, float mu, int pace)
+                    uint32_t tb, float inv_n, float lr, float mu, int pace, float *merged_out,
+                    uint64_t base_off)
 {
     switch (nw) {
-    case 1: fused_launch_u<1, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 2: fused_launch_u<2, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 4: fused_launch_u<4, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 8: fused_launch_u<8, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    case 16: fused_launch_u<16, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
-    default: fused_launch_u<0, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace); break;
+    case 1: fused_launch_u<1, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 2: fused_launch_u<2, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 4: fused_launch_u<4, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 8: fused_launch_u<8, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 16: fused_launch_u<16, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    default: fused_launch_u<0, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
     }
 }
 
@@ -721,8 +738,9 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
 }  // namespace
 
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
-                 void *stream)
+                 void *stream, float *merged_out)
 {
+    const uint64_t base_off = sc.base_off;
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(sc.n_tiles);
@@ -733,11 +751,11 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     // the launch cannot saturate HBM with one load per wave and is bound by latency instead
     const bool deep = sc.n_tiles < 2048;
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
-        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
+        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
-        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace);
+        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
+        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
     }
     return check_launch("fused kernel launch");
 }
@@ -785,14 +803,13 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
     return check_launch("reduce kernel launch");
 }
 
-int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
-                  bool step, float lr, float mu, void *stream)
+int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *reduced, bool step,
+                  float lr, float mu, void *stream)
 {
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(sc.n_tiles);
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    const float *reduced = ws + static_cast<uint64_t>(pl.N) * epad;
     const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));
     const bool deep = sc.n_tiles < 2048;
     const int pace = pl.opt.pace;

@@ -129,13 +129,13 @@ struct LaunchScope {
     bool needs_lds;
 };
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
-                 void *stream);
+                 void *stream, float *merged_out = nullptr);
 int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
                 void *stream);
 int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
                   void *stream);
-int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
-                  bool step, float lr, float mu, void *stream);
+int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *reduced, bool step,
+                  float lr, float mu, void *stream);
 int launch_spin(double ms, void *stream);
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
 int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,

@@ -389,6 +389,149 @@ def test_workspace_errors(mg):
     assert ei.value.code == mg.ESTATE
 
 
+# ---- the two halves a transport would call (merged buffer in between) ----------------------
+
+def merged_buffer(n_elems, slack=64):
+    """NaN-filled so that untouched elements show; `slack` elements beyond the end must stay."""
+    return torch.full((n_elems + slack,), float("nan"), dtype=torch.float32, device="cuda")
+
+
+@pytest.mark.parametrize("seed,tile,small,n_workers", [
+    (0, 1024, 512, 4), (1, 2048, 0, 3), (2, 4096, 512, 8), (3, 8192, 2048, 16), (4, 4096, 512, 1)])
+def test_pack_reduce_then_unpack_update(mg, seed, tile, small, n_workers):
+    """pack_reduce writes (1/N) sum_g pack(x_g) into the merged buffer (oracle: pack every worker,
+    then reduce the packed buffers); unpack_update scatters such a buffer, or applies the update
+    from it (oracle: unpack, then the update layer by layer).  Every group and the whole plan;
+    arbitrary sizes, so most packed offsets are not multiples of four elements."""
+    w = wl.tiny_workload(200 + seed, n_workers=n_workers)
+    rng = np.random.default_rng(seed)
+    merged = random_merged(rng, w.L)
+    groups = groups0(w.L, merged)
+    pl = make_plan(mg, w, merged, tile=tile, small=small)
+    grads = wl.make_gradients(w, seed, "cuda")
+    g_np = [to_np(r) for r in grads]
+    out = [torch.zeros_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, seed, "cuda")
+    pl.bind(grads, out, wt, vt)
+    scopes = [(-1, [l for g in groups for l in g])] + [(k, g) for k, g in enumerate(groups)]
+    for scope, layers in scopes:
+        E = sum(int(w.p[l]) for l in layers)
+        mb = merged_buffer(E)
+        pl.pack_reduce(mb, group=scope)
+        torch.cuda.synchronize()
+        exp = od.reduce([od.pack(g_np[g], layers) for g in range(n_workers)])
+        host = mb.cpu().numpy()
+        assert_same(host[:E], exp, f"pack_reduce scope {scope}")
+        assert np.isnan(host[E:]).all(), "wrote past the end of the merged buffer"
+        # scatter only
+        for t in out:
+            t.fill_(float("nan"))
+        pl.unpack_update(mb, group=scope)
+        torch.cuda.synchronize()
+        exp_out = [np.full(int(n), np.nan, dtype=np.float32) for n in w.p]
+        od.unpack(exp, exp_out, layers)
+        for l in range(w.L):
+            assert_same(out[l].cpu().numpy(), exp_out[l], f"unpack scope {scope} layer {l}")
+        # update from the merged buffer
+        w_np, v_np = to_np(wt), to_np(vt)
+        for l in layers:
+            od.sgd(w_np[l], v_np[l], exp_out[l], 0.05, 0.9)
+        pl.unpack_update(mb, group=scope, update=True, lr=0.05, momentum=0.9)
+        torch.cuda.synchronize()
+        for l in range(w.L):
+            assert_same(wt[l].cpu().numpy(), w_np[l], f"w scope {scope} layer {l}")
+            assert_same(vt[l].cpu().numpy(), v_np[l], f"v scope {scope} layer {l}")
+
+
+def test_unpack_update_scatter_is_a_bit_copy(mg):
+    w = wl.tiny_workload(7)
+    merged = [l for l in range(2, w.L + 1) if l % 3]
+    groups = groups0(w.L, merged)
+    pl = make_plan(mg, w, merged, tile=1024, small=512)
+    grads = wl.make_gradients(w, 7, "cuda")
+    out = [torch.zeros_like(t) for t in grads[0]]
+    pl.bind(grads, out)
+    layers = [l for g in groups for l in g]
+    src = np.random.default_rng(11).integers(0, 2 ** 32, size=w.P, dtype=np.uint64).astype(np.uint32)
+    mb = torch.from_numpy(src.view(np.float32).copy()).cuda()
+    pl.unpack_update(mb)
+    torch.cuda.synchronize()
+    exp_out = [np.zeros(int(n), dtype=np.uint32) for n in w.p]
+    od.unpack(src, exp_out, layers)
+    for l in range(w.L):
+        assert np.array_equal(bits(out[l].cpu().numpy()), exp_out[l]), f"layer {l}"
+
+
+def test_merged_buffer_errors(mg):
+    w = wl.custom_workload([100, 200], 2)
+    pl = make_plan(mg, w, [2])
+    grads = wl.make_gradients(w, 1, "cuda")
+    pl.bind(grads, [torch.empty_like(t) for t in grads[0]])
+    mb = torch.empty(300 + 64, device="cuda")
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.pack_reduce(mb[:299])
+    assert ei.value.code == mg.EINVAL and "too small" in str(ei.value)
+    with pytest.raises(mg.MgwfbpError):
+        pl.pack_reduce(mb[1:])                           # not 256-byte aligned
+    with pytest.raises(mg.MgwfbpError):
+        pl.pack_reduce(mb, group=1)                      # the plan has one group
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.unpack_update(mb, update=True, lr=0.1, momentum=0.9)   # w, v not bound
+    assert ei.value.code == mg.ESTATE
+    pl.pack_reduce(mb)
+    pl.unpack_update(mb)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,per_group", [("resnet50", False), ("resnet50", True), ("vgg16", False)])
+def test_full_size_two_halves_sampled(mg, name, per_group):
+    """Full-size sets through pack_reduce and unpack_update (the update from the merged buffer),
+    in the launch configuration bench.py times; the oracle recomputes sampled windows."""
+    w = wl.cnn_workload(name)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    groups = pl.groups()
+    grads = wl.make_gradients(w, wl.BASE_SEED + 1, "cuda")
+    wt, vt = wl.make_weights(w, wl.BASE_SEED + 1, "cuda")
+    rng = np.random.default_rng(5)
+    windows = {l: window_starts(int(n), rng, 8200) for l, n in enumerate(w.p)}
+    w0 = {(l, s): wt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
+    v0 = {(l, s): vt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
+    pl.bind(grads, None, wt, vt)
+    plan_off, off = {}, 0
+    if per_group:
+        for k, g in enumerate(groups):         # one merged buffer per group, as Algorithm 2 has
+            sub = merged_buffer(sum(int(w.p[l]) for l in g))
+            pl.pack_reduce(sub, group=k)
+            pl.unpack_update(sub, group=k, update=True, lr=0.1, momentum=0.9)
+            o = 0
+            for l in g:
+                plan_off[l] = (sub, o)
+                o += int(w.p[l])
+            assert o + 64 == sub.numel()
+        torch.cuda.synchronize()
+    else:
+        mb = merged_buffer(w.P)
+        pl.pack_reduce(mb)
+        pl.unpack_update(mb, update=True, lr=0.1, momentum=0.9)
+        torch.cuda.synchronize()
+        for g in groups:
+            for l in g:
+                plan_off[l] = (mb, off)
+                off += int(w.p[l])
+        assert off == w.P
+        assert bool(torch.isnan(mb[w.P:]).all()) and bool(torch.isfinite(mb[:w.P]).all())
+    for l in windows:
+        buf, o = plan_off[l]
+        for s, c in windows[l]:
+            xs = [grads[g][l][s:s + c].cpu().numpy().copy() for g in range(w.n_workers)]
+            avg = od.reduce(xs)
+            assert_same(buf[o + s:o + s + c].cpu().numpy(), avg, f"{name} merged layer {l} window {s}")
+            ww, vv = w0[(l, s)], v0[(l, s)]
+            od.sgd(ww, vv, avg, 0.1, 0.9)
+            assert_same(wt[l][s:s + c].cpu().numpy(), ww, f"{name} w layer {l} window {s}")
+            assert_same(vt[l][s:s + c].cpu().numpy(), vv, f"{name} v layer {l} window {s}")
+
+
 # ---- full-size gradient sets ---------------------------------------------------------------
 
 def window_starts(n, rng, width):
