@@ -82,11 +82,11 @@ def main():
     alg_bytes = {"fused": 4 * (N + 1) * P, "per_group": 4 * (N + 1) * P,
                  "materialised": 4 * (N + 1) * P, "step": 4 * (N + 5) * P}
     set_bytes = 4 * (N + 1) * P
-    n_sets = args.sets if args.sets > 0 else max(2, min(4, int(np.ceil(768e6 / set_bytes)) + 1))
+    n_sets = args.sets if args.sets > 0 else max(3, min(4, int(np.ceil(768e6 / set_bytes)) + 1))
     if args.workload == "vgg16":
         n_sets = args.sets if args.sets > 0 else 1  # 9.4 GB per pass evicts itself
 
-    def new_plan():
+    def new_plan(mode=mode):
         pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, N, mode)
         if args.tile:
             pl.set_option(mg.OPT_TILE_ELEMS, args.tile)
@@ -194,6 +194,28 @@ def main():
             extra[variant] = {"ms_per_step": round(ms, 5),
                               "GBps_algorithmic": round(alg_bytes[variant] / (ms * 1e-3) / 1e9, 1),
                               "event_avg_us": round(kk["avg_ms"] * 1e3, 2)}
+        # the two extreme plans (every tensor its own group / one group) through the same fused
+        # launch: the rate should not depend on the plan
+        for nm, md in (("fused_plan_wfbp", mg.MODE_WFBP), ("fused_plan_single", mg.MODE_SINGLE)):
+            alt = []
+            for st in sets:
+                pa = new_plan(md)
+                pa.bind(st["grads"], st["out"], st["w"], st["v"])
+                alt.append(pa)
+            for i in range(w2):
+                alt[i % n_sets].pack_reduce_unpack(stream=stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(k2):
+                alt[i % n_sets].pack_reduce_unpack(stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / k2
+            extra[nm] = {"groups": alt[0].info()["n_groups"], "us_per_step": round(us, 2),
+                         "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
+            for pa in alt:
+                pa.destroy()
         # the three materialised kernels one by one (actual bytes: pack 8NP, reduce 4(N+1)P, unpack 8P)
         pl0 = sets[0]["plan"]
         for nm, fn, nbytes in (("k_pack", lambda: pl0.pack(ws, stream=stream), 8 * N * P),

@@ -217,19 +217,34 @@ __device__ __forceinline__ void lds_to_global(const float *lds, float *dst, uint
 // a tile to the top, ~270 registers, one wave per SIMD).  Such a load is invisible to the
 // compiler's own wait-count bookkeeping, so its result is passed through wait_all_loads()
 // before the first use.
+template <int OFF>
 __device__ __forceinline__ v4f ld_stream(const char *base, uint32_t voff)
 {
     v4f r;
-    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(r) : "v"(voff), "s"(base));
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(r) : "v"(voff), "s"(base), "n"(OFF));
     return r;
 }
 
 // Same load, ordered after the computation of `dep` (an in/out operand that is not touched).
+template <int OFF>
 __device__ __forceinline__ v4f ld_stream_after(const char *base, uint32_t voff, v4f &dep)
 {
     v4f r;
-    asm volatile("global_load_dwordx4 %0, %2, %3 nt" : "=v"(r), "+v"(dep) : "v"(voff), "s"(base));
+    asm volatile("global_load_dwordx4 %0, %2, %3 offset:%4 nt"
+                 : "=v"(r), "+v"(dep)
+                 : "v"(voff), "s"(base), "n"(OFF));
     return r;
+}
+
+// 128-bit streaming store in the same addressing form (the compiler, left to choose, builds a
+// 64-bit address per lane and per piece: two registers and two additions each).
+template <int OFF>
+__device__ __forceinline__ void st_stream(char *base, uint32_t voff, const v4f &x)
+{
+    asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3 nt"
+                 :
+                 : "v"(voff), "v"(x), "s"(base), "n"(OFF)
+                 : "memory");
 }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a
@@ -255,11 +270,6 @@ __device__ __forceinline__ void wait_loads(v4f &x)
 }
 
 __device__ __forceinline__ void wait_all_loads(v4f &x) { wait_loads<0>(x); }
-
-__device__ __forceinline__ void st_stream(char *base, uint32_t voff, v4f x)
-{
-    __builtin_nontemporal_store(x, (MGWFBP_GLOBAL v4f *)(base + voff));
-}
 
 // A uniform pointer moved into scalar registers whatever the compiler thought of it.
 // An SGPR written by a vector instruction (v_readfirstlane) must not be read by a vector
@@ -298,29 +308,38 @@ __device__ __forceinline__ void pace_wave(int pace)
 // src(g) yields worker g's tile base pointer (uniform over the workgroup).  SCALE = false
 // skips the multiplication by 1/N: with NW = 1 the tile is then moved bit for bit, which is
 // what pack and unpack need.
+#ifndef MGWFBP_STEP_BATCH
+#define MGWFBP_STEP_BATCH 4
+#endif
+
 template <int NW, int U, bool STEP, int D, bool SCALE, class SrcFn>
 __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, float *vp,
                                           float inv_n, float lr, float mu, int pace)
 {
-    uint32_t vo[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) vo[u] = threadIdx.x * 16u + u * (kBlock * 16u);
+    // Lane offset of piece 0 (+BIAS); piece u sits u KiB further on, which the load and store
+    // instructions add as their immediate offset (13 bits, signed: -4096 .. 4095), so one
+    // register addresses the whole tile.  Each wave walks its own contiguous U KiB.
+    constexpr int BIAS = U * 1024 > 4096 ? 4096 : 0;
+    static_assert(U * 1024 - 1024 - BIAS <= 4095 && -BIAS >= -4096, "piece offsets must fit the immediate");
+    const uint32_t vo = (threadIdx.x >> 6) * (U * 1024u) + (threadIdx.x & 63u) * 16u + BIAS;
+#define MGWFBP_OFF(u) ((u) * 1024 - BIAS)
     v4f res[U];
     if constexpr (D == 1) {
-#pragma unroll
-        for (int g = 0; g < NW; ++g) {
+        static_for<NW>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
             const char *sb = scalar_ptr(src(g));
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
                 // the load is ordered after the previous add through its operand res[..]
-                v4f x = (g == 0 && u == 0) ? ld_stream(sb, vo[u])
-                                           : ld_stream_after(sb, vo[u], res[u == 0 ? U - 1 : u - 1]);
+                v4f x;
+                if constexpr (g == 0 && u == 0) x = ld_stream<MGWFBP_OFF(u)>(sb, vo);
+                else x = ld_stream_after<MGWFBP_OFF(u)>(sb, vo, res[u == 0 ? U - 1 : u - 1]);
                 wait_all_loads(x);
-                if (g == 0) res[u] = x;
+                if constexpr (g == 0) res[u] = x;
                 else res[u] = res[u] + x;
                 pace_wave(pace);
-            }
-        }
+            });
+        });
     } else {
         // Launches too small to fill the chip are bound by latency, not bandwidth: keep D
         // loads in flight through a register ring (same visiting and summation order).
@@ -332,7 +351,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
         v4f x[DD];
         static_for<DD>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            x[j] = ld_stream(sb[j / U], vo[j % U]);
+            x[j] = ld_stream<MGWFBP_OFF(j % U)>(sb[j / U], vo);
         });
         static_for<T>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -344,7 +363,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             // the next load re-uses the slot just consumed; naming res[u] as an operand keeps
             // the add above ahead of it, so no more than DD loaded values are ever live
             if constexpr (j + DD < T)
-                x[j % DD] = ld_stream_after(sb[(j + DD) / U], vo[(j + DD) % U], res[u]);
+                x[j % DD] = ld_stream_after<MGWFBP_OFF((j + DD) % U)>(sb[(j + DD) / U], vo, res[u]);
         });
     }
     if constexpr (SCALE) {
@@ -355,32 +374,35 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
         // weights and momentum: read a batch, update, write the batch
         const char *wb = scalar_ptr(wp);
         const char *vb = scalar_ptr(vp);
-        constexpr int UB = U < 2 ? U : 2;  // float4 of w and of v held at once
-#pragma unroll
-        for (int u0 = 0; u0 < U; u0 += UB) {
+        constexpr int UB = U < MGWFBP_STEP_BATCH ? U : MGWFBP_STEP_BATCH;  // float4 of w and of v held at once
+        static_for<U / UB>([&](auto bc) {
+            constexpr int u0 = decltype(bc)::value * UB;
             v4f w[UB], v[UB];
-#pragma unroll
-            for (int k = 0; k < UB; ++k) {
-                w[k] = ld_stream_after(wb, vo[u0 + k], res[u0 + k]);
+            static_for<UB>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                w[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(wb, vo, res[u0 + k]);
                 wait_all_loads(w[k]);
-                v[k] = ld_stream_after(vb, vo[u0 + k], w[k]);
+                v[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(vb, vo, w[k]);
                 wait_all_loads(v[k]);
-            }
+            });
 #pragma unroll
             for (int k = 0; k < UB; ++k) sgd_momentum(res[u0 + k], w[k], v[k], lr, mu);
-#pragma unroll
-            for (int k = 0; k < UB; ++k) {
-                st_stream(const_cast<char *>(vb), vo[u0 + k], v[k]);
-                st_stream(const_cast<char *>(wb), vo[u0 + k], w[k]);
-            }
-        }
+            static_for<UB>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(vb), vo, v[k]);
+                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(wb), vo, w[k]);
+            });
+        });
     }
     // without the update the averaged gradient is the only output, so out[] is always bound
     if (!STEP || outp) {
-        char *ob = reinterpret_cast<char *>(outp);
-#pragma unroll
-        for (int u = 0; u < U; ++u) st_stream(ob, vo[u], res[u]);
+        char *ob = const_cast<char *>(scalar_ptr(outp));
+        static_for<U>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            st_stream<MGWFBP_OFF(u)>(ob, vo, res[u]);
+        });
     }
+#undef MGWFBP_OFF
 }
 
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,

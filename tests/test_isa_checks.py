@@ -2,12 +2,12 @@
 assembly with the library's own flags and scanned.
 
 1. fp32 arithmetic is one rounding per operation: no fused multiply-add, no packed fp32.
-2. Hazard check for the hand-written loads of the fast path.  On gfx9-class hardware an SGPR
+2. Hazard check for the hand-written loads and stores of the fast path.  On gfx9-class hardware an SGPR
    written by a vector instruction (v_readfirstlane, v_readlane, a carry-out ...) must not be
    read by a vector memory instruction within 5 wait states.  The compiler pads its own memory
    instructions but does not look inside inline assembly, so a base pointer that reaches an
-   inline-asm global_load through v_readfirstlane without padding makes the load use a stale
-   address.  The kernels read their pointer tables with scalar loads and pad in scalar_ptr();
+   inline-asm global_load or global_store through v_readfirstlane without padding makes the
+   access use a stale address.  The kernels read their pointer tables with scalar loads and pad in scalar_ptr();
    this test keeps it that way.
 """
 import os
@@ -60,7 +60,7 @@ def _sgpr_dests(line):
 
 
 def test_hand_written_loads_respect_the_sgpr_hazard(isa_lines):
-    pat = re.compile(r"global_load_dwordx4 v\[\d+:\d+\], v\d+, s\[(\d+):(\d+)\].* nt")
+    pat = re.compile(r"global_(?:load_dwordx4 v\[\d+:\d+\], v\d+|store_dwordx4 v\d+, v\[\d+:\d+\]), s\[(\d+):(\d+)\].* nt")
     checked, bad = 0, []
     for i, l in enumerate(isa_lines):
         m = pat.search(l)
