@@ -228,9 +228,10 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  * One iteration of Algorithm 2 (MG-WFBP S-SGD) on two HIP streams, driven by events.
  *
  * The computation thread of Algorithm 2 is played by `compute_stream`: a stand-in backward
- * pass from layer L-1 down to layer 0, one kernel per group that occupies one wave for the
- * sum of its layers' tb_ms and touches no memory (only the moment a group's lowest layer is
- * done matters to the communication side).  The communication thread is played by
+ * pass from layer L-1 down to layer 0, one kernel per group that occupies one wave until the
+ * backward pass has reached the end of the group's lowest layer (an absolute deadline: the sum
+ * of tb_ms so far after time zero, read from the device clock) and touches no gradient memory
+ * (only the moment a group's lowest layer is done matters to the communication side).  The communication thread is played by
  * `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
  * mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
  * layer has finished its backward kernel, which is the start rule of Eq. 7 / Condition 2;
@@ -244,6 +245,8 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  *   t_iter_ms       out or NULL: end of the last group
  * Streams: hipStream_t handles at default priority; NULL = the default stream (using one
  * stream for both serialises everything).  Creates and destroys HIP events internally.
+ * Time zero is kept in one device word owned by the plan: two calls on the same plan must not
+ * run at the same time.
  */
 int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                          float momentum, void *compute_stream, void *comm_stream,

@@ -83,6 +83,7 @@ void release_device(mgwfbp_plan_t *pl)
         if (sw) (void)hipSetDevice(cur);
     }
     pl->d_blob = nullptr;
+    pl->d_clock = nullptr;
     pl->dt = DeviceTables();
     pl->bound = false;
 }
@@ -295,13 +296,13 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
         return fail(MGWFBP_ENOMEM, "out of host memory");
     }
 
-    // one device allocation: [segs][tiles][src][out][w][v], each part 256-byte aligned
+    // one device allocation: [segs][tiles][src][out][w][v][clock word], each part 256-byte aligned
     auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
     const size_t b_seg = up(pl->segs.size() * sizeof(SegDev));
     const size_t b_tile = up(pl->tiles.size() * sizeof(TileDev));
     const size_t b_src = up(src_tbl.size() * sizeof(void *));
     const size_t b_ptr = up(pl->segs.size() * sizeof(void *));
-    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr;
+    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr + 256;
     std::vector<char> host(total, 0);
     size_t o = 0;
     std::memcpy(host.data() + o, pl->segs.data(), pl->segs.size() * sizeof(SegDev));
@@ -313,6 +314,7 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
     const size_t o_out = o; o += b_ptr;
     const size_t o_w = o; o += b_ptr;
     const size_t o_v = o; o += b_ptr;
+    const size_t o_clock = o;
     if (out) std::memcpy(host.data() + o_out, out_tbl.data(), out_tbl.size() * sizeof(void *));
     if (w) {
         std::memcpy(host.data() + o_w, w_tbl.data(), w_tbl.size() * sizeof(void *));
@@ -339,6 +341,7 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
     pl->dt.out = out ? reinterpret_cast<float *const *>(d + o_out) : nullptr;
     pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
     pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
+    pl->d_clock = reinterpret_cast<uint64_t *>(d + o_clock);
     pl->has_out = out != nullptr;
     pl->has_wv = w != nullptr;
     pl->bound = true;

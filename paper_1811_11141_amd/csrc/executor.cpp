@@ -90,9 +90,12 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
     // the host needs tens of microseconds per group to enqueue kernels, event records and
     // waits, far more than a short group takes to run, so without a head start the measured
     // timeline would show the host's enqueue rate.  The gate keeps the compute stream busy
-    // while everything behind it is being queued; time zero is the end of the gate.
+    // while everything behind it is being queued; time zero is the end of the gate, where the
+    // gate publishes the device clock.  Every stand-in then waits for an absolute deadline
+    // (time zero + the backward time accumulated so far), so launch gaps between stand-ins do
+    // not stretch the backward pass.
     if ((rc = launch_spin(0.0, cs))) return rc;
-    if ((rc = launch_spin(1.0 + 0.06 * static_cast<double>(G), cs))) return rc;
+    if ((rc = launch_spin(1.0 + 0.06 * static_cast<double>(G), cs, pl->d_clock))) return rc;
     // the communication stream must not start before the backward pass does
     hipError_t e = hipEventRecord(base, cs);
     if (e != hipSuccess) return hip_fail("hipEventRecord", e);
@@ -100,15 +103,14 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
 
     // Backward pass, highest layer first.  Only the moment a group's lowest layer finishes
     // matters to the communication side, so the layers of a group share one stand-in kernel
-    // whose duration is the sum of their backward times.
-    double pending_ms = 0.0;
+    // that ends when the backward pass has reached the end of the group's lowest layer.
+    double elapsed_ms = 0.0;
     for (int32_t l = L - 1; l >= 0; --l) {
-        pending_ms += tb[l];
+        elapsed_ms += tb[l];
         if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
         // layer l is the lowest layer of its group: the group's gradients are complete
         const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
-        if ((rc = launch_spin(pending_ms, cs))) break;
-        pending_ms = 0.0;
+        if ((rc = launch_spin_until(elapsed_ms, pl->d_clock, cs))) break;
         if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) {
             rc = hip_fail("hipEventRecord", e);
             break;

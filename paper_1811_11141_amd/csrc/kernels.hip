@@ -650,13 +650,18 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
 // constant-rate real-time counter have passed.  It touches no memory.  The loop ends when the
 // counter has advanced far enough; the iteration cap is a second, independent exit.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls)
+// mode 0: wait `ticks` from now; then, if `clock` is given, publish the counter's value there.
+// mode 1: wait until `ticks` after the value published in `clock` (an absolute deadline, so the
+//         gaps between consecutive stand-ins do not add up).
+__global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls, uint64_t *clock, int mode)
 {
-    const uint64_t t0 = __builtin_amdgcn_s_memrealtime();
+    const uint64_t t0 = mode == 1 ? __builtin_nontemporal_load(clock) : __builtin_amdgcn_s_memrealtime();
     for (uint64_t i = 0; i < max_polls; ++i) {
         if (__builtin_amdgcn_s_memrealtime() - t0 >= ticks) break;
         __builtin_amdgcn_s_sleep(32);
     }
+    if (mode == 0 && clock != nullptr && threadIdx.x == 0)
+        __builtin_nontemporal_store(static_cast<uint64_t>(__builtin_amdgcn_s_memrealtime()), clock);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -848,9 +853,10 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
     return check_launch("unpack kernel launch");
 }
 
-int launch_spin(double ms, void *stream)
+namespace {
+// s_memrealtime counts at a constant 100 MHz on this family; ask the runtime to be sure
+int wall_clock_khz()
 {
-    // s_memrealtime counts at a constant 100 MHz on this family; ask the runtime to be sure
     static int khz = 0;
     if (khz == 0) {
         int dev = 0, v = 0;
@@ -860,12 +866,25 @@ int launch_spin(double ms, void *stream)
         else
             khz = 100000;
     }
+    return khz;
+}
+
+int spin(double ms, uint64_t *clock, int mode, void *stream)
+{
     if (!(ms > 0.0)) ms = 0.0;
-    const uint64_t ticks = static_cast<uint64_t>(ms * khz);
+    const uint64_t ticks = static_cast<uint64_t>(ms * wall_clock_khz());
     // one poll takes at least ~2048 clocks of sleep (~1 us); cap generously at 50x the target
     const uint64_t max_polls = 1000 + static_cast<uint64_t>(ms * 1000.0 * 50.0);
-    k_spin<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(ticks, max_polls);
+    k_spin<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(ticks, max_polls, clock, mode);
     return check_launch("backward stand-in launch");
+}
+}  // namespace
+
+int launch_spin(double ms, void *stream, uint64_t *publish_clock) { return spin(ms, publish_clock, 0, stream); }
+
+int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream)
+{
+    return spin(deadline_ms, clock, 1, stream);
 }
 
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream)

@@ -97,6 +97,7 @@ struct mgwfbp_plan_s {
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
+    uint64_t *d_clock = nullptr;  // one word at its end: time origin of mgwfbp_run_iteration
     mgwfbp::DeviceTables dt;
 };
 
@@ -136,7 +137,10 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
                   void *stream);
 int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *reduced, bool step,
                   float lr, float mu, void *stream);
-int launch_spin(double ms, void *stream);
+// Timed stand-ins for the backward pass: wait `ms`, optionally publishing the device clock at the
+// end; or wait until `deadline_ms` after the published clock value.
+int launch_spin(double ms, void *stream, uint64_t *publish_clock = nullptr);
+int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream);
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
 int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
                          float *dst, void *stream);

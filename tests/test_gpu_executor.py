@@ -45,12 +45,14 @@ def test_iteration_results_and_timeline(mg, seed, update):
     exp = od.merged_gradient_path(g_np, groups)
     for l in range(w.L):
         assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
-    # timeline: backward stand-ins take about t_b each (Eq. 6)
+    # timeline: each stand-in ends at its layer's mu_b after time zero (Eq. 6).  Time zero is
+    # the device clock read by the gate kernel just before it ends, the reported times count
+    # from an event recorded after that kernel, so "never early" holds up to a few microseconds.
     ready, gs, gf = tl["group_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
     mu_b = np.array(op.backward_finish(tb.tolist(), 0.0))
     mu_low = np.array([mu_b[grp[-1]] for grp in groups])      # mu_b of each group's lowest layer
-    assert np.all(ready >= mu_low - 1e-3)                     # never early
-    assert np.all(ready <= mu_low * 1.10 + 0.15)              # launch gaps only
+    assert np.all(ready >= mu_low - 5e-3)                     # never early
+    assert np.all(ready <= mu_low + 0.05)                     # absolute deadlines: gaps do not add up
     eps = 0.02
     for k, grp in enumerate(groups):
         assert gs[k] >= ready[k] - eps                        # gradients exist (Condition 2)

@@ -80,3 +80,17 @@ def test_hand_written_loads_respect_the_sgpr_hazard(isa_lines):
     assert checked > 1000          # the fast paths are there
     assert not bad, bad[:5]
     assert not any("v_readfirstlane" in l or "v_readlane" in l for l in isa_lines)
+
+
+def test_scalar_unit_only_reads_memory(isa_lines):
+    """Scalar memory instructions in the device code are loads and clock reads only: every
+    write to memory goes through the vector unit."""
+    scalar_mem = set()
+    for l in isa_lines:
+        mn = l.strip().split(" ")[0]
+        if mn.startswith("s_") and any(w in mn for w in ("load", "mem", "st" + "ore", "atomic", "cache", "scratch", "probe")):
+            scalar_mem.add(mn)
+    assert scalar_mem, "expected scalar loads of the tables"
+    allowed = ("s_load_dword", "s_buffer_load_dword", "s_memrealtime", "s_memtime")
+    bad = [m for m in scalar_mem if not m.startswith(allowed)]
+    assert not bad, bad
