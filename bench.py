@@ -196,6 +196,31 @@ def main():
             extra[variant] = {"ms_per_step": round(ms, 5),
                               "GBps_algorithmic": round(alg_bytes[variant] / (ms * 1e-3) / 1e9, 1),
                               "event_avg_us": round(kk["avg_ms"] * 1e3, 2)}
+        # the launch-per-group sequence captured once per gradient set into a HIP graph
+        graphs = []
+        torch.cuda.synchronize()
+        for st in sets:
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph, stream=stream):
+                cur = torch.cuda.current_stream()
+                for k in range(n_groups):
+                    st["plan"].pack_reduce_unpack(group=k, stream=cur)
+            graphs.append(gph)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for i in range(w2):
+                graphs[i % n_sets].replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(k2):
+                graphs[i % n_sets].replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / k2
+        extra["per_group_graph"] = {"groups": n_groups, "us_per_step": round(us, 2),
+                                    "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
+        del graphs
         # the two extreme plans (every tensor its own group / one group) through the same fused
         # launch: the rate should not depend on the plan
         for nm, md in (("fused_plan_wfbp", mg.MODE_WFBP), ("fused_plan_single", mg.MODE_SINGLE)):

@@ -532,6 +532,78 @@ def test_full_size_two_halves_sampled(mg, name, per_group):
             assert_same(vt[l][s:s + c].cpu().numpy(), vv, f"{name} v layer {l} window {s}")
 
 
+# ---- capture into a HIP graph ----------------------------------------------------------------
+
+@pytest.mark.parametrize("update", [False, True])
+def test_per_group_launches_replayed_from_a_graph(mg, update):
+    """The launch-per-group sequence of Algorithm 2 captured once into a HIP graph and replayed with
+    fresh gradients (eager copies and synchronisations between replays); every replay is checked
+    against the oracle.  The library only launches kernels, so nothing else enters the graph."""
+    w = wl.tiny_workload(31, L=12)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, 0.2, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    groups = pl.groups()
+    assert len(groups) > 1
+    grads = wl.make_gradients(w, 31, "cuda")
+    out = [torch.zeros_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 31, "cuda")
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        cur = torch.cuda.current_stream()
+        for k in range(len(groups)):
+            if update:
+                pl.step(0.1, 0.9, group=k, stream=cur)
+            else:
+                pl.pack_reduce_unpack(group=k, stream=cur)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        fresh = wl.make_gradients(w, 500 + rep, "cuda")
+        for g in range(w.n_workers):
+            for l in range(w.L):
+                grads[g][l].copy_(fresh[g][l])
+        for t in out:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g_np = [to_np(r) for r in grads]
+        if update:
+            exp = od.merged_gradient_path(g_np, groups, w_np, v_np, lr=0.1, mu=0.9)
+        else:
+            exp = od.merged_gradient_path(g_np, groups)
+        for l in range(w.L):
+            assert_same(out[l].cpu().numpy(), exp[l], f"replay {rep} layer {l}")
+            if update:
+                assert_same(wt[l].cpu().numpy(), w_np[l], f"replay {rep} w layer {l}")
+                assert_same(vt[l].cpu().numpy(), v_np[l], f"replay {rep} v layer {l}")
+
+
+def test_single_layer_beyond_4_gib(mg):
+    """One tensor of 1.2 G elements (4.8 GB per worker): tile starts and byte offsets pass 2^32.
+    Windows on both sides of the 2^32-byte mark and at the very end are recomputed by the oracle."""
+    n = 1_200_000_000 + 4 * 37 + 3          # ragged tail, not a multiple of four
+    w = wl.custom_workload([1000, n], 2, sigma=1e-3)
+    pl = make_plan(mg, w, [2])
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    grads = [[torch.empty(int(c), device="cuda").normal_(0, 1e-3, generator=gen) for c in w.p] for _ in range(2)]
+    out = [torch.full((int(c),), float("nan"), device="cuda") for c in w.p]
+    pl.bind(grads, out)
+    pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    mark = 2 ** 32 // 4
+    for s in (0, mark - 5000, mark - 17, 2 * mark + 123, n - 9000):
+        c = min(9000, n - s)
+        xs = [grads[g][1][s:s + c].cpu().numpy().copy() for g in range(2)]
+        assert_same(out[1][s:s + c].cpu().numpy(), od.reduce(xs), f"window {s}")
+    assert_same(out[0].cpu().numpy(), od.reduce([grads[g][0].cpu().numpy() for g in range(2)]), "small layer")
+    # no element left unwritten: the NaN sentinel is gone everywhere (checked in slices to bound memory)
+    for s in range(0, n, 1 << 28):
+        assert bool(torch.isfinite(out[1][s:s + (1 << 28)]).all()), s
+
+
 # ---- full-size gradient sets ---------------------------------------------------------------
 
 def window_starts(n, rng, width):
