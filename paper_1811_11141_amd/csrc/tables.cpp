@@ -21,7 +21,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     const int32_t L = pl.L, N = pl.N;
     const uint32_t tile = pl.opt.tile_elems;
     const uint32_t small = std::min(pl.opt.small_elems, tile);
-    // elements one gather tile may hold: a few per lane, since each costs a table search
+    // elements one gather tile may hold: a few per lane, since each costs a table search;
+    // small <= tile, so no tile of any kind exceeds tile_elems (the LDS staging size)
     const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
     std::vector<TileDev> all_slow, all_full;
 

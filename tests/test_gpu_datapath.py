@@ -532,6 +532,82 @@ def test_full_size_two_halves_sampled(mg, name, per_group):
             assert_same(vt[l][s:s + c].cpu().numpy(), vv, f"{name} v layer {l} window {s}")
 
 
+# ---- randomised sweep ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_all_entry_points(mg, seed):
+    """Random layer counts, sizes (tiny, around tile boundaries, large), worker counts, merge
+    sets, tilings and pointer misalignments; every data-path entry point against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(1, 41))
+    tile = int(rng.choice([1024, 2048, 4096, 8192]))
+    small = int(rng.choice([0, 1, 64, 512, 1024, 2048]))
+    kinds = rng.integers(0, 4, size=L)
+    sizes = []
+    for kd in kinds:
+        if kd == 0:
+            sizes.append(int(rng.integers(1, 600)))
+        elif kd == 1:
+            sizes.append(max(1, int(rng.integers(1, 6)) * tile + int(rng.integers(-5, 6))))
+        elif kd == 2:
+            sizes.append(int(rng.integers(1, 40)) * 4)
+        else:
+            sizes.append(int(rng.integers(10_000, 300_000)))
+    N = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 17]))
+    w = wl.custom_workload(sizes, N, sigma=1e-2)
+    merged = random_merged(rng, L)
+    groups = groups0(L, merged)
+    pl = make_plan(mg, w, merged, tile=tile, small=small, nt=int(rng.integers(0, 2)))
+    misalign = bool(rng.integers(0, 2))
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+
+    def tensor(n, scale):
+        k = int(rng.integers(0, 4)) if misalign else 0
+        base = torch.empty(n + 4, dtype=torch.float32, device="cuda").normal_(0, scale, generator=gen)
+        return base[k:k + n]
+
+    grads = [[tensor(n, 1e-2) for n in sizes] for _ in range(N)]
+    out = [tensor(n, 1.0) for n in sizes]
+    wt = [tensor(n, 0.1) for n in sizes]
+    vt = [tensor(n, 1e-3) for n in sizes]
+    g_np, w_np, v_np = [to_np(r) for r in grads], to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    exp = od.merged_gradient_path(g_np, groups)
+
+    def check_out(what):
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert_same(out[l].cpu().numpy(), exp[l], f"{what} layer {l} (seed {seed})")
+            out[l].fill_(float("nan"))
+
+    pl.pack_reduce_unpack()
+    check_out("fused")
+    for k in range(len(groups)):
+        pl.pack_reduce_unpack(group=k)
+    check_out("fused per group")
+    pl.pack_reduce_unpack(workspace=alloc_ws(pl))
+    check_out("materialised")
+    P = int(sum(sizes))
+    mb = merged_buffer(P)
+    pl.pack_reduce(mb)
+    pl.unpack_update(mb)
+    check_out("two halves")
+    layers = [l for g in groups for l in g]
+    assert_same(mb[:P].cpu().numpy(), od.pack(exp, layers), "merged buffer")
+    # three different routes to the update, each advancing (w, v) by one step
+    pl.step(0.1, 0.9)
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.1, 0.9)
+    for k in range(len(groups)):
+        pl.step(0.05, 0.8, group=k, workspace=alloc_ws(pl, k))
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.05, 0.8)
+    pl.unpack_update(mb, update=True, lr=0.2, momentum=0.5)
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.2, 0.5)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l} (seed {seed})")
+        assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l} (seed {seed})")
+
+
 # ---- capture into a HIP graph ----------------------------------------------------------------
 
 @pytest.mark.parametrize("update", [False, True])
