@@ -303,10 +303,34 @@ def main():
             extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
                          "GBps": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1)}
         del src, dst, srcs
+        # the tiny configuration (8 layers, N = 4): launch latency only, no bandwidth claim
+        lat = []
+        for seed in range(8):
+            tw = wl.tiny_workload(seed)
+            tg = wl.make_gradients(tw, seed, dev)
+            tp = mg.mgwfbp_plan(tw.p, tw.tb_ms, 0.0, tw.a_ms, tw.b_ms_per_byte, tw.n_workers, mg.MODE_OPTIMAL)
+            tp.bind(tg, [torch.empty_like(t) for t in tg[0]])
+            for _ in range(5):
+                tp.pack_reduce_unpack(stream=stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(50):
+                tp.pack_reduce_unpack(stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) * 1e3 / 50)
+            tp.destroy()
+        extra["tiny_config_us_per_launch"] = {"median": round(float(np.median(lat)), 2),
+                                              "min": round(float(np.min(lat)), 2), "seeds": len(lat)}
         result["extra"] = extra
+    props = torch.cuda.get_device_properties(0)
+    result["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
+                        "hbm_GiB": round(props.total_memory / 2 ** 30, 1)}
 
     if args.cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, sets[0], info, args.cpu_seconds)
+        result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)
 
     print(json.dumps(result))
 
@@ -327,7 +351,7 @@ def cpu_baseline(w, s, info, budget_s):
         od.merged_gradient_path(g_np, groups, threads=1)
         passes += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or passes >= 50:
+        if el >= budget_s or passes >= 1000:
             break
     sec = el / passes
     nthreads = min(od.max_threads(), os.cpu_count() or 1)
@@ -337,7 +361,7 @@ def cpu_baseline(w, s, info, budget_s):
     return {"value": round(4 * (N + 1) * P / sec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"{passes} whole passes of the oracle (pack, reduce, unpack per group) over "
                       f"gradient set 0 of the same workload, {el:.1f} s",
-            "seconds_per_pass": round(sec, 4),
+            "seconds_per_pass": round(sec, 4), "ns_per_element": round(sec / P * 1e9, 3),
             "all_threads": {"threads": nthreads, "value": round(4 * (N + 1) * P / sec_mt / 1e9, 3),
                             "seconds_per_pass": round(sec_mt, 4),
                             "note": "reduce loop split statically over threads; pack/unpack stay serial"}}
