@@ -125,6 +125,22 @@ int mgwfbp_plan_timeline(const mgwfbp_plan_t *plan, double *mu_b, double *group_
 int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
 
 /*
+ * Host-only view of the segment and tile tables the kernels would run with under the plan's
+ * current options (the tile table of Section IV's layer buffer, cut for the GPU).  Needs no
+ * device and no binding: every tensor is taken to be 16-byte aligned.
+ *   segments  host [segments_cap][4] out or NULL: layer, elements, offset in the plan-wide
+ *             merged order (elements), group -- in communication order
+ *   tiles     host [tiles_cap][5] out or NULL: first segment, segment count, start, elements,
+ *             list.  segment count 1: `start` is the element offset inside that segment;
+ *             more than one: the tile gathers whole short segments and `start` is its offset
+ *             in the plan-wide merged order.  list 0: the per-group lists (group after group);
+ *             list 1: the second copy used by whole-plan launches.
+ *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)
+ */
+int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t *segments,
+                       size_t segments_cap, uint64_t *n_tiles, uint64_t *tiles, size_t tiles_cap);
+
+/*
  * Attach tensors and upload the segment, tile and pointer tables (once; the pointers are
  * not re-read from host memory afterwards).  A second call replaces the binding.
  *   grads  host array [N*L] of device pointers, worker-major: grads[g*L + l] is worker g's

@@ -22,7 +22,7 @@ OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE = 1, 2, 3, 4
 
 EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
-    "mgwfbp_plan_set_option", "mgwfbp_bind", "mgwfbp_workspace_bytes",
+    "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update",
     "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
@@ -54,6 +54,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_plan_info.argtypes = [vp, P(i32), P(i32), P(u64), P(u64), P(f64), P(f64)]
     lib.mgwfbp_plan_timeline.argtypes = [vp, P(f64), P(f64), P(f64)]
     lib.mgwfbp_plan_set_option.argtypes = [vp, i32, i64]
+    lib.mgwfbp_plan_layout.argtypes = [vp, vp, vp, sz, vp, vp, sz]
     lib.mgwfbp_bind.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
     lib.mgwfbp_workspace_bytes.argtypes = [vp, i32, P(sz)]
     lib.mgwfbp_pack_reduce_unpack.argtypes = [vp, i32, vp, sz, vp]
@@ -163,6 +164,17 @@ class Plan:
     # ---- set-up ----------------------------------------------------------------------
     def set_option(self, key: int, value: int) -> None:
         _check(_lib.mgwfbp_plan_set_option(self._h, key, value))
+
+    def layout(self) -> dict:
+        """Segment and tile tables as the kernels would see them (host only, no device needed):
+        segments [n][layer, elements, plan offset, group], tiles [n][first segment, segment
+        count, start, elements, list]."""
+        ns, nt = C.c_uint64(0), C.c_uint64(0)
+        _check(_lib.mgwfbp_plan_layout(self._h, C.byref(ns), None, 0, C.byref(nt), None, 0))
+        segs = np.zeros((ns.value, 4), dtype=np.uint64)
+        tiles = np.zeros((nt.value, 5), dtype=np.uint64)
+        _check(_lib.mgwfbp_plan_layout(self._h, None, segs.ctypes.data, ns.value, None, tiles.ctypes.data, nt.value))
+        return {"segments": segs, "tiles": tiles}
 
     def bind(self, grads: Sequence[Sequence], out: Optional[Sequence] = None,
              w: Optional[Sequence] = None, v: Optional[Sequence] = None) -> None:

@@ -269,6 +269,49 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
     }
 }
 
+int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *segments,
+                       size_t segments_cap, uint64_t *n_tiles, uint64_t *tiles, size_t tiles_cap)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    try {
+        // the tables are built on a copy, from placeholder pointers that are only inspected for
+        // their alignment and never dereferenced; the copy owns no device memory
+        mgwfbp_plan_t tmp = *pl;
+        tmp.d_blob = nullptr;
+        tmp.d_clock = nullptr;
+        tmp.bound = false;
+        const size_t L = static_cast<size_t>(pl->L), N = static_cast<size_t>(pl->N);
+        float *const fake = reinterpret_cast<float *>(uintptr_t(1) << 20);
+        std::vector<const float *> g(N * L, fake);
+        std::vector<float *> o(L, fake);
+        std::vector<const float *> src_tbl;
+        std::vector<float *> out_tbl, w_tbl, v_tbl;
+        build_tables(tmp, g.data(), o.data(), o.data(), o.data(), src_tbl, out_tbl, w_tbl, v_tbl);
+        if (n_segments) *n_segments = tmp.segs.size();
+        if (n_tiles) *n_tiles = tmp.tiles.size();
+        if (segments) {
+            if (segments_cap < tmp.segs.size()) return fail(MGWFBP_EINVAL, "segments array too small");
+            for (size_t i = 0; i < tmp.segs.size(); ++i) {
+                const SegDev &sd = tmp.segs[i];
+                uint64_t *r = segments + 4 * i;
+                r[0] = sd.layer; r[1] = sd.n; r[2] = sd.plan_off; r[3] = sd.group;
+            }
+        }
+        if (tiles) {
+            if (tiles_cap < tmp.tiles.size()) return fail(MGWFBP_EINVAL, "tiles array too small");
+            for (size_t i = 0; i < tmp.tiles.size(); ++i) {
+                const TileDev &t = tmp.tiles[i];
+                uint64_t *r = tiles + 5 * i;
+                r[0] = t.seg; r[1] = t.nseg; r[2] = t.start; r[3] = t.n;
+                r[4] = i >= tmp.all_tile_begin ? 1 : 0;
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+    return MGWFBP_OK;
+}
+
 int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, float *const *w,
                 float *const *v)
 {

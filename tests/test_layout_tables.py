@@ -1,0 +1,107 @@
+"""Host logic of the segment / tile tables (no GPU): what the kernels would be told to do.
+
+The oracle side is only the definition of the merged order: groups in communication order,
+layers inside a group from the highest down (Algorithm 2 pushes layers as their backward pass
+ends), offsets = running element counts without padding (Condition 3)."""
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import planner as op
+from paper_1811_11141_amd import binding as mg
+from paper_1811_11141_amd import workloads as wl
+
+
+def expected_segments(p, merged):
+    """[(layer0, n, plan offset, group)] in merged order, from the oracle's grouping."""
+    rows, off = [], 0
+    for k, grp in enumerate(op.groups_from_merged(len(p), merged)):
+        for l in grp:
+            rows.append((l - 1, int(p[l - 1]), off, k))
+            off += int(p[l - 1])
+    return rows
+
+
+def check_layout(p, merged, tile, small):
+    L = len(p)
+    pl = mg.mgwfbp_plan_explicit(p, np.ones(L), 0.0, 0.5, 1e-6, 2, merged)
+    pl.set_option(mg.OPT_TILE_ELEMS, tile)
+    pl.set_option(mg.OPT_SMALL_ELEMS, small)
+    lay = pl.layout()
+    segs, tiles = lay["segments"], lay["tiles"]
+    exp = expected_segments(p, merged)
+    assert [tuple(int(x) for x in r) for r in segs] == exp
+    P = int(np.sum(p))
+    small_eff = min(small, tile)
+    for which in (0, 1):                      # per-group lists, whole-plan list
+        cover = np.zeros(P, dtype=np.uint8)
+        sel = tiles[tiles[:, 4] == which]
+        assert len(sel) > 0
+        last_group, seen_full_in_group = -1, False
+        for first, nseg, start, n, _ in (tuple(int(x) for x in r) for r in sel):
+            assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
+            assert 1 <= nseg <= 256
+            if nseg == 1:
+                lyr, sn, soff, grp = exp[first]
+                assert start + n <= sn, "direct tile stays inside its segment"
+                assert start % tile == 0
+                assert n == tile or start + n == sn, "only the last piece of a segment is ragged"
+                lo = soff + start
+            else:
+                members = exp[first:first + nseg]
+                assert all(m[1] < small_eff for m in members), "gather tiles hold short layers only"
+                assert len({m[3] for m in members}) == 1, "a gather tile never crosses a group"
+                assert start == members[0][2] and n == sum(m[1] for m in members)
+                assert n <= max(min(tile, 1024), small_eff)
+                grp = members[0][3]
+                lo = start
+            cover[lo:lo + n] += 1
+            if which == 0:
+                # group after group; inside a group the slow tiles (gather, ragged) come first
+                assert grp >= last_group
+                if grp != last_group:
+                    last_group, seen_full_in_group = grp, False
+                full = nseg == 1 and n == tile
+                assert not (seen_full_in_group and not full), "slow tile after a full tile"
+                seen_full_in_group = seen_full_in_group or full
+        assert cover.min() == 1 and cover.max() == 1, "every element in exactly one tile"
+    pl.destroy()
+
+
+@pytest.mark.parametrize("tile,small", [(1024, 0), (1024, 512), (4096, 512), (4096, 8192), (8192, 1), (2048, 2048)])
+def test_layout_tiny_nets(tile, small):
+    for seed in range(6):
+        w = wl.tiny_workload(seed, L=10)
+        rng = np.random.default_rng(seed)
+        merged = [l for l in range(2, w.L + 1) if rng.random() < 0.5]
+        check_layout(w.p, merged, tile, small)
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.lists(st.integers(1, 20000), min_size=1, max_size=30), st.data(),
+       st.sampled_from([1024, 2048, 4096, 8192]), st.sampled_from([0, 1, 64, 512, 1024, 4096, 8192]))
+def test_layout_random(p, data, tile, small):
+    L = len(p)
+    merged = [l for l in range(2, L + 1) if data.draw(st.booleans())]
+    check_layout(np.array(p, dtype=np.uint64), merged, tile, small)
+
+
+def test_layout_many_tiny_layers_split_gather_tiles():
+    """300 layers of 3 elements in one group: more than 256 segments cannot share one tile."""
+    p = np.full(300, 3, dtype=np.uint64)
+    check_layout(p, list(range(2, 301)), 4096, 512)
+
+
+def test_layout_cnn_sets_default_options():
+    for name, n_tiles_min in (("resnet50", 6000), ("vgg16", 33000)):
+        w = wl.cnn_workload(name)
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+        lay = pl.layout()
+        whole = lay["tiles"][lay["tiles"][:, 4] == 1]
+        assert len(whole) >= n_tiles_min
+        assert int(whole[:, 3].sum()) == w.P
+        full = whole[(whole[:, 1] == 1) & (whole[:, 3] == 4096)]
+        assert int(full[:, 3].sum()) > 0.97 * w.P          # the bulk runs the fast path
+        merged = pl.merged_layers()
+        assert [tuple(int(x) for x in r) for r in lay["segments"]] == expected_segments(w.p, merged)
+        pl.destroy()
