@@ -259,6 +259,8 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  *   group_start_ms  host [n_groups] out or NULL: when group k's kernel could start (tau_c)
  *   group_finish_ms host [n_groups] out or NULL
  *   t_iter_ms       out or NULL: end of the last group
+ * Per-group timestamps cost a timed event record each (a few microseconds of stream time);
+ * pass NULL for the three arrays to run the schedule with only the events it needs.
  * Streams: hipStream_t handles at default priority; NULL = the default stream (using one
  * stream for both serialises everything).  Creates and destroys HIP events internally.
  * Time zero is kept in one device word owned by the plan: two calls on the same plan must not

@@ -241,8 +241,9 @@ class Plan:
                                          C.c_void_p(_stream(stream))))
 
     def run_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
-                      lr: float = 0.0, momentum: float = 0.0) -> dict:
-        """One event-driven iteration (see mgwfbp_run_iteration); returns the measured timeline."""
+                      lr: float = 0.0, momentum: float = 0.0, timeline: bool = True) -> dict:
+        """One event-driven iteration (see mgwfbp_run_iteration); returns the measured timeline,
+        or only t_iter_ms with timeline=False (no per-group timestamps are taken then)."""
         ng = self.info()["n_groups"]
         ready, gs, gf = np.zeros(ng), np.zeros(ng), np.zeros(ng)
         t_iter = C.c_double()
@@ -252,7 +253,10 @@ class Plan:
             raise ValueError("tb_ms must have L entries")
         _check(_lib.mgwfbp_run_iteration(self._h, None if tb is None else dp(tb), int(update), lr, momentum,
                                          C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)),
-                                         dp(ready), dp(gs), dp(gf), C.byref(t_iter)))
+                                         dp(ready) if timeline else None, dp(gs) if timeline else None,
+                                         dp(gf) if timeline else None, C.byref(t_iter)))
+        if not timeline:
+            return {"t_iter_ms": t_iter.value}
         return {"group_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
                 "t_iter_ms": t_iter.value}
 

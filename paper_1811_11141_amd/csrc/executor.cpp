@@ -26,9 +26,9 @@ struct Events {
     {
         for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     }
-    int make(hipEvent_t *out)
+    int make(hipEvent_t *out, bool timed = true)
     {
-        const hipError_t e = hipEventCreate(out);
+        const hipError_t e = timed ? hipEventCreate(out) : hipEventCreateWithFlags(out, hipEventDisableTiming);
         if (e != hipSuccess) {
             set_error(std::string("hipEventCreate: ") + hipGetErrorString(e));
             return MGWFBP_EHIP;
@@ -75,14 +75,19 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);
     hipStream_t ms = static_cast<hipStream_t>(comm_stream);
 
+    // Per-group timestamps are taken only when the caller asks for them: a timed event record
+    // costs a few microseconds of stream time, which is a large part of a short group's cost.
+    const bool time_ready = group_ready_ms != nullptr;
+    const bool time_comm = group_start_ms != nullptr || group_finish_ms != nullptr;
     Events pool;
-    hipEvent_t base;
-    std::vector<hipEvent_t> g_ready(G), g_start(G), g_finish(G);
+    hipEvent_t base, done;
+    std::vector<hipEvent_t> g_ready(G), g_start(time_comm ? G : 0), g_finish(time_comm ? G : 0);
     int rc = pool.make(&base);
+    if (!rc) rc = pool.make(&done);
     for (size_t k = 0; k < G && !rc; ++k) {
-        rc = pool.make(&g_ready[k]);
-        if (!rc) rc = pool.make(&g_start[k]);
-        if (!rc) rc = pool.make(&g_finish[k]);
+        rc = pool.make(&g_ready[k], time_ready);
+        if (!rc && time_comm) rc = pool.make(&g_start[k]);
+        if (!rc && time_comm) rc = pool.make(&g_finish[k]);
     }
     if (rc) return rc;
 
@@ -119,17 +124,19 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
             rc = hip_fail("hipStreamWaitEvent", e);
             break;
         }
-        if ((e = hipEventRecord(g_start[k], ms)) != hipSuccess) {
+        if (time_comm && (e = hipEventRecord(g_start[k], ms)) != hipSuccess) {
             rc = hip_fail("hipEventRecord", e);
             break;
         }
         if ((rc = run_scope(pl, static_cast<int32_t>(k), update != 0, lr, momentum, nullptr, 0, ms)))
             break;
-        if ((e = hipEventRecord(g_finish[k], ms)) != hipSuccess) {
+        if (time_comm && (e = hipEventRecord(g_finish[k], ms)) != hipSuccess) {
             rc = hip_fail("hipEventRecord", e);
             break;
         }
     }
+    // groups run in order on the communication stream: its end is the end of the iteration (Eq. 8)
+    if (!rc && (e = hipEventRecord(done, ms)) != hipSuccess) rc = hip_fail("hipEventRecord", e);
     // whatever was enqueued must drain before the events are destroyed or read
     const hipError_t e1 = hipStreamSynchronize(cs);
     const hipError_t e2 = hipStreamSynchronize(ms);
@@ -144,17 +151,21 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
         *out = static_cast<double>(t);
         return MGWFBP_OK;
     };
-    double last = 0.0;
     for (size_t k = 0; k < G; ++k) {
-        double tr, ts, tf;
-        if ((rc = since_base(g_ready[k], &tr))) return rc;
-        if (group_ready_ms) group_ready_ms[k] = tr;
-        if ((rc = since_base(g_start[k], &ts))) return rc;
-        if ((rc = since_base(g_finish[k], &tf))) return rc;
-        if (group_start_ms) group_start_ms[k] = ts;
-        if (group_finish_ms) group_finish_ms[k] = tf;
-        if (tf > last) last = tf;
+        double t;
+        if (time_ready) {
+            if ((rc = since_base(g_ready[k], &t))) return rc;
+            group_ready_ms[k] = t;
+        }
+        if (time_comm) {
+            if ((rc = since_base(g_start[k], &t))) return rc;
+            if (group_start_ms) group_start_ms[k] = t;
+            if ((rc = since_base(g_finish[k], &t))) return rc;
+            if (group_finish_ms) group_finish_ms[k] = t;
+        }
     }
-    if (t_iter_ms) *t_iter_ms = last;
+    double total = 0.0;
+    if ((rc = since_base(done, &total))) return rc;
+    if (t_iter_ms) *t_iter_ms = total;
     return MGWFBP_OK;
 }
