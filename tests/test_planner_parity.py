@@ -186,6 +186,35 @@ def test_cnn_plans_are_consistent():
         assert int(inf["group_elems"].sum()) == w.P
 
 
+@pytest.mark.parametrize("name", ["resnet50", "googlenet", "alexnet", "vgg16"])
+@pytest.mark.parametrize("a_ms,g_eff", [(0.1, 2e12), (0.5, 2e12), (2.0, 2e12), (0.5, 2e13), (0.02, 2e14)])
+def test_full_size_plans_admit_no_better_neighbour(name, a_ms, g_eff):
+    """Where brute force cannot go (L up to 161): necessary conditions of optimality, all
+    evaluated by the oracle's simulate.  No plan reached by toggling one layer (for the short
+    nets: any two layers) of the optimal merge set, no random merge set, and none of the named
+    plans (no merging, single group, Theorem 1's rule) finishes earlier."""
+    w = wl.cnn_workload(name, a_ms=a_ms, g_eff=g_eff)
+    args = oracle_args(w)
+    pl = plan_for(w, mg.MODE_OPTIMAL)
+    m_opt = set(pl.merged_layers())
+    t_opt = pl.info()["t_iter_ms"]
+    assert t_opt == op.simulate(*args, m_opt)
+    cand = list(range(2, w.L + 1))
+    for l in cand:
+        assert op.simulate(*args, m_opt ^ {l}) >= t_opt, f"toggling layer {l} is better"
+    if w.L <= 32:
+        for i, l1 in enumerate(cand):
+            for l2 in cand[i + 1:]:
+                assert op.simulate(*args, m_opt ^ {l1, l2}) >= t_opt, (l1, l2)
+    rng = np.random.default_rng(w.L)
+    for _ in range(300):
+        density = rng.random()
+        m = {l for l in cand if rng.random() < density}
+        assert op.simulate(*args, m) >= t_opt
+    assert op.simulate(*args, op.algorithm1(*args)) >= t_opt
+    assert op.wfbp_timeline(*args)[1] >= t_opt and op.simulate(*args, cand) >= t_opt
+
+
 def test_error_paths():
     lib = mg.raw()
     p = (C.c_uint64 * 3)(10, 20, 30)
