@@ -8,10 +8,12 @@
 //   k_reduce  Eq. 2 over N contiguous merged buffers.
 //   k_unpack  merged buffer back to per-layer tensors (+ update of Eq. 1-2 with momentum).
 //
-// The path is bound by HBM bandwidth (0.2-0.3 flop per byte), so the kernels are built
-// around 128-bit coalesced accesses with all N loads of a lane issued before the first add;
-// there is nothing for the matrix cores to do.  One workgroup of 128 lanes (2 wave64) owns
-// one tile.  Arithmetic order is fixed (worker 0 first, one rounding per operation; the file
+// The path is bound by HBM bandwidth (0.2-0.3 flop per byte); there is nothing for the matrix
+// cores to do.  One workgroup of 128 lanes (2 wave64) owns one tile.  Full aligned tiles, the
+// bulk of the bytes, run fast_tile(): 128-bit streaming loads and stores written out as
+// instructions, one load in flight per wave at full occupancy, stores after all loads.  The
+// rest (ragged tails, misaligned tensors, gather tiles of many tiny layers, run-time N) runs
+// compiler-scheduled loops that issue the N loads of an element before the first add.  Arithmetic order is fixed (worker 0 first, one rounding per operation; the file
 // is compiled with -ffp-contract=off) so results are reproducible bit for bit.
 #include <hip/hip_runtime.h>
 
@@ -261,8 +263,9 @@ __device__ __forceinline__ void static_for(F f)
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-// Block until at most K of this wave's vector-memory loads are outstanding.  Loads return in issue order, so this covers x when k loads were issued
-// after it.  x is an in/out operand only to pin the wait between the load and its first use.
+// Block until at most K of this wave's vector-memory loads are outstanding.  Loads return in
+// issue order, so this covers x when K loads were issued after it.  x is an in/out operand only
+// to pin the wait between the load and its first use.
 template <int K>
 __device__ __forceinline__ void wait_loads(v4f &x)
 {
