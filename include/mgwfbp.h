@@ -33,6 +33,8 @@
  *     Update arithmetic: v = mu*v + g; w = w - lr*v, each operation rounded separately.
  *     Pack and unpack are bit copies.
  *   - A plan handle must not be used from two threads at once.
+ *   - mgwfbp_bind places the plan's tables on the current device; later launches must be made
+ *     with that device current (MGWFBP_ESTATE otherwise).
  */
 #ifndef MGWFBP_H
 #define MGWFBP_H
@@ -130,11 +132,13 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  * device and no binding: every tensor is taken to be 16-byte aligned.
  *   segments  host [segments_cap][4] out or NULL: layer, elements, offset in the plan-wide
  *             merged order (elements), group -- in communication order
- *   tiles     host [tiles_cap][5] out or NULL: first segment, segment count, start, elements,
- *             list.  segment count 1: `start` is the element offset inside that segment;
+ *   tiles     host [tiles_cap][6] out or NULL: first segment, segment count, start, elements,
+ *             list, tile length.  segment count 1: `start` is the element offset inside that segment;
  *             more than one: the tile gathers whole short segments and `start` is its offset
  *             in the plan-wide merged order.  list 0: the per-group lists (group after group);
- *             list 1: the second copy used by whole-plan launches.
+ *             list 1: the second copy used by whole-plan launches.  tile length: elements of a
+ *             full tile in that list (a group launched alone is cut into shorter tiles than
+ *             the whole plan when it would otherwise give too few workgroups).
  *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)
  */
 int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t *segments,

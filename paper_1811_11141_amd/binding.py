@@ -168,11 +168,11 @@ class Plan:
     def layout(self) -> dict:
         """Segment and tile tables as the kernels would see them (host only, no device needed):
         segments [n][layer, elements, plan offset, group], tiles [n][first segment, segment
-        count, start, elements, list]."""
+        count, start, elements, list, tile length]."""
         ns, nt = C.c_uint64(0), C.c_uint64(0)
         _check(_lib.mgwfbp_plan_layout(self._h, C.byref(ns), None, 0, C.byref(nt), None, 0))
         segs = np.zeros((ns.value, 4), dtype=np.uint64)
-        tiles = np.zeros((nt.value, 5), dtype=np.uint64)
+        tiles = np.zeros((nt.value, 6), dtype=np.uint64)
         _check(_lib.mgwfbp_plan_layout(self._h, None, segs.ctypes.data, ns.value, None, tiles.ctypes.data, nt.value))
         return {"segments": segs, "tiles": tiles}
 

@@ -97,6 +97,7 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
         sc.n_tiles = pl->all_tile_count;
         sc.elems = pl->total_elems;
         sc.base_off = 0;
+        sc.tile_elems = pl->opt.tile_elems;
         sc.needs_lds = pl->all_needs_lds;
     } else {
         const GroupInfo &g = pl->groups[group];
@@ -104,6 +105,7 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
         sc.n_tiles = g.tile_end - g.tile_begin;
         sc.elems = g.elems;
         sc.base_off = g.plan_off;
+        sc.tile_elems = g.tile_elems;
         sc.needs_lds = g.needs_lds;
     }
     return MGWFBP_OK;
@@ -127,6 +129,11 @@ int check_bound(const mgwfbp_plan_t *pl, bool need_out, bool need_wv)
     if (!pl->bound) return fail(MGWFBP_ESTATE, "mgwfbp_bind has not been called");
     if (need_out && !pl->has_out) return fail(MGWFBP_ESTATE, "out[] is not bound");
     if (need_wv && !pl->has_wv) return fail(MGWFBP_ESTATE, "w[] and v[] are not bound");
+    // the tables live in the memory of the device that was current at mgwfbp_bind
+    int cur = -1;
+    if (hipGetDevice(&cur) == hipSuccess && cur != pl->device)
+        return fail(MGWFBP_ESTATE, "plan is bound on device " + std::to_string(pl->device) +
+                                       " but the current device is " + std::to_string(cur));
     return MGWFBP_OK;
 }
 
@@ -301,9 +308,13 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
             if (tiles_cap < tmp.tiles.size()) return fail(MGWFBP_EINVAL, "tiles array too small");
             for (size_t i = 0; i < tmp.tiles.size(); ++i) {
                 const TileDev &t = tmp.tiles[i];
-                uint64_t *r = tiles + 5 * i;
+                uint64_t *r = tiles + 6 * i;
                 r[0] = t.seg; r[1] = t.nseg; r[2] = t.start; r[3] = t.n;
                 r[4] = i >= tmp.all_tile_begin ? 1 : 0;
+                r[5] = tmp.opt.tile_elems;
+                if (!r[4])
+                    for (const GroupInfo &g : tmp.groups)
+                        if (i >= g.tile_begin && i < g.tile_end) r[5] = g.tile_elems;
             }
         }
     } catch (const std::bad_alloc &) {

@@ -776,7 +776,7 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const dim3 grid(sc.n_tiles);
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const bool nt = pl.opt.nontemporal != 0;
-    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));  // float4 per lane per worker
+    const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));  // float4 per lane per worker
     // 256 CUs x 4 SIMDs x 8 waves = 8192 wave slots = 4096 workgroups; below about half of that
     // the launch cannot saturate HBM with one load per wave and is bound by latency instead
     const bool deep = sc.n_tiles < 2048;
@@ -797,7 +797,7 @@ int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint6
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(sc.n_tiles, static_cast<uint32_t>(pl.N));
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));
+    const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));
     const bool deep = static_cast<uint64_t>(sc.n_tiles) * pl.N < 2048;
     const int pace = pl.opt.pace;
     if (!pl.opt.nontemporal) {
@@ -816,7 +816,7 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
 {
     if (sc.elems == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint32_t tile = pl.opt.tile_elems;
+    const uint32_t tile = sc.tile_elems;
     const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int u = static_cast<int>(tile / (kBlock * 4));
@@ -840,7 +840,7 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(sc.n_tiles);
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    const int u = static_cast<int>(pl.opt.tile_elems / (kBlock * 4));
+    const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));
     // a single read stream: eight loads in flight per wave beat one at any launch size
     // (measured: scatter +6 %, with the update +1.5 %); with N streams it is the other way round
     const bool deep = true;

@@ -68,6 +68,7 @@ struct GroupInfo {
     uint64_t plan_off = 0;
     uint32_t seg_begin = 0, seg_end = 0;
     uint32_t tile_begin = 0, tile_end = 0;
+    uint32_t tile_elems = 0;  // tile length of the group's own list (<= the plan's tile_elems)
     bool needs_lds = false;  // a gather tile or a misaligned copy exists in this group
     double start_ms = 0, finish_ms = 0;
 };
@@ -127,6 +128,7 @@ struct LaunchScope {
     uint32_t tile_begin, n_tiles;
     uint64_t elems;       // elements in scope (one group or the whole plan)
     uint64_t base_off;    // plan_off of the scope's first element
+    uint32_t tile_elems;  // length of the full tiles in this scope's list
     bool needs_lds;
 };
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,

@@ -79,45 +79,55 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         // layers shares gather tiles so that tiny tensors cost no workgroup each.  Gather
         // tiles and ragged tails run the general (slower) code path, so they are listed first:
         // workgroups are dispatched in order and the slow ones then overlap with the bulk.
-        std::vector<TileDev> slow, full;
-        uint32_t s = g.seg_begin;
-        while (s < g.seg_end) {
-            const SegDev &sd = pl.segs[s];
-            if (sd.n >= small) {
-                for (uint64_t st = 0; st < sd.n; st += tile) {
-                    TileDev t{};
-                    t.start = st;
-                    t.seg = s;
-                    t.nseg = 1;
-                    t.n = static_cast<uint32_t>(std::min<uint64_t>(tile, sd.n - st));
-                    (t.n == tile ? full : slow).push_back(t);
+        auto cut = [&](uint32_t tile_len, std::vector<TileDev> &slow, std::vector<TileDev> &full) {
+            uint32_t s = g.seg_begin;
+            while (s < g.seg_end) {
+                const SegDev &sd = pl.segs[s];
+                if (sd.n >= small) {
+                    for (uint64_t st = 0; st < sd.n; st += tile_len) {
+                        TileDev t{};
+                        t.start = st;
+                        t.seg = s;
+                        t.nseg = 1;
+                        t.n = static_cast<uint32_t>(std::min<uint64_t>(tile_len, sd.n - st));
+                        (t.n == tile_len ? full : slow).push_back(t);
+                    }
+                    ++s;
+                    continue;
                 }
-                ++s;
-                continue;
+                TileDev t{};
+                t.start = sd.plan_off;
+                t.seg = s;
+                uint64_t n = 0;
+                uint32_t cnt = 0;
+                while (s < g.seg_end && pl.segs[s].n < small && cnt < kMaxGatherSegs &&
+                       n + pl.segs[s].n <= gather_cap) {
+                    n += pl.segs[s].n;
+                    ++cnt;
+                    ++s;
+                }
+                t.nseg = cnt;
+                t.n = static_cast<uint32_t>(n);
+                if (cnt == 1) t.start = 0;  // a lone short layer is an ordinary direct tile
+                else g.needs_lds = true;
+                slow.push_back(t);
             }
-            TileDev t{};
-            t.start = sd.plan_off;
-            t.seg = s;
-            uint64_t n = 0;
-            uint32_t cnt = 0;
-            while (s < g.seg_end && pl.segs[s].n < small && cnt < kMaxGatherSegs &&
-                   n + pl.segs[s].n <= gather_cap) {
-                n += pl.segs[s].n;
-                ++cnt;
-                ++s;
-            }
-            t.nseg = cnt;
-            t.n = static_cast<uint32_t>(n);
-            if (cnt == 1) t.start = 0;  // a lone short layer is an ordinary direct tile
-            else g.needs_lds = true;
-            slow.push_back(t);
-        }
+        };
+        // A launch of this group alone is short: below about 2048 workgroups it cannot fill the
+        // chip and every wave's chain of dependent loads decides its duration, so the group's
+        // own list uses shorter tiles (more workgroups, shorter chains) while the whole-plan
+        // list keeps the long tiles that stream best.
+        g.tile_elems = tile;
+        while (g.tile_elems >= 2048 && (g.tile_elems / 2) % 1024 == 0 && g.tile_elems > tile / 4 &&
+               (g.elems + g.tile_elems - 1) / g.tile_elems < 2048)
+            g.tile_elems /= 2;
+        std::vector<TileDev> slow, full;
+        cut(g.tile_elems, slow, full);
         g.tile_begin = static_cast<uint32_t>(pl.tiles.size());
         pl.tiles.insert(pl.tiles.end(), slow.begin(), slow.end());
         pl.tiles.insert(pl.tiles.end(), full.begin(), full.end());
-        all_slow.insert(all_slow.end(), slow.begin(), slow.end());
-        all_full.insert(all_full.end(), full.begin(), full.end());
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
+        cut(tile, all_slow, all_full);
         pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
     }
     // A second copy of the tile list for whole-plan launches: every slow tile of every group

@@ -38,14 +38,16 @@ def check_layout(p, merged, tile, small):
         sel = tiles[tiles[:, 4] == which]
         assert len(sel) > 0
         last_group, seen_full_in_group = -1, False
-        for first, nseg, start, n, _ in (tuple(int(x) for x in r) for r in sel):
+        for first, nseg, start, n, _, tlen in (tuple(int(x) for x in r) for r in sel):
             assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
+            # a group's own list may use shorter tiles than the whole-plan list, never longer
+            assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
             assert 1 <= nseg <= 256
             if nseg == 1:
                 lyr, sn, soff, grp = exp[first]
                 assert start + n <= sn, "direct tile stays inside its segment"
-                assert start % tile == 0
-                assert n == tile or start + n == sn, "only the last piece of a segment is ragged"
+                assert start % tlen == 0
+                assert n == tlen or start + n == sn, "only the last piece of a segment is ragged"
                 lo = soff + start
             else:
                 members = exp[first:first + nseg]
@@ -61,10 +63,18 @@ def check_layout(p, merged, tile, small):
                 assert grp >= last_group
                 if grp != last_group:
                     last_group, seen_full_in_group = grp, False
-                full = nseg == 1 and n == tile
+                full = nseg == 1 and n == tlen
                 assert not (seen_full_in_group and not full), "slow tile after a full tile"
                 seen_full_in_group = seen_full_in_group or full
         assert cover.min() == 1 and cover.max() == 1, "every element in exactly one tile"
+        if which == 0:
+            # the shorter tiles are there to give a short launch enough workgroups
+            for k, grp in enumerate(op.groups_from_merged(len(p), merged)):
+                ge = sum(int(p[l - 1]) for l in grp)
+                tl_k = {int(r[5]) for r in sel if exp[int(r[0])][3] == k}
+                assert len(tl_k) == 1
+                t_k = tl_k.pop()
+                assert t_k == tile or -(-ge // (2 * t_k)) < 2048, "halved only while the launch is short"
     pl.destroy()
 
 
