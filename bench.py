@@ -303,6 +303,19 @@ def main():
             extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
                          "GBps": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1)}
         del src, dst, srcs
+        # host side, once per training job: planning and binding time
+        host = {}
+        for nm, md in (("optimal", mg.MODE_OPTIMAL), ("theorem1", mg.MODE_PAPER_GREEDY)):
+            t0 = time.perf_counter()
+            for _ in range(20):
+                new_plan(md).destroy()
+            host[f"plan_{nm}_us"] = round((time.perf_counter() - t0) / 20 * 1e6, 1)
+        pb = new_plan()
+        t0 = time.perf_counter()
+        pb.bind(sets[0]["grads"], sets[0]["out"], sets[0]["w"], sets[0]["v"])
+        host["bind_us"] = round((time.perf_counter() - t0) * 1e6, 1)
+        pb.destroy()
+        extra["host_once"] = host
         # the tiny configuration (8 layers, N = 4): launch latency only, no bandwidth claim
         lat = []
         for seed in range(8):
