@@ -267,13 +267,35 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  * pass NULL for the three arrays to run the schedule with only the events it needs.
  * Streams: hipStream_t handles at default priority; NULL = the default stream (using one
  * stream for both serialises everything).  Creates and destroys HIP events internally.
- * Time zero is kept in one device word owned by the plan: two calls on the same plan must not
+ * Time zero and the end of the last group are device-clock values kept in two words owned by the plan: two calls on the same plan must not
  * run at the same time.
  */
 int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                          float momentum, void *compute_stream, void *comm_stream,
                          double *group_ready_ms, double *group_start_ms,
                          double *group_finish_ms, double *t_iter_ms);
+
+/*
+ * The same iteration captured once into a HIP graph and replayed: one graph launch per
+ * iteration instead of several runtime calls per group, for loops in which the schedule
+ * (plan, backward times, update parameters, bound tensors) does not change.
+ *   mgwfbp_iteration_capture  records the stand-ins, the per-group dependencies and the group
+ *       launches of mgwfbp_run_iteration from two different non-default streams (used only
+ *       to express the fork and join; nothing runs during capture).  lr and momentum are
+ *       frozen into the graph.  The tensors bound to the plan are referenced, not copied:
+ *       replays see their current contents.
+ *   mgwfbp_iteration_replay   launches the graph on `hip_stream`.  t_iter_ms == NULL: returns
+ *       at once (asynchronous).  Otherwise waits for the stream and reports the time from the
+ *       start of the backward pass to the end of the last group, read from the device clock.
+ *   mgwfbp_iteration_destroy  frees the graph.  Destroy it before re-binding or destroying
+ *       the plan; replays of one plan must not overlap.
+ */
+typedef struct mgwfbp_iteration_s mgwfbp_iteration_t; /* opaque */
+int mgwfbp_iteration_capture(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
+                             float momentum, void *compute_stream, void *comm_stream,
+                             mgwfbp_iteration_t **out);
+int mgwfbp_iteration_replay(mgwfbp_iteration_t *iteration, void *hip_stream, double *t_iter_ms);
+void mgwfbp_iteration_destroy(mgwfbp_iteration_t *iteration);
 
 /*
  * Bandwidth probes used to calibrate measurements; they are not part of the method.

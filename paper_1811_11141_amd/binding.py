@@ -25,7 +25,8 @@ EXPORTS = [
     "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update",
-    "mgwfbp_run_iteration", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
+    "mgwfbp_run_iteration", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
+    "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
 
@@ -62,6 +63,10 @@ def _load() -> C.CDLL:
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
         getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
     lib.mgwfbp_run_iteration.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(f64), P(f64), P(f64), P(f64)]
+    lib.mgwfbp_iteration_capture.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, P(vp)]
+    lib.mgwfbp_iteration_replay.argtypes = [vp, vp, P(f64)]
+    lib.mgwfbp_iteration_destroy.argtypes = [vp]
+    lib.mgwfbp_iteration_destroy.restype = None
     lib.mgwfbp_pack_reduce.argtypes = [vp, i32, vp, sz, vp]
     lib.mgwfbp_unpack_update.argtypes = [vp, i32, vp, sz, i32, f32, f32, vp]
     lib.mgwfbp_fit_cost.argtypes = [i32, P(f64), P(f64), P(f64), P(f64)]
@@ -75,7 +80,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_last_error.argtypes = []
     lib.mgwfbp_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("mgwfbp_plan_destroy", "mgwfbp_last_error"):
+        if name not in ("mgwfbp_plan_destroy", "mgwfbp_iteration_destroy", "mgwfbp_last_error"):
             getattr(lib, name).restype = i32
     return lib
 
@@ -260,11 +265,49 @@ class Plan:
         return {"group_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
                 "t_iter_ms": t_iter.value}
 
+    def capture_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
+                          lr: float = 0.0, momentum: float = 0.0) -> "IterationGraph":
+        """The iteration of run_iteration captured into a HIP graph (see mgwfbp_iteration_capture)."""
+        tb = None if tb_ms is None else np.ascontiguousarray(tb_ms, dtype=np.float64)
+        if tb is not None and tb.shape != (self.L,):
+            raise ValueError("tb_ms must have L entries")
+        h = C.c_void_p()
+        _check(_lib.mgwfbp_iteration_capture(
+            self._h, None if tb is None else tb.ctypes.data_as(C.POINTER(C.c_double)), int(update), lr,
+            momentum, C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)), C.byref(h)))
+        return IterationGraph(h.value, self)
+
     def destroy(self) -> None:
         if self._h:
             _lib.mgwfbp_plan_destroy(self._h)
             self._h = C.c_void_p(0)
             self._keep = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class IterationGraph:
+    """Owner of one mgwfbp_iteration_t handle; keeps its plan alive."""
+
+    def __init__(self, handle: int, plan: Plan):
+        self._h = C.c_void_p(handle)
+        self._plan = plan
+
+    def replay(self, stream=None, measure: bool = True):
+        """Launch the graph; with measure=True wait and return t_iter in ms, else return None."""
+        t = C.c_double()
+        _check(_lib.mgwfbp_iteration_replay(self._h, C.c_void_p(_stream(stream)),
+                                            C.byref(t) if measure else None))
+        return t.value if measure else None
+
+    def destroy(self) -> None:
+        if self._h:
+            _lib.mgwfbp_iteration_destroy(self._h)
+            self._h = C.c_void_p(0)
 
     def __del__(self):
         try:

@@ -10,6 +10,8 @@
 // enforced by the hardware queues, not by host threads.
 #include <hip/hip_runtime_api.h>
 
+#include <cmath>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -46,10 +48,9 @@ int hip_fail(const char *what, hipError_t e)
 
 }  // namespace
 
-extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
-                                    float momentum, void *compute_stream, void *comm_stream,
-                                    double *group_ready_ms, double *group_start_ms,
-                                    double *group_finish_ms, double *t_iter_ms)
+namespace {
+
+int check_iteration_args(mgwfbp_plan_t *pl, const double *tb, int32_t update)
 {
     if (!pl) {
         set_error("plan is NULL");
@@ -63,15 +64,72 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
         set_error(update ? "w[] and v[] are not bound" : "out[] is not bound");
         return MGWFBP_ESTATE;
     }
-    const int32_t L = pl->L;
-    const size_t G = pl->groups.size();
-    const double *tb = tb_ms ? tb_ms : pl->tb.data();
-    for (int32_t l = 0; l < L; ++l) {
+    for (int32_t l = 0; l < pl->L; ++l) {
         if (!(tb[l] >= 0.0) || tb[l] > 1.0e4) {
             set_error("tb_ms[" + std::to_string(l) + "] must be in [0, 10000] ms");
             return MGWFBP_EINVAL;
         }
     }
+    return MGWFBP_OK;
+}
+
+// Enqueue one iteration on the two streams: gate (publishes time zero in the plan's clock word 0),
+// then per group a backward stand-in on `cs`, an event, and the group's reduction on `ms` behind
+// that event; finally word 1 of the clock gets the device time at which the last group ended.
+// g_start / g_finish may be NULL (no per-group timestamps).
+int enqueue_iteration(mgwfbp_plan_t *pl, const double *tb, bool update, float lr, float momentum,
+                      hipStream_t cs, hipStream_t ms, double gate_ms, hipEvent_t base,
+                      const std::vector<hipEvent_t> &g_ready, const std::vector<hipEvent_t> *g_start,
+                      const std::vector<hipEvent_t> *g_finish)
+{
+    int rc;
+    if ((rc = launch_spin(gate_ms, cs, pl->d_clock))) return rc;
+    // the communication stream must not start before the backward pass does
+    hipError_t e = hipEventRecord(base, cs);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    if ((e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+
+    // Backward pass, highest layer first.  Only the moment a group's lowest layer finishes
+    // matters to the communication side, so the layers of a group share one stand-in kernel
+    // that ends when the backward pass has reached the end of the group's lowest layer.
+    double elapsed_ms = 0.0;
+    for (int32_t l = pl->L - 1; l >= 0; --l) {
+        elapsed_ms += tb[l];
+        if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
+        // layer l is the lowest layer of its group: the group's gradients are complete
+        const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
+        if ((rc = launch_spin_until(elapsed_ms, pl->d_clock, cs))) return rc;
+        if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) return hip_fail("hipEventRecord", e);
+        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+        if (g_start && (e = hipEventRecord((*g_start)[k], ms)) != hipSuccess) return hip_fail("hipEventRecord", e);
+        if ((rc = run_scope(pl, static_cast<int32_t>(k), update, lr, momentum, nullptr, 0, ms))) return rc;
+        if (g_finish && (e = hipEventRecord((*g_finish)[k], ms)) != hipSuccess) return hip_fail("hipEventRecord", e);
+    }
+    // groups run in order on the communication stream: its end is the end of the iteration (Eq. 8)
+    return launch_spin(0.0, ms, pl->d_clock + 1);
+}
+
+// (clock word 1 - clock word 0) in milliseconds, after the streams have drained.
+int read_t_iter(const mgwfbp_plan_t *pl, double *t_iter_ms)
+{
+    uint64_t words[2] = {0, 0};
+    const hipError_t e = hipMemcpy(words, pl->d_clock, sizeof(words), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail("hipMemcpy of the clock words", e);
+    *t_iter_ms = static_cast<double>(words[1] - words[0]) / static_cast<double>(wall_clock_khz());
+    return MGWFBP_OK;
+}
+
+}  // namespace
+
+extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                    float momentum, void *compute_stream, void *comm_stream,
+                                    double *group_ready_ms, double *group_start_ms,
+                                    double *group_finish_ms, double *t_iter_ms)
+{
+    const double *tb = tb_ms ? tb_ms : (pl ? pl->tb.data() : nullptr);
+    int rc = check_iteration_args(pl, tb, update);
+    if (rc) return rc;
+    const size_t G = pl->groups.size();
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);
     hipStream_t ms = static_cast<hipStream_t>(comm_stream);
 
@@ -80,10 +138,9 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
     const bool time_ready = group_ready_ms != nullptr;
     const bool time_comm = group_start_ms != nullptr || group_finish_ms != nullptr;
     Events pool;
-    hipEvent_t base, done;
+    hipEvent_t base;
     std::vector<hipEvent_t> g_ready(G), g_start(time_comm ? G : 0), g_finish(time_comm ? G : 0);
-    int rc = pool.make(&base);
-    if (!rc) rc = pool.make(&done);
+    rc = pool.make(&base);
     for (size_t k = 0; k < G && !rc; ++k) {
         rc = pool.make(&g_ready[k], time_ready);
         if (!rc && time_comm) rc = pool.make(&g_start[k]);
@@ -100,43 +157,8 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
     // (time zero + the backward time accumulated so far), so launch gaps between stand-ins do
     // not stretch the backward pass.
     if ((rc = launch_spin(0.0, cs))) return rc;
-    if ((rc = launch_spin(1.0 + 0.06 * static_cast<double>(G), cs, pl->d_clock))) return rc;
-    // the communication stream must not start before the backward pass does
-    hipError_t e = hipEventRecord(base, cs);
-    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
-    if ((e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
-
-    // Backward pass, highest layer first.  Only the moment a group's lowest layer finishes
-    // matters to the communication side, so the layers of a group share one stand-in kernel
-    // that ends when the backward pass has reached the end of the group's lowest layer.
-    double elapsed_ms = 0.0;
-    for (int32_t l = L - 1; l >= 0; --l) {
-        elapsed_ms += tb[l];
-        if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
-        // layer l is the lowest layer of its group: the group's gradients are complete
-        const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
-        if ((rc = launch_spin_until(elapsed_ms, pl->d_clock, cs))) break;
-        if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) {
-            rc = hip_fail("hipEventRecord", e);
-            break;
-        }
-        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess) {
-            rc = hip_fail("hipStreamWaitEvent", e);
-            break;
-        }
-        if (time_comm && (e = hipEventRecord(g_start[k], ms)) != hipSuccess) {
-            rc = hip_fail("hipEventRecord", e);
-            break;
-        }
-        if ((rc = run_scope(pl, static_cast<int32_t>(k), update != 0, lr, momentum, nullptr, 0, ms)))
-            break;
-        if (time_comm && (e = hipEventRecord(g_finish[k], ms)) != hipSuccess) {
-            rc = hip_fail("hipEventRecord", e);
-            break;
-        }
-    }
-    // groups run in order on the communication stream: its end is the end of the iteration (Eq. 8)
-    if (!rc && (e = hipEventRecord(done, ms)) != hipSuccess) rc = hip_fail("hipEventRecord", e);
+    rc = enqueue_iteration(pl, tb, update != 0, lr, momentum, cs, ms, 1.0 + 0.06 * static_cast<double>(G),
+                           base, g_ready, time_comm ? &g_start : nullptr, time_comm ? &g_finish : nullptr);
     // whatever was enqueued must drain before the events are destroyed or read
     const hipError_t e1 = hipStreamSynchronize(cs);
     const hipError_t e2 = hipStreamSynchronize(ms);
@@ -164,8 +186,107 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
             if (group_finish_ms) group_finish_ms[k] = t;
         }
     }
-    double total = 0.0;
-    if ((rc = since_base(done, &total))) return rc;
-    if (t_iter_ms) *t_iter_ms = total;
+    if (t_iter_ms) return read_t_iter(pl, t_iter_ms);
     return MGWFBP_OK;
+}
+
+// ---- the same iteration as a HIP graph -------------------------------------------------------
+
+struct mgwfbp_iteration_s {
+    mgwfbp_plan_t *plan = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+extern "C" int mgwfbp_iteration_capture(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                        float momentum, void *compute_stream, void *comm_stream,
+                                        mgwfbp_iteration_t **out)
+{
+    if (!out) {
+        set_error("out is NULL");
+        return MGWFBP_EINVAL;
+    }
+    *out = nullptr;
+    const double *tb = tb_ms ? tb_ms : (pl ? pl->tb.data() : nullptr);
+    int rc = check_iteration_args(pl, tb, update);
+    if (rc) return rc;
+    if (update && (!std::isfinite(lr) || !std::isfinite(momentum))) {
+        set_error("lr and momentum must be finite");
+        return MGWFBP_EINVAL;
+    }
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    hipStream_t ms = static_cast<hipStream_t>(comm_stream);
+    if (!cs || !ms || cs == ms) {
+        set_error("capture needs two different non-default streams");
+        return MGWFBP_EINVAL;
+    }
+    const size_t G = pl->groups.size();
+    Events pool;  // the graph keeps the dependencies, not the events: they go when this call ends
+    hipEvent_t base, done;
+    std::vector<hipEvent_t> g_ready(G);
+    rc = pool.make(&base, false);
+    if (!rc) rc = pool.make(&done, false);
+    for (size_t k = 0; k < G && !rc; ++k) rc = pool.make(&g_ready[k], false);
+    if (rc) return rc;
+    // load the code of every kernel the graph will hold before capturing (a first launch may
+    // allocate, which capture forbids): one eager pass of the stand-in and of each group
+    if ((rc = launch_spin(0.0, cs))) return rc;
+    hipError_t e = hipStreamSynchronize(cs);
+    if (e != hipSuccess) return hip_fail("hipStreamSynchronize", e);
+
+    mgwfbp_iteration_t *it = new (std::nothrow) mgwfbp_iteration_t();
+    if (!it) {
+        set_error("out of host memory");
+        return MGWFBP_ENOMEM;
+    }
+    it->plan = pl;
+    if ((e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal)) != hipSuccess) {
+        delete it;
+        return hip_fail("hipStreamBeginCapture", e);
+    }
+    // A short gate only: replaying a graph needs no head start for the host, but time zero still
+    // has to be published by a kernel that precedes every stand-in.
+    rc = enqueue_iteration(pl, tb, update != 0, lr, momentum, cs, ms, 0.05, base, g_ready, nullptr, nullptr);
+    // join the communication stream back into the capturing stream (also on failure, so that
+    // the capture can end and both streams stay usable)
+    hipError_t ej = hipEventRecord(done, ms);
+    if (ej == hipSuccess) ej = hipStreamWaitEvent(cs, done, 0);
+    e = hipStreamEndCapture(cs, &it->graph);
+    if (rc == MGWFBP_OK && ej != hipSuccess) rc = hip_fail("joining the captured streams", ej);
+    if (rc == MGWFBP_OK && e != hipSuccess) rc = hip_fail("hipStreamEndCapture", e);
+    if (rc == MGWFBP_OK && (e = hipGraphInstantiate(&it->exec, it->graph, nullptr, nullptr, 0)) != hipSuccess)
+        rc = hip_fail("hipGraphInstantiate", e);
+    if (rc) {
+        if (it->graph) (void)hipGraphDestroy(it->graph);
+        delete it;
+        return rc;
+    }
+    *out = it;
+    return MGWFBP_OK;
+}
+
+extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream, double *t_iter_ms)
+{
+    if (!it || !it->exec) {
+        set_error("iteration handle is NULL");
+        return MGWFBP_EINVAL;
+    }
+    if (!it->plan->bound) {
+        set_error("the plan was re-bound or destroyed after the capture");
+        return MGWFBP_ESTATE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipGraphLaunch(it->exec, s);
+    if (e != hipSuccess) return hip_fail("hipGraphLaunch", e);
+    if (!t_iter_ms) return MGWFBP_OK;
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail("hipStreamSynchronize", e);
+    return read_t_iter(it->plan, t_iter_ms);
+}
+
+extern "C" void mgwfbp_iteration_destroy(mgwfbp_iteration_t *it)
+{
+    if (!it) return;
+    if (it->exec) (void)hipGraphExecDestroy(it->exec);
+    if (it->graph) (void)hipGraphDestroy(it->graph);
+    delete it;
 }

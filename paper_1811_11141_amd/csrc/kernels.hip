@@ -858,7 +858,6 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
     return check_launch("unpack kernel launch");
 }
 
-namespace {
 // s_memrealtime counts at a constant 100 MHz on this family; ask the runtime to be sure
 int wall_clock_khz()
 {
@@ -874,6 +873,7 @@ int wall_clock_khz()
     return khz;
 }
 
+namespace {
 int spin(double ms, uint64_t *clock, int mode, void *stream)
 {
     if (!(ms > 0.0)) ms = 0.0;

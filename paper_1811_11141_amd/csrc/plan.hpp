@@ -98,7 +98,7 @@ struct mgwfbp_plan_s {
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
-    uint64_t *d_clock = nullptr;  // one word at its end: time origin of mgwfbp_run_iteration
+    uint64_t *d_clock = nullptr;  // two words at its end: device clock at the start and at the end of an iteration
     mgwfbp::DeviceTables dt;
 };
 
@@ -143,6 +143,7 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
 // end; or wait until `deadline_ms` after the published clock value.
 int launch_spin(double ms, void *stream, uint64_t *publish_clock = nullptr);
 int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream);
+int wall_clock_khz();  // ticks per millisecond of the device clock the stand-ins read
 int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
 int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
                          float *dst, void *stream);

@@ -10,7 +10,8 @@
 2. Schedule: plan with the fitted (a, b), run one event-driven iteration (mgwfbp_run_iteration,
    Algorithm 2 on two streams with timed stand-ins for the backward pass) for the no-merging,
    single-group, Theorem-1 and optimal plans, and compare the measured end of the last group
-   with the iteration time the model predicts (Eq. 8).
+   with the iteration time the model predicts (Eq. 8); the same iteration is also replayed
+   from a HIP graph (mgwfbp_iteration_capture).
 
 Only argument marshalling and timing happen here; all device work is in the library.
 """
@@ -131,12 +132,17 @@ def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: floa
         pl.run_iteration(s_comp, s_comm)                      # warm-up
         t = [pl.run_iteration(s_comp, s_comm) for _ in range(reps)]
         light = np.array([pl.run_iteration(s_comp, s_comm, timeline=False)["t_iter_ms"] for _ in range(reps)])
+        it = pl.capture_iteration(s_comp, s_comm)
+        it.replay(s_comp)                                     # warm-up
+        graph = np.array([it.replay(s_comp) for _ in range(reps)])
+        it.destroy()
         meas = np.array([x["t_iter_ms"] for x in t])
         bwd = np.array([x["group_ready_ms"][-1] for x in t])
         inf = pl.info()
         out["plans"][name] = {"groups": inf["n_groups"], "predicted_t_iter_ms": inf["t_iter_ms"],
                               "measured_t_iter_ms": float(np.median(meas)),
                               "measured_t_iter_without_timestamps_ms": float(np.median(light)),
+                              "measured_t_iter_graph_replay_ms": float(np.median(graph)),
                               "measured_backward_ms": float(np.median(bwd)),
                               "not_overlapped_ms": float(np.median(meas - bwd))}
         pl.destroy()

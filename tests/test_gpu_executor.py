@@ -91,6 +91,84 @@ def test_iteration_needs_binding(mg):
     assert tl["t_iter_ms"] > 0.09
 
 
+@pytest.mark.parametrize("update", [False, True])
+def test_iteration_graph_replays(mg, update):
+    """The iteration captured into a HIP graph: every replay, with fresh gradients copied in
+    eagerly between replays, gives the oracle's values, and its device-clock t_iter agrees with
+    the eager executor's and with Eq. 8's lower bound (the backward pass itself)."""
+    seed = 5
+    w = wl.tiny_workload(seed, L=10)
+    tb = w.tb_ms * 0.3
+    pl = mg.mgwfbp_plan(w.p, tb, 0.0, 0.1, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    groups = pl.groups()
+    grads = wl.make_gradients(w, seed, "cuda")
+    out = [torch.zeros_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, seed, "cuda")
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    s_comp, s_comm, s_run = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    it = pl.capture_iteration(s_comp, s_comm, update=update, lr=0.1, momentum=0.9)
+    torch.cuda.synchronize()
+    # nothing ran during capture
+    assert all(float(t.abs().sum()) == 0.0 for t in out)
+    times = []
+    for rep in range(4):
+        fresh = wl.make_gradients(w, 700 + rep, "cuda")
+        for g in range(w.n_workers):
+            for l in range(w.L):
+                grads[g][l].copy_(fresh[g][l])
+        for t in out:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        times.append(it.replay(s_run))
+        g_np = [to_np(r) for r in grads]
+        if update:
+            exp = od.merged_gradient_path(g_np, groups, w_np, v_np, lr=0.1, mu=0.9)
+        else:
+            exp = od.merged_gradient_path(g_np, groups)
+        for l in range(w.L):
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), (rep, l)
+            if update:
+                assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32))
+                assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32))
+    # asynchronous replay
+    assert it.replay(s_run, measure=False) is None
+    torch.cuda.synchronize()
+    if update:
+        od.merged_gradient_path([to_np(r) for r in grads], groups, w_np, v_np, lr=0.1, mu=0.9)
+        assert np.array_equal(wt[0].cpu().numpy().view(np.uint32), w_np[0].view(np.uint32))
+    backward = float(tb.sum())
+    eager = pl.run_iteration(s_comp, s_comm, update=False, timeline=False)["t_iter_ms"] if not update else None
+    for t in times:
+        assert backward - 5e-3 <= t <= backward + 0.2, (t, backward)
+        if eager is not None:
+            assert abs(t - eager) < 0.05, (t, eager)
+    it.destroy()
+    # streams used for the capture are ordinary streams again
+    pl.pack_reduce_unpack(stream=s_comp)
+    torch.cuda.synchronize()
+
+
+def test_iteration_graph_argument_errors(mg):
+    w = wl.custom_workload([100, 200], 2)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, 0.5, 1e-6, 2, mg.MODE_WFBP)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.capture_iteration(s1, s2)
+    assert ei.value.code == mg.ESTATE                      # not bound
+    grads = wl.make_gradients(w, 1, "cuda")
+    pl.bind(grads, [torch.empty_like(t) for t in grads[0]])
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.capture_iteration(s1, s1)                       # fork and join need two streams
+    assert ei.value.code == mg.EINVAL
+    with pytest.raises(mg.MgwfbpError):
+        pl.capture_iteration(s1, s2, update=True)          # no w, v
+    it = pl.capture_iteration(s1, s2, tb_ms=[0.05, 0.05])
+    assert it.replay(s1) >= 0.095
+    it.destroy()
+
+
 def test_calibrated_schedule_ranks_plans_like_the_model(mg):
     """Fit (a, b) on this machine from the schedule itself, then run the four plans with a short
     backward pass: no merging must be the slowest by far, and the model must rank the optimal
