@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "googlenet", "alexnet", "vgg16"])
     ap.add_argument("--a-ms", type=float, default=0.5)
+    ap.add_argument("--n-workers", type=int, default=0, help="replicas N (0 = the workload's own: 8, VGG-16 16)")
     ap.add_argument("--mode", default="optimal", choices=["optimal", "greedy", "wfbp", "single"])
     ap.add_argument("--sets", type=int, default=0, help="gradient sets to rotate over (0 = auto)")
     ap.add_argument("--tile", type=int, default=0)
@@ -76,7 +77,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
-    w = wl.cnn_workload(args.workload, a_ms=args.a_ms)
+    w = wl.cnn_workload(args.workload, a_ms=args.a_ms, n_workers=args.n_workers or None)
     N, P, L = w.n_workers, w.P, w.L
     mode = {"optimal": mg.MODE_OPTIMAL, "greedy": mg.MODE_PAPER_GREEDY, "wfbp": mg.MODE_WFBP,
             "single": mg.MODE_SINGLE}[args.mode]

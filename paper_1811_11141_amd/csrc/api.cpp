@@ -64,7 +64,6 @@ int make_plan(int32_t L, const uint64_t *p, const double *tb, double tf, double 
         pl->merged.assign(L, 0);
         // 8 float4 per lane and worker in the fused kernel
         pl->opt.tile_elems = 4096;
-        pl->opt.pace = N >= 16 ? 4 : 1;
     } catch (const std::bad_alloc &) {
         delete pl;
         return fail(MGWFBP_ENOMEM, "out of host memory");
@@ -269,7 +268,7 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
         pl->opt.nontemporal = static_cast<int>(value);
         return MGWFBP_OK;
     case MGWFBP_OPT_PACE:
-        if (value < 0 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [0, 16]");
+        if (value < -1 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [-1, 16]");
         pl->opt.pace = static_cast<int>(value);
         return MGWFBP_OK;
     default: return fail(MGWFBP_EINVAL, "unknown option key");

@@ -767,9 +767,30 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
 
 }  // namespace
 
+namespace {
+// Pause between two loads of a wave (MGWFBP_OPT_PACE; -1 = chosen here).  Measured on MI355X:
+// a launch of a few thousand workgroups (ResNet-50, GoogLeNet sized) is fastest with almost no
+// pause, because a slower workgroup lengthens the partly filled last batch; long launches gain
+// from thinning the request stream (AlexNet sized, N = 8: +2.5 % at 12; VGG-16 sized: N = 16
+// +4 % at 8, N = 8 +5 % at 12-16).  The update kernel pauses only in its gradient phase and
+// peaks earlier (4).  Copies (pack, unpack) keep the small values they were tuned with.
+enum class Stream { reduce, update, copy };
+int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
+{
+    if (pl.opt.pace >= 0) return pl.opt.pace;
+    const bool long_launch = workgroups >= 8192;
+    switch (kind) {
+    case Stream::reduce: return !long_launch ? 2 : pl.N >= 16 ? 8 : 12;
+    case Stream::update: return !long_launch ? 2 : 4;
+    default: return pl.N >= 16 ? 4 : 1;
+    }
+}
+}  // namespace
+
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
                  void *stream, float *merged_out)
 {
+    const int pace = pace_for(pl, step ? Stream::update : Stream::reduce, sc.n_tiles);
     const uint64_t base_off = sc.base_off;
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -781,11 +802,11 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     // the launch cannot saturate HBM with one load per wave and is bound by latency instead
     const bool deep = sc.n_tiles < 2048;
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
-        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
+        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
-        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pl.opt.pace, merged_out, base_off);
+        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     }
     return check_launch("fused kernel launch");
 }
@@ -799,7 +820,7 @@ int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint6
     const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
     const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));
     const bool deep = static_cast<uint64_t>(sc.n_tiles) * pl.N < 2048;
-    const int pace = pl.opt.pace;
+    const int pace = pace_for(pl, Stream::copy, sc.n_tiles);
     if (!pl.opt.nontemporal) {
         k_pack<false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off, pace);
     } else {
@@ -821,14 +842,15 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int u = static_cast<int>(tile / (kBlock * 4));
     const bool deep = grid.x < 2048;
+    const int pace = pace_for(pl, Stream::reduce, grid.x);
     const bool nt = pl.opt.nontemporal != 0;
     switch (pl.N) {
-    case 1: reduce_launch<1>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
-    case 2: reduce_launch<2>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
-    case 4: reduce_launch<4>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
-    case 8: reduce_launch<8>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
-    case 16: reduce_launch<16>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
-    default: reduce_launch<0>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pl.opt.pace); break;
+    case 1: reduce_launch<1>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
+    case 2: reduce_launch<2>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
+    case 4: reduce_launch<4>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
+    case 8: reduce_launch<8>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
+    case 16: reduce_launch<16>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
+    default: reduce_launch<0>(nt, u, deep, grid, s, ws, epad, sc.elems, tile, pl.N, inv_n, pace); break;
     }
     return check_launch("reduce kernel launch");
 }
@@ -844,7 +866,7 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
     // a single read stream: eight loads in flight per wave beat one at any launch size
     // (measured: scatter +6 %, with the update +1.5 %); with N streams it is the other way round
     const bool deep = true;
-    const int pace = pl.opt.pace;
+    const int pace = pace_for(pl, Stream::copy, sc.n_tiles);
     if (!pl.opt.nontemporal) {
         if (step) k_unpack<true, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
         else k_unpack<false, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);

@@ -59,7 +59,7 @@ struct Options {
     uint32_t tile_elems = 4096;
     uint32_t small_elems = 512;
     int nontemporal = 1;
-    int pace = 1;
+    int pace = -1;  // -1: chosen per launch from its size and N
 };
 
 struct GroupInfo {
