@@ -68,8 +68,11 @@ enum {
     MGWFBP_OPT_TILE_ELEMS = 1,  /* elements of one layer handled by one workgroup; multiple of 1024, <= 8192 */
     MGWFBP_OPT_SMALL_ELEMS = 2, /* layers shorter than this share gather tiles                      */
     MGWFBP_OPT_NONTEMPORAL = 3, /* 1: streaming (non-temporal) loads and stores; 0: plain            */
-    MGWFBP_OPT_PACE = 4         /* pause between two loads of a wave, units of ~64 clocks, 0..16;
+    MGWFBP_OPT_PACE = 4,        /* pause between two loads of a wave, units of ~64 clocks, 0..16;
                                    -1 (default): chosen per launch from its size and N           */
+    MGWFBP_OPT_LONG_TILES = 5   /* whole-plan fused reduce pass on tiles of 2 * tile_elems (only for
+                                   tile_elems = 4096): 1 always, 0 never, -1 (default) when that puts
+                                   every workgroup on the chip at once and tile_elems does not      */
 };
 
 /*
@@ -137,7 +140,8 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             list, tile length.  segment count 1: `start` is the element offset inside that segment;
  *             more than one: the tile gathers whole short segments and `start` is its offset
  *             in the plan-wide merged order.  list 0: the per-group lists (group after group);
- *             list 1: the second copy used by whole-plan launches.  tile length: elements of a
+ *             list 1: the second copy used by whole-plan launches; list 2 (when built): the
+ *             whole plan in double-length tiles (MGWFBP_OPT_LONG_TILES).  tile length: elements of a
  *             full tile in that list (a group launched alone is cut into shorter tiles than
  *             the whole plan when it would otherwise give too few workgroups).
  *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)

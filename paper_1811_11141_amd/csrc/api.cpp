@@ -87,7 +87,8 @@ void release_device(mgwfbp_plan_t *pl)
     pl->bound = false;
 }
 
-int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
+// long_ok: the caller's kernel has the double-length fast path (the fused pass without update)
+int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_ok = false)
 {
     if (group < -1 || group >= static_cast<int32_t>(pl->groups.size()))
         return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
@@ -98,6 +99,11 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc)
         sc.base_off = 0;
         sc.tile_elems = pl->opt.tile_elems;
         sc.needs_lds = pl->all_needs_lds;
+        if (long_ok && pl->long_tile_count) {
+            sc.tile_begin = pl->long_tile_begin;
+            sc.n_tiles = pl->long_tile_count;
+            sc.tile_elems = pl->long_tile_elems;
+        }
     } else {
         const GroupInfo &g = pl->groups[group];
         sc.tile_begin = g.tile_begin;
@@ -146,7 +152,7 @@ int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, v
     if (step && (!std::isfinite(lr) || !std::isfinite(mu)))
         return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
     LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = scope_of(pl, group, sc, !ws && !step))) return rc;
     if (!ws) {
         if (bytes != 0) return fail(MGWFBP_EINVAL, "workspace is NULL but workspace_bytes != 0");
         return launch_fused(*pl, sc, step, lr, mu, stream);
@@ -271,6 +277,10 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
         if (value < -1 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [-1, 16]");
         pl->opt.pace = static_cast<int>(value);
         return MGWFBP_OK;
+    case MGWFBP_OPT_LONG_TILES:
+        if (value < -1 || value > 1) return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0 or 1");
+        pl->opt.long_tiles = static_cast<int>(value);
+        return MGWFBP_OK;
     default: return fail(MGWFBP_EINVAL, "unknown option key");
     }
 }
@@ -311,6 +321,10 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
                 r[0] = t.seg; r[1] = t.nseg; r[2] = t.start; r[3] = t.n;
                 r[4] = i >= tmp.all_tile_begin ? 1 : 0;
                 r[5] = tmp.opt.tile_elems;
+                if (tmp.long_tile_count && i >= tmp.long_tile_begin) {
+                    r[4] = 2;
+                    r[5] = tmp.long_tile_elems;
+                }
                 if (!r[4])
                     for (const GroupInfo &g : tmp.groups)
                         if (i >= g.tile_begin && i < g.tile_end) r[5] = g.tile_elems;
@@ -475,7 +489,7 @@ int mgwfbp_pack_reduce(mgwfbp_plan_t *pl, int32_t group, void *merged, size_t me
     int rc = check_bound(pl, false, false);
     if (rc) return rc;
     LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
+    if ((rc = scope_of(pl, group, sc, true))) return rc;
     if ((rc = check_merged(sc, merged, merged_bytes))) return rc;
     return launch_fused(*pl, sc, false, 0.0f, 0.0f, hip_stream, static_cast<float *>(merged));
 }

@@ -322,10 +322,12 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
     // Lane offset of piece 0 (+BIAS); piece u sits u KiB further on, which the load and store
     // instructions add as their immediate offset (13 bits, signed: -4096 .. 4095), so one
     // register addresses the whole tile.  Each wave walks its own contiguous U KiB.
+    // Pieces 8 and up (U = 16) sit 8 KiB further on: the scalar base is moved instead.
     constexpr int BIAS = U * 1024 > 4096 ? 4096 : 0;
-    static_assert(U * 1024 - 1024 - BIAS <= 4095 && -BIAS >= -4096, "piece offsets must fit the immediate");
+    static_assert(U <= 8 || U == 16, "piece offsets must fit the immediate");
     const uint32_t vo = (threadIdx.x >> 6) * (U * 1024u) + (threadIdx.x & 63u) * 16u + BIAS;
-#define MGWFBP_OFF(u) ((u) * 1024 - BIAS)
+#define MGWFBP_OFF(u) (((u) % 8) * 1024 - BIAS)
+#define MGWFBP_HI(u) (((u) / 8) * 8192)
     v4f res[U];
     if constexpr (D == 1) {
         static_for<NW>([&](auto gc) {
@@ -336,7 +338,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
                 // the load is ordered after the previous add through its operand res[..]
                 v4f x;
                 if constexpr (g == 0 && u == 0) x = ld_stream<MGWFBP_OFF(u)>(sb, vo);
-                else x = ld_stream_after<MGWFBP_OFF(u)>(sb, vo, res[u == 0 ? U - 1 : u - 1]);
+                else x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
                 wait_all_loads(x);
                 if constexpr (g == 0) res[u] = x;
                 else res[u] = res[u] + x;
@@ -354,7 +356,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
         v4f x[DD];
         static_for<DD>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            x[j] = ld_stream<MGWFBP_OFF(j % U)>(sb[j / U], vo);
+            x[j] = ld_stream<MGWFBP_OFF(j % U)>(sb[j / U] + MGWFBP_HI(j % U), vo);
         });
         static_for<T>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -366,7 +368,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             // the next load re-uses the slot just consumed; naming res[u] as an operand keeps
             // the add above ahead of it, so no more than DD loaded values are ever live
             if constexpr (j + DD < T)
-                x[j % DD] = ld_stream_after<MGWFBP_OFF((j + DD) % U)>(sb[(j + DD) / U], vo, res[u]);
+                x[j % DD] = ld_stream_after<MGWFBP_OFF((j + DD) % U)>(sb[(j + DD) / U] + MGWFBP_HI((j + DD) % U), vo, res[u]);
         });
     }
     if constexpr (SCALE) {
@@ -383,17 +385,17 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             v4f w[UB], v[UB];
             static_for<UB>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                w[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(wb, vo, res[u0 + k]);
+                w[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(wb + MGWFBP_HI(u0 + k), vo, res[u0 + k]);
                 wait_all_loads(w[k]);
-                v[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(vb, vo, w[k]);
+                v[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(vb + MGWFBP_HI(u0 + k), vo, w[k]);
                 wait_all_loads(v[k]);
             });
 #pragma unroll
             for (int k = 0; k < UB; ++k) sgd_momentum(res[u0 + k], w[k], v[k], lr, mu);
             static_for<UB>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(vb), vo, v[k]);
-                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(wb), vo, w[k]);
+                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(vb) + MGWFBP_HI(u0 + k), vo, v[k]);
+                st_stream<MGWFBP_OFF(u0 + k)>(const_cast<char *>(wb) + MGWFBP_HI(u0 + k), vo, w[k]);
             });
         });
     }
@@ -402,10 +404,11 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
         char *ob = const_cast<char *>(scalar_ptr(outp));
         static_for<U>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
-            st_stream<MGWFBP_OFF(u)>(ob, vo, res[u]);
+            st_stream<MGWFBP_OFF(u)>(ob + MGWFBP_HI(u), vo, res[u]);
         });
     }
 #undef MGWFBP_OFF
+#undef MGWFBP_HI
 }
 
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
@@ -719,6 +722,9 @@ void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTabl
         if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
         if (u == 8) { if (deep) MGWFBP_LAUNCH(8, 8); else MGWFBP_LAUNCH(8, 1); return; }
+        if constexpr (!STEP) {
+            if (u == 16) { if (deep) MGWFBP_LAUNCH(16, 8); else MGWFBP_LAUNCH(16, 1); return; }
+        }
     }
     MGWFBP_LAUNCH(0, 1);
 #undef MGWFBP_LAUNCH

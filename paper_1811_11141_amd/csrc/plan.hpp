@@ -60,6 +60,7 @@ struct Options {
     uint32_t small_elems = 512;
     int nontemporal = 1;
     int pace = -1;  // -1: chosen per launch from its size and N
+    int long_tiles = -1;  // whole-plan fused reduce on double-length tiles: -1 by rule, 0 never, 1 always
 };
 
 struct GroupInfo {
@@ -95,6 +96,9 @@ struct mgwfbp_plan_s {
     int device = -1;
     bool all_needs_lds = false;
     uint32_t all_tile_begin = 0, all_tile_count = 0;  // whole-plan ordering of the tiles
+    // third list: the whole plan cut into tiles of twice the length, for the fused reduce pass
+    // when that puts every workgroup on the chip at once (0 tiles = not built)
+    uint32_t long_tile_begin = 0, long_tile_count = 0, long_tile_elems = 0;
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table

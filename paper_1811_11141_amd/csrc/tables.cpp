@@ -24,7 +24,9 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     // elements one gather tile may hold: a few per lane, since each costs a table search;
     // small <= tile, so no tile of any kind exceeds tile_elems (the LDS staging size)
     const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
-    std::vector<TileDev> all_slow, all_full;
+    std::vector<TileDev> all_slow, all_full, long_slow, long_full;
+    // double-length tiles exist for 16 pieces per lane only (8192 elements)
+    const uint32_t long_tile = tile == 4096 && pl.opt.long_tiles != 0 ? 8192u : 0u;
 
     pl.segs.clear();
     pl.tiles.clear();
@@ -128,6 +130,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         pl.tiles.insert(pl.tiles.end(), full.begin(), full.end());
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
         cut(tile, all_slow, all_full);
+        if (long_tile) cut(long_tile, long_slow, long_full);
         pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
     }
     // A second copy of the tile list for whole-plan launches: every slow tile of every group
@@ -136,6 +139,22 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     pl.tiles.insert(pl.tiles.end(), all_slow.begin(), all_slow.end());
     pl.tiles.insert(pl.tiles.end(), all_full.begin(), all_full.end());
     pl.all_tile_count = static_cast<uint32_t>(all_slow.size() + all_full.size());
+    // A third copy in double-length tiles.  A workgroup lives for as long as its chain of
+    // N * (pieces per lane) dependent loads, tens of microseconds, so a launch of a few
+    // batches of workgroups ends with a partly filled batch that costs almost a full one.  When
+    // the double-length tiles put the whole launch on the chip at once (7 waves per SIMD fit:
+    // 3584 workgroups) and the ordinary tiles do not (more than 4096), the fused reduce pass
+    // uses this list; it is not long enough to keep the chip busy below 2048 workgroups.
+    pl.long_tile_begin = static_cast<uint32_t>(pl.tiles.size());
+    pl.long_tile_count = 0;
+    pl.long_tile_elems = long_tile;
+    const size_t n_long = long_slow.size() + long_full.size();
+    const bool by_rule = pl.all_tile_count > 4096 && n_long <= 3584 && n_long >= 2048;
+    if (long_tile && (pl.opt.long_tiles == 1 || by_rule)) {
+        pl.tiles.insert(pl.tiles.end(), long_slow.begin(), long_slow.end());
+        pl.tiles.insert(pl.tiles.end(), long_full.begin(), long_full.end());
+        pl.long_tile_count = static_cast<uint32_t>(n_long);
+    }
 }
 
 }  // namespace mgwfbp

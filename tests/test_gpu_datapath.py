@@ -154,6 +154,34 @@ def test_fused_tilings(mg, tile, small):
         assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
 
 
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 8, 16])
+def test_fused_double_length_tiles(mg, n_workers):
+    """The third tile list (tiles of 8192 elements, 16 pieces per lane) forced on: whole-plan
+    reduce pass and the pass into a merged buffer; sizes around the tile length, ragged tails."""
+    sizes = [8192 * 3, 8192 + 5, 8192, 8191, 4096, 70000, 300, 12, 8192 * 2 + 4096]
+    w = wl.custom_workload(sizes, n_workers, sigma=1e-2)
+    merged = [9, 8, 6, 5, 3]
+    groups = groups0(len(sizes), merged)
+    pl = make_plan(mg, w, merged)
+    pl.set_option(mg.OPT_LONG_TILES, 1)
+    assert int((pl.layout()["tiles"][:, 4] == 2).sum()) > 0
+    grads = wl.make_gradients(w, 77, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    pl.bind(grads, out)
+    pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    g_np = [to_np(r) for r in grads]
+    exp = od.merged_gradient_path(g_np, groups)
+    for l in range(len(sizes)):
+        assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
+    mb = merged_buffer(w.P)
+    pl.pack_reduce(mb)
+    torch.cuda.synchronize()
+    layers = [l for g in groups for l in g]
+    assert_same(mb[:w.P].cpu().numpy(), od.pack(exp, layers), "merged buffer")
+    assert bool(torch.isnan(mb[w.P:]).all())
+
+
 @pytest.mark.parametrize("nt,pace", [(0, 0), (1, 0), (1, 3)])
 def test_fused_options_do_not_change_results(mg, nt, pace):
     """Non-temporal on/off and the pacing of loads are performance knobs only."""
@@ -558,6 +586,7 @@ def test_random_shapes_all_entry_points(mg, seed):
     merged = random_merged(rng, L)
     groups = groups0(L, merged)
     pl = make_plan(mg, w, merged, tile=tile, small=small, nt=int(rng.integers(0, 2)))
+    pl.set_option(mg.OPT_LONG_TILES, int(rng.integers(-1, 2)))
     misalign = bool(rng.integers(0, 2))
     gen = torch.Generator(device="cuda").manual_seed(seed)
 

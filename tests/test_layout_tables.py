@@ -22,26 +22,32 @@ def expected_segments(p, merged):
     return rows
 
 
-def check_layout(p, merged, tile, small):
+def check_layout(p, merged, tile, small, long_tiles=-1):
     L = len(p)
     pl = mg.mgwfbp_plan_explicit(p, np.ones(L), 0.0, 0.5, 1e-6, 2, merged)
     pl.set_option(mg.OPT_TILE_ELEMS, tile)
     pl.set_option(mg.OPT_SMALL_ELEMS, small)
+    pl.set_option(mg.OPT_LONG_TILES, long_tiles)
     lay = pl.layout()
     segs, tiles = lay["segments"], lay["tiles"]
     exp = expected_segments(p, merged)
     assert [tuple(int(x) for x in r) for r in segs] == exp
     P = int(np.sum(p))
     small_eff = min(small, tile)
-    for which in (0, 1):                      # per-group lists, whole-plan list
+    lists = sorted({int(x) for x in tiles[:, 4]})
+    assert lists[:2] == [0, 1] and (2 in lists) == (long_tiles == 1 and tile == 4096)
+    for which in lists:                       # per-group lists, whole-plan list, double-length list
         cover = np.zeros(P, dtype=np.uint8)
         sel = tiles[tiles[:, 4] == which]
         assert len(sel) > 0
         last_group, seen_full_in_group = -1, False
         for first, nseg, start, n, _, tlen in (tuple(int(x) for x in r) for r in sel):
-            assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
-            # a group's own list may use shorter tiles than the whole-plan list, never longer
-            assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
+            if which == 2:
+                assert tlen == 2 * tile and 1 <= n <= tlen
+            else:
+                assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
+                # a group's own list may use shorter tiles than the whole-plan list, never longer
+                assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
             assert 1 <= nseg <= 256
             if nseg == 1:
                 lyr, sn, soff, grp = exp[first]
@@ -94,6 +100,31 @@ def test_layout_random(p, data, tile, small):
     L = len(p)
     merged = [l for l in range(2, L + 1) if data.draw(st.booleans())]
     check_layout(np.array(p, dtype=np.uint64), merged, tile, small)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_layout_double_length_list(seed):
+    w = wl.tiny_workload(seed, L=12)
+    rng = np.random.default_rng(seed)
+    merged = [l for l in range(2, w.L + 1) if rng.random() < 0.5]
+    check_layout(w.p, merged, 4096, 512, long_tiles=1)
+    check_layout(w.p, merged, 4096, 512, long_tiles=0)
+    check_layout(w.p, merged, 2048, 512, long_tiles=1)     # only built for 4096-element tiles
+
+
+def test_double_length_list_is_chosen_by_launch_size():
+    """Built by rule exactly when the ordinary tiles need more than one batch of workgroups
+    (> 4096) and the double-length ones fit the chip at once (2048 .. 3584)."""
+    for name, expect in (("resnet50", True), ("googlenet", False), ("alexnet", False), ("vgg16", False)):
+        w = wl.cnn_workload(name)
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+        tiles = pl.layout()["tiles"]
+        n1, n2 = int((tiles[:, 4] == 1).sum()), int((tiles[:, 4] == 2).sum())
+        assert (n2 > 0) == expect, (name, n1, n2)
+        if expect:
+            assert n1 > 4096 and 2048 <= n2 <= 3584
+            assert int(tiles[tiles[:, 4] == 2][:, 3].sum()) == w.P
+        pl.destroy()
 
 
 def test_layout_many_tiny_layers_split_gather_tiles():
