@@ -765,6 +765,12 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
         k_reduce<NW, false, 0, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
         return;
     }
+    if constexpr (NW > 0) {
+        if (u == 16 && !deep) {  // double-length tiles, chosen by launch_reduce
+            k_reduce<NW, true, 16, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
+            return;
+        }
+    }
     with_shape(NW > 0, u, deep, [&](auto uc, auto dc) {
         k_reduce<NW, true, decltype(uc)::value, decltype(dc)::value>
             <<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
@@ -843,7 +849,13 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
 {
     if (sc.elems == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint32_t tile = sc.tile_elems;
+    // contiguous buffers need no tile table; the same rule as for the fused pass picks
+    // double-length tiles when they put the whole launch on the chip at once
+    uint32_t tile = sc.tile_elems;
+    if (tile == 4096 && pl.opt.long_tiles != 0 && pl.opt.nontemporal) {
+        const uint64_t n1 = (sc.elems + 4095) / 4096, n2 = (sc.elems + 8191) / 8192;
+        if (n1 > 4096 && n2 <= 3584 && n2 >= 2048) tile = 8192;
+    }
     const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int u = static_cast<int>(tile / (kBlock * 4));

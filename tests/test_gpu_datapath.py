@@ -718,6 +718,35 @@ def window_starts(n, rng, width):
     return [(s, width) for s in picks]
 
 
+def test_full_size_materialised_sampled(mg):
+    """ResNet-50-shaped set through pack -> reduce -> unpack with a workspace (the contiguous
+    reduce takes its double-length tiles at this size); sampled windows against the oracle."""
+    w = wl.cnn_workload("resnet50")
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    grads = wl.make_gradients(w, wl.BASE_SEED + 2, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    pl.bind(grads, out)
+    ws = alloc_ws(pl)
+    pl.pack_reduce_unpack(workspace=ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    for l, n in enumerate(w.p):
+        for s0, c in window_starts(int(n), rng, 8200):
+            xs = [grads[g][l][s0:s0 + c].cpu().numpy().copy() for g in range(w.n_workers)]
+            assert_same(out[l][s0:s0 + c].cpu().numpy(), od.reduce(xs), f"layer {l} window {s0}")
+    for l in range(w.L):
+        assert bool(torch.isfinite(out[l]).all())
+    # the reduced buffer itself: first, last and a middle window of the merged order
+    E = w.P
+    epad = (E + 63) // 64 * 64
+    layers = [l for g in pl.groups() for l in g]
+    first, last = layers[0], layers[-1]
+    red = ws[w.n_workers * epad:w.n_workers * epad + E]
+    assert_same(red[:64].cpu().numpy(), out[first][:64].cpu().numpy(), "head of the reduced buffer")
+    assert_same(red[E - 64:].cpu().numpy(), out[last][-64:].cpu().numpy(), "tail of the reduced buffer")
+
+
+
 @pytest.mark.parametrize("name,a_ms,tile,per_group", [
     ("resnet50", 0.5, None, False), ("googlenet", 0.5, None, False), ("alexnet", 0.5, None, False),
     ("vgg16", 0.1, None, False), ("vgg16", 2.0, None, False),
