@@ -10,6 +10,10 @@ per-layer tensors, for every group of the merge plan, in one fused launch
 region.  Consecutive steps rotate over several independently allocated gradient sets so that
 no step finds its inputs in the 256 MB Infinity Cache.
 
+The timed plans launch by the library's built-in rules.  `extra.fused_tuned` is the same pass
+after mgwfbp_tune has timed a few launch shapes at set-up and kept the fastest (its choices are
+listed; 0 = the rules won); --tune 1 applies that to the timed plans themselves.
+
 Prints one JSON line.  `value` = algorithmic bytes 4*(N+1)*P per step / wall time per step.
 `roofline.achieved` = the same bytes / average kernel duration from HIP events recorded on the
 launch stream around every 8th launch of the timed region (an event pair costs ~5 us of
@@ -55,6 +59,8 @@ def parse():
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--variant", default="fused", choices=["fused", "step", "materialised", "per_group"],
                     help="what one step runs (the headline is 'fused')")
+    ap.add_argument("--tune", type=int, default=0,
+                    help="1: let mgwfbp_tune pick the launch shape of the timed plans at set-up (untimed)")
     ap.add_argument("--extras", type=int, default=1, help="also time the other variants and the probes")
     ap.add_argument("--cpu-baseline", type=int, default=1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -107,6 +113,7 @@ def main():
         pl = new_plan()
         pl.bind(grads, out, wt, vt)
         sets.append({"plan": pl, "grads": grads, "out": out, "w": wt, "v": vt})
+    tuned = [s_["plan"].tune()["candidate"] for s_ in sets] if args.tune else None
     info = sets[0]["plan"].info()
     n_groups = info["n_groups"]
     ws = None
@@ -175,6 +182,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped gradient set", "tensors": L, "P": P,
                    "n_workers": N, "plan": args.mode, "a_ms": w.a_ms, "b_ms_per_byte": w.b_ms_per_byte,
                    "groups": n_groups, "variant": args.variant, "rotating_sets": n_sets,
+                   "tuned_launch_shape": tuned,
                    "algorithmic_bytes_per_step": bytes_step,
                    "percent_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -222,6 +230,29 @@ def main():
         extra["per_group_graph"] = {"groups": n_groups, "us_per_step": round(us, 2),
                                     "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
         del graphs
+        # the same pass after mgwfbp_tune (set-up, untimed) has picked the launch shape
+        if not args.tune and args.variant == "fused":
+            alt, picks = [], []
+            for st in sets:
+                pa = new_plan()
+                pa.bind(st["grads"], st["out"], st["w"], st["v"])
+                picks.append(pa.tune(stream)["candidate"])
+                alt.append(pa)
+            for i in range(w2):
+                alt[i % n_sets].pack_reduce_unpack(stream=stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(k2):
+                alt[i % n_sets].pack_reduce_unpack(stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / k2
+            extra["fused_tuned"] = {"us_per_step": round(us, 2), "choices": picks,
+                                    "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1),
+                                    "frac_of_peak": round(alg_bytes["fused"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+            for pa in alt:
+                pa.destroy()
         # the two extreme plans (every tensor its own group / one group) through the same fused
         # launch: the rate should not depend on the plan
         for nm, md in (("fused_plan_wfbp", mg.MODE_WFBP), ("fused_plan_single", mg.MODE_SINGLE)):

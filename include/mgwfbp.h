@@ -140,8 +140,9 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             list, tile length.  segment count 1: `start` is the element offset inside that segment;
  *             more than one: the tile gathers whole short segments and `start` is its offset
  *             in the plan-wide merged order.  list 0: the per-group lists (group after group);
- *             list 1: the second copy used by whole-plan launches; list 2 (when built): the
- *             whole plan in double-length tiles (MGWFBP_OPT_LONG_TILES).  tile length: elements of a
+ *             list 1: the second copy used by whole-plan launches; list 2 or 3 (when built):
+ *             the whole plan in double-length tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused
+ *             reduce pass uses it by default, 3 if only mgwfbp_tune may select it.  tile length: elements of a
  *             full tile in that list (a group launched alone is cut into shorter tiles than
  *             the whole plan when it would otherwise give too few workgroups).
  *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)
@@ -163,6 +164,20 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t
  */
 int mgwfbp_bind(mgwfbp_plan_t *plan, const float *const *grads, float *const *out,
                 float *const *w, float *const *v);
+
+/*
+ * Optional, after mgwfbp_bind: time the whole-plan fused reduce pass (mgwfbp_pack_reduce_unpack
+ * with group = -1 and no workspace) under a handful of launch shapes -- tile list, pause
+ * between loads, workgroups per compute unit -- on the bound tensors, and keep the fastest for
+ * later whole-plan launches of this plan (also for mgwfbp_pack_reduce).  How well a launch
+ * fills the chip depends on its size in ways the built-in rules only approximate; the result
+ * is the same whatever shape is chosen.  Runs the pass about 80 times on `hip_stream` and waits
+ * for it; out[] ends up holding the reduced gradients.  out[] must be bound and must not alias
+ * a gradient tensor (the pass is repeated).  A new mgwfbp_bind discards the choice.
+ *   chosen      out or NULL: index of the winning candidate (0 = the built-in rules)
+ *   chosen_ms   out or NULL: its time per launch in milliseconds
+ */
+int mgwfbp_tune(mgwfbp_plan_t *plan, void *hip_stream, int32_t *chosen, double *chosen_ms);
 
 /*
  * Workspace size in bytes for the materialised path on `group` (-1 = all groups at once):

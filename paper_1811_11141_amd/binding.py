@@ -22,7 +22,7 @@ OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES = 1, 
 
 EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
-    "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_workspace_bytes",
+    "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_tune", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update",
     "mgwfbp_run_iteration", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
@@ -58,6 +58,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_plan_layout.argtypes = [vp, vp, vp, sz, vp, vp, sz]
     lib.mgwfbp_bind.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
     lib.mgwfbp_workspace_bytes.argtypes = [vp, i32, P(sz)]
+    lib.mgwfbp_tune.argtypes = [vp, vp, P(i32), P(f64)]
     lib.mgwfbp_pack_reduce_unpack.argtypes = [vp, i32, vp, sz, vp]
     lib.mgwfbp_step.argtypes = [vp, i32, f32, f32, vp, sz, vp]
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
@@ -200,6 +201,12 @@ class Plan:
         _check(_lib.mgwfbp_bind(self._h, _ptr_array(flat), _ptr_array(out), _ptr_array(w),
                                 _ptr_array(v)))
         self._keep = (grads, out, w, v)
+
+    def tune(self, stream=None) -> dict:
+        """Pick the launch shape of the whole-plan fused reduce pass by timing (see mgwfbp_tune)."""
+        idx, ms = C.c_int32(), C.c_double()
+        _check(_lib.mgwfbp_tune(self._h, C.c_void_p(_stream(stream)), C.byref(idx), C.byref(ms)))
+        return {"candidate": idx.value, "ms_per_launch": ms.value}
 
     def workspace_bytes(self, group: int = -1) -> int:
         n = C.c_size_t()

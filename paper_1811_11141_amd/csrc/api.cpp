@@ -7,6 +7,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/mgwfbp.h"
 #include "plan.hpp"
@@ -92,6 +93,8 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_
 {
     if (group < -1 || group >= static_cast<int32_t>(pl->groups.size()))
         return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
+    sc.pace = -1;
+    sc.occupancy_lds = 0;
     if (group < 0) {
         sc.tile_begin = pl->all_tile_begin;
         sc.n_tiles = pl->all_tile_count;
@@ -99,10 +102,15 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_
         sc.base_off = 0;
         sc.tile_elems = pl->opt.tile_elems;
         sc.needs_lds = pl->all_needs_lds;
-        if (long_ok && pl->long_tile_count) {
+        const bool use_long = pl->tuned.valid ? pl->tuned.use_long : pl->long_by_default;
+        if (long_ok && pl->long_tile_count && use_long) {
             sc.tile_begin = pl->long_tile_begin;
             sc.n_tiles = pl->long_tile_count;
             sc.tile_elems = pl->long_tile_elems;
+        }
+        if (long_ok && pl->tuned.valid) {
+            sc.pace = pl->tuned.pace;
+            sc.occupancy_lds = pl->tuned.occupancy_lds;
         }
     } else {
         const GroupInfo &g = pl->groups[group];
@@ -322,7 +330,7 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
                 r[4] = i >= tmp.all_tile_begin ? 1 : 0;
                 r[5] = tmp.opt.tile_elems;
                 if (tmp.long_tile_count && i >= tmp.long_tile_begin) {
-                    r[4] = 2;
+                    r[4] = tmp.long_by_default ? 2 : 3;
                     r[5] = tmp.long_tile_elems;
                 }
                 if (!r[4])
@@ -354,6 +362,7 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
             return fail(MGWFBP_EINVAL, "w/v[" + std::to_string(l) + "] is NULL or misaligned");
     }
     release_device(pl);
+    pl->tuned = mgwfbp_plan_s::Tuned();
 
     std::vector<const float *> src_tbl;
     std::vector<float *> out_tbl, w_tbl, v_tbl;
@@ -409,6 +418,8 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
     pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
     pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
     pl->d_clock = reinterpret_cast<uint64_t *>(d + o_clock);
+    pl->host_src = src_tbl;
+    pl->host_out = out_tbl;
     pl->has_out = out != nullptr;
     pl->has_wv = w != nullptr;
     pl->bound = true;
@@ -470,6 +481,79 @@ int mgwfbp_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t work
     if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
     const float *reduced = static_cast<float *>(workspace) + static_cast<uint64_t>(pl->N) * padded(sc.elems);
     return launch_unpack(*pl, sc, reduced, false, 0.0f, 0.0f, hip_stream);
+}
+
+int mgwfbp_tune(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chosen_ms)
+{
+    int rc = check_bound(pl, true, false);
+    if (rc) return rc;
+    for (const float *src : pl->host_src)
+        for (const float *o : pl->host_out)
+            if (src == o) return fail(MGWFBP_EINVAL, "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(MGWFBP_EHIP, "hipEventCreate failed");
+    }
+    // candidate launch shapes: (double-length list, pause, LDS bytes that cap the workgroups per
+    // CU at 16 / 13 / 12).  Index 0 is what the rules alone would do.
+    struct Cand { int use_long; int pace; uint32_t lds; };
+    std::vector<Cand> cands;
+    cands.push_back({-1, -1, 0});
+    for (int use_long = 0; use_long <= (pl->long_tile_count ? 1 : 0); ++use_long) {
+        for (int pace : {1, 4, 8, 12}) cands.push_back({use_long, pace, 0});
+        for (int pace : {2, 4}) cands.push_back({use_long, pace, 11000});
+        cands.push_back({use_long, 2, 12500});
+    }
+    const mgwfbp_plan_s::Tuned before = pl->tuned;
+    int best = 0;
+    double best_ms = 0.0;
+    hipError_t e = hipSuccess;
+    for (size_t c = 0; c < cands.size() && !rc && e == hipSuccess; ++c) {
+        if (cands[c].use_long < 0) {
+            pl->tuned = mgwfbp_plan_s::Tuned();
+        } else {
+            pl->tuned.valid = true;
+            pl->tuned.use_long = cands[c].use_long != 0;
+            pl->tuned.pace = cands[c].pace;
+            pl->tuned.occupancy_lds = cands[c].lds;
+        }
+        for (int i = 0; i < 2 && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        if (rc) break;
+        if ((e = hipEventRecord(e0, s)) != hipSuccess) break;
+        const int reps = 4;
+        for (int i = 0; i < reps && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        if (rc) break;
+        if ((e = hipEventRecord(e1, s)) != hipSuccess) break;
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) break;
+        float ms = 0.0f;
+        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) break;
+        const double per = static_cast<double>(ms) / reps;
+        // a candidate must beat the rules by more than the noise of four launches to replace them
+        if (c == 0 || per < best_ms * (best == 0 ? 0.99 : 1.0)) {
+            best = static_cast<int>(c);
+            best_ms = per;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc || e != hipSuccess) {
+        pl->tuned = before;
+        (void)hipStreamSynchronize(s);
+        return rc ? rc : fail(MGWFBP_EHIP, std::string("timing a candidate: ") + hipGetErrorString(e));
+    }
+    if (best == 0) {
+        pl->tuned = mgwfbp_plan_s::Tuned();
+    } else {
+        pl->tuned.valid = true;
+        pl->tuned.use_long = cands[best].use_long != 0;
+        pl->tuned.pace = cands[best].pace;
+        pl->tuned.occupancy_lds = cands[best].lds;
+    }
+    if (chosen) *chosen = best;
+    if (chosen_ms) *chosen_ms = best_ms;
+    return MGWFBP_OK;
 }
 
 namespace {

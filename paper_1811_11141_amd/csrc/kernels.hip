@@ -712,12 +712,12 @@ int check_launch(const char *what)
 // The fast path exists for tiles of U*kBlock float4, U = 2, 4 or 8 (1024, 2048, 4096 elements).
 // deep = launch too small to fill the chip (latency-bound): 8 loads in flight per wave.
 template <int NW, bool STEP, bool NT>
-void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt, uint32_t tb,
-                    int nw, float inv_n, float lr, float mu, int pace, float *merged_out,
+void fused_launch_u(int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s, const DeviceTables &dt,
+                    uint32_t tb, int nw, float inv_n, float lr, float mu, int pace, float *merged_out,
                     uint64_t base_off)
 {
 #define MGWFBP_LAUNCH(UU, DD)                                                                  \
-    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, 0, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off)
+    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, cap_lds, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off)
     if constexpr (NW > 0 && NT) {
         if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
@@ -731,17 +731,17 @@ void fused_launch_u(int u, bool deep, dim3 grid, hipStream_t s, const DeviceTabl
 }
 
 template <bool STEP, bool NT>
-void fused_dispatch(int nw, int u, bool deep, dim3 grid, hipStream_t s, const DeviceTables &dt,
-                    uint32_t tb, float inv_n, float lr, float mu, int pace, float *merged_out,
-                    uint64_t base_off)
+void fused_dispatch(int nw, int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s,
+                    const DeviceTables &dt, uint32_t tb, float inv_n, float lr, float mu, int pace,
+                    float *merged_out, uint64_t base_off)
 {
     switch (nw) {
-    case 1: fused_launch_u<1, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
-    case 2: fused_launch_u<2, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
-    case 4: fused_launch_u<4, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
-    case 8: fused_launch_u<8, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
-    case 16: fused_launch_u<16, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
-    default: fused_launch_u<0, STEP, NT>(u, deep, grid, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 1: fused_launch_u<1, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 2: fused_launch_u<2, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 4: fused_launch_u<4, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 8: fused_launch_u<8, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    case 16: fused_launch_u<16, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
+    default: fused_launch_u<0, STEP, NT>(u, deep, grid, cap_lds, s, dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); break;
     }
 }
 
@@ -802,7 +802,7 @@ int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
                  void *stream, float *merged_out)
 {
-    const int pace = pace_for(pl, step ? Stream::update : Stream::reduce, sc.n_tiles);
+    const int pace = sc.pace >= 0 ? sc.pace : pace_for(pl, step ? Stream::update : Stream::reduce, sc.n_tiles);
     const uint64_t base_off = sc.base_off;
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -814,11 +814,11 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     // the launch cannot saturate HBM with one load per wave and is bound by latency instead
     const bool deep = sc.n_tiles < 2048;
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
-        else fused_dispatch<true, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<true, false>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
-        else fused_dispatch<false, false>(pl.N, u, deep, grid, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<false, false>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     }
     return check_launch("fused kernel launch");
 }

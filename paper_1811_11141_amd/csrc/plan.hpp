@@ -99,6 +99,16 @@ struct mgwfbp_plan_s {
     // third list: the whole plan cut into tiles of twice the length, for the fused reduce pass
     // when that puts every workgroup on the chip at once (0 tiles = not built)
     uint32_t long_tile_begin = 0, long_tile_count = 0, long_tile_elems = 0;
+    std::vector<const float *> host_src;  // host copies of the bound pointers (alias checks)
+    std::vector<float *> host_out;
+    bool long_by_default = false;  // the rule (or the option) says to use it
+    // launch shape of the whole-plan fused reduce pass found by mgwfbp_tune (valid = false: rules)
+    struct Tuned {
+        bool valid = false;
+        bool use_long = false;
+        int pace = 0;
+        uint32_t occupancy_lds = 0;  // dynamic LDS bytes requested only to cap workgroups per CU
+    } tuned;
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
@@ -134,6 +144,8 @@ struct LaunchScope {
     uint64_t base_off;    // plan_off of the scope's first element
     uint32_t tile_elems;  // length of the full tiles in this scope's list
     bool needs_lds;
+    int pace;                // >= 0: use this pause instead of the rule
+    uint32_t occupancy_lds;  // unused dynamic LDS bytes, to cap the workgroups per CU (0 = no cap)
 };
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
                  void *stream, float *merged_out = nullptr);

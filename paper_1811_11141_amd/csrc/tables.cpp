@@ -150,7 +150,9 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     pl.long_tile_elems = long_tile;
     const size_t n_long = long_slow.size() + long_full.size();
     const bool by_rule = pl.all_tile_count > 4096 && n_long <= 3584 && n_long >= 2048;
-    if (long_tile && (pl.opt.long_tiles == 1 || by_rule)) {
+    pl.long_by_default = long_tile && (pl.opt.long_tiles == 1 || by_rule);
+    // kept also when the rule says no but the launch would be long enough: mgwfbp_tune may pick it
+    if (long_tile && (pl.opt.long_tiles == 1 || n_long >= 2048)) {
         pl.tiles.insert(pl.tiles.end(), long_slow.begin(), long_slow.end());
         pl.tiles.insert(pl.tiles.end(), long_full.begin(), long_full.end());
         pl.long_tile_count = static_cast<uint32_t>(n_long);

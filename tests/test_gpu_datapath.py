@@ -637,6 +637,87 @@ def test_random_shapes_all_entry_points(mg, seed):
         assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l} (seed {seed})")
 
 
+# ---- launch-shape tuning ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["googlenet", "alexnet"])
+def test_tune_keeps_results_and_is_not_slower(mg, name):
+    """mgwfbp_tune only changes how the whole-plan pass is launched: the values stay the oracle's,
+    for the pass into out[] and into a merged buffer, and the pass does not get slower."""
+    w = wl.cnn_workload(name)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    grads = wl.make_gradients(w, wl.BASE_SEED + 3, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    pl.bind(grads, out)
+    stream = torch.cuda.Stream()
+
+    def per_launch_us():
+        best = 1e9
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(10):
+                pl.pack_reduce_unpack(stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 100.0)
+        return best
+
+    pl.pack_reduce_unpack(stream=stream)
+    before = per_launch_us()
+    res = pl.tune(stream)
+    assert res["candidate"] >= 0 and res["ms_per_launch"] > 0
+    after = per_launch_us()
+    assert after <= before * 1.05, (before, after, res)
+    for t in out:
+        t.fill_(float("nan"))
+    mb = merged_buffer(w.P)
+    torch.cuda.synchronize()               # the fills ran on another stream
+    pl.pack_reduce_unpack(stream=stream)
+    pl.pack_reduce(mb, stream=stream)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    off, plan_off = 0, {}
+    for g in pl.groups():
+        for l in g:
+            plan_off[l] = off
+            off += int(w.p[l])
+    for l, n in enumerate(w.p):
+        for s0, c in window_starts(int(n), rng, 8200):
+            xs = [grads[g][l][s0:s0 + c].cpu().numpy().copy() for g in range(w.n_workers)]
+            avg = od.reduce(xs)
+            assert_same(out[l][s0:s0 + c].cpu().numpy(), avg, f"{name} layer {l} window {s0}")
+            o = plan_off[l] + s0
+            assert_same(mb[o:o + c].cpu().numpy(), avg, f"{name} merged layer {l} window {s0}")
+    for l in range(w.L):
+        assert bool(torch.isfinite(out[l]).all())
+    assert bool(torch.isnan(mb[w.P:]).all())
+
+
+def test_tune_argument_errors(mg):
+    w = wl.custom_workload([5000, 200], 2)
+    pl = make_plan(mg, w, [2])
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.tune()
+    assert ei.value.code == mg.ESTATE                       # not bound
+    grads = wl.make_gradients(w, 1, "cuda")
+    pl.bind(grads, None, *wl.make_weights(w, 1, "cuda"))
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.tune()
+    assert ei.value.code == mg.ESTATE                       # out[] not bound
+    pl.bind(grads, [grads[0][0], torch.empty_like(grads[0][1])])
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.tune()                                           # in place over worker 0: cannot be repeated
+    assert ei.value.code == mg.EINVAL and "alias" in str(ei.value)
+    out = [torch.empty_like(t) for t in grads[0]]
+    pl.bind(grads, out)
+    assert pl.tune()["candidate"] >= 0
+    torch.cuda.synchronize()
+    exp = od.merged_gradient_path([to_np(r) for r in grads], groups0(2, [2]))
+    for l in range(2):
+        assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
+
+
 # ---- capture into a HIP graph ----------------------------------------------------------------
 
 @pytest.mark.parametrize("update", [False, True])

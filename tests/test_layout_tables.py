@@ -120,7 +120,9 @@ def test_double_length_list_is_chosen_by_launch_size():
         pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
         tiles = pl.layout()["tiles"]
         n1, n2 = int((tiles[:, 4] == 1).sum()), int((tiles[:, 4] == 2).sum())
+        n3 = int((tiles[:, 4] == 3).sum())        # built for the tuner only, not used by default
         assert (n2 > 0) == expect, (name, n1, n2)
+        assert n3 == 0 or (n2 == 0 and n3 >= 2048)
         if expect:
             assert n1 > 4096 and 2048 <= n2 <= 3584
             assert int(tiles[tiles[:, 4] == 2][:, 3].sum()) == w.P
