@@ -1,6 +1,7 @@
 """Measurements around the hot path: cost-model calibration and the event-driven schedule.
 
     python -m paper_1811_11141_amd.experiments --workload resnet50
+    python -m paper_1811_11141_amd.experiments --workload resnet50 --scaling     (host only)
 
 1. Calibration (what Section V-A does for the network): time every group of a plan alone,
    as a function of its message size M = 4 * (parameters in the group), and fit
@@ -12,6 +13,8 @@
    single-group, Theorem-1 and optimal plans, and compare the measured end of the last group
    with the iteration time the model predicts (Eq. 8); the same iteration is also replayed
    from a HIP graph (mgwfbp_iteration_capture).
+
+3. Scaling (--scaling): the trace-based simulation of Section V-C on the synthetic traces.
 
 Only argument marshalling and timing happen here; all device work is in the library.
 """
@@ -149,11 +152,38 @@ def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: floa
     return out
 
 
+def scaling(workload: str, workers=(4, 8, 16, 32, 64), algorithm: str = "ring", alpha_ms: float = 0.04526,
+            beta_ms_per_byte: float = 8e-7, gamma_ms_per_byte: float = 0.0):
+    """Trace-based weak-scaling table (Section V-C): Table II costs per worker count, planned per
+    mode, Eq. 4 speedup, and the communication left outside the computation,
+    t_iter - (t_f + sum t_b).  Host only.  alpha: 45.26 us is what the ring start-ups of Section
+    V-A imply; beta: 10 Gb/s.  t_f is taken as half the backward pass."""
+    from . import binding as mg
+    from . import workloads as wl
+
+    w = wl.cnn_workload(workload)
+    tf = float(w.tb_ms.sum()) / 2.0
+    comp = tf + float(w.tb_ms.sum())
+    out = {"workload": workload, "algorithm": algorithm, "alpha_ms": alpha_ms, "beta_ms_per_byte": beta_ms_per_byte,
+           "t_f_ms": tf, "t_b_ms": float(w.tb_ms.sum()), "workers": list(workers), "modes": {}}
+    for name, mode in (("wfbp", mg.MODE_WFBP), ("single", mg.MODE_SINGLE),
+                       ("theorem1", mg.MODE_PAPER_GREEDY), ("optimal", mg.MODE_OPTIMAL)):
+        t_iter, speedup = mg.mgwfbp_scaling_curve(w.p, w.tb_ms, tf, algorithm, alpha_ms, beta_ms_per_byte,
+                                                  gamma_ms_per_byte, list(workers), mode)
+        out["modes"][name] = {"t_iter_ms": [float(x) for x in t_iter], "speedup": [float(x) for x in speedup],
+                              "not_overlapped_ms": [float(x) - comp for x in t_iter]}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "googlenet", "alexnet", "vgg16"])
     ap.add_argument("--backward-ms", type=float, nargs="+", default=[5.0, 1.0])
+    ap.add_argument("--scaling", action="store_true", help="only the host-side scaling table (no GPU)")
     args = ap.parse_args()
+    if args.scaling:
+        print(json.dumps(scaling(args.workload)))
+        return
     cal = calibrate(args.workload)
     cal2 = calibrate_in_schedule(args.workload)
     sched = [schedule(args.workload, cal2["a_ms"], cal2["b_ms_per_byte"], t) for t in args.backward_ms]

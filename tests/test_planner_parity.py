@@ -313,3 +313,25 @@ def test_scaling_curve_matches_oracle():
         assert curves["optimal"][1][0] == pytest.approx(1.0, rel=1e-12)      # one worker: a = b = 0
         _, s_free = mg.mgwfbp_scaling_curve(w.p, w.tb_ms, tf, "ring", 0.0, 0.0, 0.0, nodes, mg.MODE_OPTIMAL)
         assert np.allclose(s_free, nodes, rtol=1e-12)
+
+
+def test_experiments_scaling_table_is_host_only_and_consistent():
+    """The scaling table of the experiments module: same numbers as the oracle's Table II costs,
+    planning and Eq. 4, and the communication left outside the computation is t_iter - (t_f + t_b)."""
+    from paper_1811_11141_amd import experiments as ex
+
+    tab = ex.scaling("googlenet", workers=(4, 16, 64))
+    w = wl.cnn_workload("googlenet")
+    tf, tb_total = tab["t_f_ms"], float(w.tb_ms.sum())
+    for i, n in enumerate(tab["workers"]):
+        a, b = op.table2_cost("ring", n, tab["alpha_ms"], tab["beta_ms_per_byte"], 0.0)
+        args = (w.p.tolist(), w.tb_ms.tolist(), tf, a, b)
+        t_wfbp = op.wfbp_timeline(*args)[1]
+        assert tab["modes"]["wfbp"]["t_iter_ms"][i] == pytest.approx(t_wfbp, rel=1e-12)
+        assert tab["modes"]["wfbp"]["speedup"][i] == pytest.approx(op.speedup(n, tf, tb_total, t_wfbp), rel=1e-12)
+        t_rule = op.simulate(*args, op.algorithm1(*args))
+        assert tab["modes"]["theorem1"]["t_iter_ms"][i] == pytest.approx(t_rule, rel=1e-12)
+        for m in tab["modes"].values():
+            assert m["not_overlapped_ms"][i] == pytest.approx(m["t_iter_ms"][i] - tf - tb_total, abs=1e-9)
+            assert m["not_overlapped_ms"][i] >= -1e-9
+        assert tab["modes"]["optimal"]["t_iter_ms"][i] <= min(t_wfbp, t_rule) * (1 + 1e-12)
