@@ -1,0 +1,16 @@
+// Stand-ins for the kernel launchers, so that the host sources of the library (api, planner,
+// tables, executor) link into a host-only test binary without any device code.  No test that
+// uses them reaches a launch: every launch path is refused earlier (plan not bound).
+#include "../../paper_1811_11141_amd/csrc/plan.hpp"
+
+namespace mgwfbp {
+int launch_fused(const mgwfbp_plan_t &, const LaunchScope &, bool, float, float, void *, float *) { return MGWFBP_EHIP; }
+int launch_pack(const mgwfbp_plan_t &, const LaunchScope &, float *, uint64_t, void *) { return MGWFBP_EHIP; }
+int launch_reduce(const mgwfbp_plan_t &, const LaunchScope &, float *, uint64_t, void *) { return MGWFBP_EHIP; }
+int launch_unpack(const mgwfbp_plan_t &, const LaunchScope &, const float *, bool, float, float, void *) { return MGWFBP_EHIP; }
+int launch_spin(double, void *, uint64_t *) { return MGWFBP_EHIP; }
+int launch_spin_until(double, uint64_t *, void *) { return MGWFBP_EHIP; }
+int wall_clock_khz() { return 100000; }
+int launch_probe_copy(const float *, float *, uint64_t, void *) { return MGWFBP_EHIP; }
+int launch_probe_streams(const float *, int32_t, uint64_t, uint64_t, float *, void *) { return MGWFBP_EHIP; }
+}  // namespace mgwfbp
