@@ -137,14 +137,17 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *   segments  host [segments_cap][4] out or NULL: layer, elements, offset in the plan-wide
  *             merged order (elements), group -- in communication order
  *   tiles     host [tiles_cap][6] out or NULL: first segment, segment count, start, elements,
- *             list, tile length.  segment count 1: `start` is the element offset inside that segment;
- *             more than one: the tile gathers whole short segments and `start` is its offset
- *             in the plan-wide merged order.  list 0: the per-group lists (group after group);
- *             list 1: the second copy used by whole-plan launches; list 2 or 3 (when built):
- *             the whole plan in double-length tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused
- *             reduce pass uses it by default, 3 if only mgwfbp_tune may select it.  tile length: elements of a
- *             full tile in that list (a group launched alone is cut into shorter tiles than
- *             the whole plan when it would otherwise give too few workgroups).
+ *             list, tile length.
+ *             segment count 1: `start` is the element offset inside that segment; more than
+ *             one: the tile gathers whole short segments and `start` is its offset in the
+ *             plan-wide merged order.
+ *             list 0: the per-group lists (group after group); list 1: the second copy used
+ *             by whole-plan launches; list 2 or 3 (when built): the whole plan in
+ *             double-length tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses
+ *             it by default, 3 if only mgwfbp_tune may select it.
+ *             tile length: elements of a full tile in that list (a group launched alone is
+ *             cut into shorter tiles than the whole plan when it would otherwise give too
+ *             few workgroups).
  *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)
  */
 int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t *segments,
@@ -171,7 +174,7 @@ int mgwfbp_bind(mgwfbp_plan_t *plan, const float *const *grads, float *const *ou
  * between loads, workgroups per compute unit -- on the bound tensors, and keep the fastest for
  * later whole-plan launches of this plan (also for mgwfbp_pack_reduce).  How well a launch
  * fills the chip depends on its size in ways the built-in rules only approximate; the result
- * is the same whatever shape is chosen.  Runs the pass about 80 times on `hip_stream` and waits
+ * is the same whatever shape is chosen.  Runs the pass up to about 90 times on `hip_stream` and waits
  * for it; out[] ends up holding the reduced gradients.  out[] must be bound and must not alias
  * a gradient tensor (the pass is repeated).  A new mgwfbp_bind discards the choice.
  *   chosen      out or NULL: index of the winning candidate (0 = the built-in rules)
@@ -271,8 +274,8 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  * pass from layer L-1 down to layer 0, one kernel per group that occupies one wave until the
  * backward pass has reached the end of the group's lowest layer (an absolute deadline: the sum
  * of tb_ms so far after time zero, read from the device clock) and touches no gradient memory
- * (only the moment a group's lowest layer is done matters to the communication side).  The communication thread is played by
- * `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
+ * (only the moment a group's lowest layer is done matters to the communication side).  The
+ * communication thread is played by `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
  * mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
  * layer has finished its backward kernel, which is the start rule of Eq. 7 / Condition 2;
  * groups follow each other in communication order.  The call blocks until both streams are
@@ -287,8 +290,8 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  * pass NULL for the three arrays to run the schedule with only the events it needs.
  * Streams: hipStream_t handles at default priority; NULL = the default stream (using one
  * stream for both serialises everything).  Creates and destroys HIP events internally.
- * Time zero and the end of the last group are device-clock values kept in two words owned by the plan: two calls on the same plan must not
- * run at the same time.
+ * Time zero and the end of the last group are device-clock values kept in two words owned by
+ * the plan: two calls on the same plan must not run at the same time.
  */
 int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                          float momentum, void *compute_stream, void *comm_stream,
