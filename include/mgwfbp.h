@@ -174,8 +174,8 @@ int mgwfbp_bind(mgwfbp_plan_t *plan, const float *const *grads, float *const *ou
  * between loads, workgroups per compute unit -- on the bound tensors, and keep the fastest for
  * later whole-plan launches of this plan (also for mgwfbp_pack_reduce).  How well a launch
  * fills the chip depends on its size in ways the built-in rules only approximate; the result
- * is the same whatever shape is chosen.  Runs the pass up to about 90 times on `hip_stream` and waits
- * for it; out[] ends up holding the reduced gradients.  out[] must be bound and must not alias
+ * is the same whatever shape is chosen.  Runs the pass up to about 90 times on `hip_stream` and
+ * waits for it; out[] ends up holding the reduced gradients.  out[] must be bound and must not alias
  * a gradient tensor (the pass is repeated).  A new mgwfbp_bind discards the choice.
  *   chosen      out or NULL: index of the winning candidate (0 = the built-in rules)
  *   chosen_ms   out or NULL: its time per launch in milliseconds
@@ -275,8 +275,8 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
  * backward pass has reached the end of the group's lowest layer (an absolute deadline: the sum
  * of tb_ms so far after time zero, read from the device clock) and touches no gradient memory
  * (only the moment a group's lowest layer is done matters to the communication side).  The
- * communication thread is played by `comm_stream`: the reduction of group k (mgwfbp_pack_reduce_unpack or, with update != 0,
- * mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
+ * communication thread is played by `comm_stream`: the reduction of group k
+ * (mgwfbp_pack_reduce_unpack or, with update != 0, mgwfbp_step, fused form) is enqueued behind an event recorded when the group's lowest
  * layer has finished its backward kernel, which is the start rule of Eq. 7 / Condition 2;
  * groups follow each other in communication order.  The call blocks until both streams are
  * idle and reports the measured timeline, in milliseconds from the start of the backward pass:
