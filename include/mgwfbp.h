@@ -70,9 +70,16 @@ enum {
     MGWFBP_OPT_NONTEMPORAL = 3, /* 1: streaming (non-temporal) loads and stores; 0: plain            */
     MGWFBP_OPT_PACE = 4,        /* pause between two loads of a wave, units of ~64 clocks, 0..16;
                                    -1 (default): chosen per launch from its size and N           */
-    MGWFBP_OPT_LONG_TILES = 5   /* whole-plan fused reduce pass on tiles of 2 * tile_elems (only for
+    MGWFBP_OPT_LONG_TILES = 5,  /* whole-plan fused reduce pass on tiles of 2 * tile_elems (only for
                                    tile_elems = 4096): 1 always, 0 never, -1 (default) when that puts
                                    every workgroup on the chip at once and tile_elems does not      */
+    MGWFBP_OPT_PAD_ELEMS = 6    /* layout of the merged buffers.  0 (default): the layers of a group
+                                   follow each other without padding, as the cost model counts them
+                                   (Condition 3).  4: every layer starts on a 16-byte boundary; the
+                                   1-3 padding elements after a layer are written as zeros by pack and
+                                   mgwfbp_pack_reduce and skipped by unpack.  offset_in_group,
+                                   group_elems, workspace and merged-buffer sizes follow the layout;
+                                   the predicted times do not change                               */
 };
 
 /*
@@ -110,7 +117,8 @@ int mgwfbp_plan_explicit(int32_t L, const uint64_t *p_elems, const double *tb_ms
  *   group_of_layer   [L]  group id of each layer
  *   offset_in_group  [L]  element offset of the layer inside its group's merged buffer
  *                         (arrival order: the highest layer of a group has offset 0)
- *   group_elems      [n_groups]  total elements of each group (no padding)
+ *   group_elems      [n_groups]  total elements of each group's merged buffer (no padding
+ *                         unless MGWFBP_OPT_PAD_ELEMS is set)
  *   t_iter_ms        predicted iteration time of this plan
  *   t_iter_wfbp_ms   predicted iteration time without merging
  */
@@ -134,10 +142,10 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  * Host-only view of the segment and tile tables the kernels would run with under the plan's
  * current options (the tile table of Section IV's layer buffer, cut for the GPU).  Needs no
  * device and no binding: every tensor is taken to be 16-byte aligned.
- *   segments  host [segments_cap][4] out or NULL: layer, elements, offset in the plan-wide
+ *   segments  host [segments_cap][MGWFBP_LAYOUT_SEGMENT_COLS] out or NULL: layer, elements, offset in the plan-wide
  *             merged order (elements), group -- in communication order
- *   tiles     host [tiles_cap][6] out or NULL: first segment, segment count, start, elements,
- *             list, tile length.
+ *   tiles     host [tiles_cap][MGWFBP_LAYOUT_TILE_COLS] out or NULL: first segment, segment count, start, elements,
+ *             list, tile length, padding.
  *             segment count 1: `start` is the element offset inside that segment; more than
  *             one: the tile gathers whole short segments and `start` is its offset in the
  *             plan-wide merged order.
@@ -148,8 +156,12 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too
  *             few workgroups).
+ *             padding: padding elements of the merged order that follow the tile and belong
+ *             to it (MGWFBP_OPT_PAD_ELEMS; a gather tile's `elements` already include the
+ *             padding between and after its layers).
  *   n_segments, n_tiles   out or NULL: the counts (call with NULL arrays to size them)
  */
+enum { MGWFBP_LAYOUT_SEGMENT_COLS = 4, MGWFBP_LAYOUT_TILE_COLS = 7 }; /* row widths of the two arrays */
 int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t *segments,
                        size_t segments_cap, uint64_t *n_tiles, uint64_t *tiles, size_t tiles_cap);
 

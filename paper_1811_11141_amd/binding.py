@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmgwfbp.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
-OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES = 1, 2, 3, 4, 5
+OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES, OPT_PAD_ELEMS = 1, 2, 3, 4, 5, 6
 
 EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
@@ -174,11 +174,11 @@ class Plan:
     def layout(self) -> dict:
         """Segment and tile tables as the kernels would see them (host only, no device needed):
         segments [n][layer, elements, plan offset, group], tiles [n][first segment, segment
-        count, start, elements, list, tile length]."""
+        count, start, elements, list, tile length, padding]."""
         ns, nt = C.c_uint64(0), C.c_uint64(0)
         _check(_lib.mgwfbp_plan_layout(self._h, C.byref(ns), None, 0, C.byref(nt), None, 0))
         segs = np.zeros((ns.value, 4), dtype=np.uint64)
-        tiles = np.zeros((nt.value, 6), dtype=np.uint64)
+        tiles = np.zeros((nt.value, 7), dtype=np.uint64)
         _check(_lib.mgwfbp_plan_layout(self._h, None, segs.ctypes.data, ns.value, None, tiles.ctypes.data, nt.value))
         return {"segments": segs, "tiles": tiles}
 

@@ -285,6 +285,15 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
         if (value < -1 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [-1, 16]");
         pl->opt.pace = static_cast<int>(value);
         return MGWFBP_OK;
+    case MGWFBP_OPT_PAD_ELEMS:
+        if (value != 0 && value != 4) return fail(MGWFBP_EINVAL, "pad_elems must be 0 or 4");
+        pl->opt.pad_elems = static_cast<uint32_t>(value);
+        try {
+            finish_plan(*pl);  // offsets and group sizes follow the layout
+        } catch (const std::bad_alloc &) {
+            return fail(MGWFBP_ENOMEM, "out of host memory");
+        }
+        return MGWFBP_OK;
     case MGWFBP_OPT_LONG_TILES:
         if (value < -1 || value > 1) return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0 or 1");
         pl->opt.long_tiles = static_cast<int>(value);
@@ -317,7 +326,7 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
             if (segments_cap < tmp.segs.size()) return fail(MGWFBP_EINVAL, "segments array too small");
             for (size_t i = 0; i < tmp.segs.size(); ++i) {
                 const SegDev &sd = tmp.segs[i];
-                uint64_t *r = segments + 4 * i;
+                uint64_t *r = segments + MGWFBP_LAYOUT_SEGMENT_COLS * i;
                 r[0] = sd.layer; r[1] = sd.n; r[2] = sd.plan_off; r[3] = sd.group;
             }
         }
@@ -325,8 +334,8 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
             if (tiles_cap < tmp.tiles.size()) return fail(MGWFBP_EINVAL, "tiles array too small");
             for (size_t i = 0; i < tmp.tiles.size(); ++i) {
                 const TileDev &t = tmp.tiles[i];
-                uint64_t *r = tiles + 6 * i;
-                r[0] = t.seg; r[1] = t.nseg; r[2] = t.start; r[3] = t.n;
+                uint64_t *r = tiles + MGWFBP_LAYOUT_TILE_COLS * i;
+                r[0] = t.seg; r[1] = t.nseg; r[2] = t.start; r[3] = t.n; r[6] = t.pad;
                 r[4] = i >= tmp.all_tile_begin ? 1 : 0;
                 r[5] = tmp.opt.tile_elems;
                 if (tmp.long_tile_count && i >= tmp.long_tile_begin) {

@@ -62,7 +62,8 @@ __device__ __forceinline__ T table_load(const T *p)
     return *(const MGWFBP_CONST T *)p;
 }
 
-// A tile descriptor is three 64-bit words: start | seg, nseg | n, pad.
+// A tile descriptor is three 64-bit words: start | seg, nseg | n, pad (pad = elements of
+// padding that follow the tile in the merged order; only with the padded layout).
 __device__ __forceinline__ TileDev load_tile(const TileDev *p)
 {
     const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
@@ -72,7 +73,7 @@ __device__ __forceinline__ TileDev load_tile(const TileDev *p)
     t.seg = static_cast<uint32_t>(w1);
     t.nseg = static_cast<uint32_t>(w1 >> 32);
     t.n = static_cast<uint32_t>(w2);
-    t.pad = 0;
+    t.pad = static_cast<uint32_t>(w2 >> 32);
     return t;
 }
 
@@ -146,13 +147,17 @@ __device__ __forceinline__ void finish(T avg, float *outp, float *wp, float *vp,
     if (outp) st<NT>(reinterpret_cast<T *>(outp) + i, avg);
 }
 
-// Offsets (relative to the tile start) of the segments a gather tile spans go to LDS; each
-// lane then finds the segment holding its element by binary search.
+// Offsets (relative to the tile start) and lengths of the segments a gather tile spans go to
+// LDS; each lane then finds the segment holding its element by binary search.  With the padded
+// layout the run has holes between the layers: position k lies in a hole when it is past the
+// end of the segment that starts at or before it.
 __device__ __forceinline__ void stage_gather_offsets(const DeviceTables &dt, const TileDev &tl,
-                                                     uint32_t *s_rel)
+                                                     uint32_t *s_rel, uint32_t *s_len)
 {
-    for (uint32_t k = threadIdx.x; k < tl.nseg; k += kBlock)
+    for (uint32_t k = threadIdx.x; k < tl.nseg; k += kBlock) {
         s_rel[k] = static_cast<uint32_t>(dt.segs[tl.seg + k].plan_off - tl.start);
+        s_len[k] = static_cast<uint32_t>(dt.segs[tl.seg + k].n);
+    }
     __syncthreads();
 }
 
@@ -420,7 +425,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
 {
     // merged_out != nullptr: the averaged values go to a merged buffer (the layer buffer of
     // Algorithm 2, already reduced) at their packed position instead of the per-layer out[].
-    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
@@ -450,6 +455,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
                 return;
             }
         }
+        if (!STEP && merged_out && threadIdx.x < tl.pad) st<NT>(outp + n + threadIdx.x, 0.0f);
         const uint32_t n4 = vec ? (n >> 2) : 0;
         if constexpr (NW > 0) {
             // per-worker base pointers of this tile (uniform over the workgroup)
@@ -481,12 +487,16 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
             }
         }
     } else {
-        stage_gather_offsets(dt, tl, s_rel);
+        stage_gather_offsets(dt, tl, s_rel, s_len);
 #pragma unroll 1
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
             const uint32_t s = find_segment(s_rel, tl.nseg, k);
             const uint32_t si = tl.seg + s;
             const uint32_t i = k - s_rel[s];
+            if (i >= s_len[s]) {  // padding between two layers: zero in a merged buffer, else nothing
+                if (!STEP && merged_out) st<NT>(merged_out + (tl.start - base_off) + k, 0.0f);
+                continue;
+            }
             const float *const *sp_tbl = dt.src + static_cast<size_t>(si) * nw;
             const float avg = nway_mean_dyn<NT, float>([sp_tbl](int g) { return sp_tbl[g]; }, nw, i, inv_n);
             if (!STEP && merged_out)  // a gather tile is one contiguous run of the merged buffer
@@ -510,7 +520,7 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
        int pace)
 {
     extern __shared__ float lds[];
-    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
     const uint32_t g = blockIdx.y;
     float *merged = ws + static_cast<uint64_t>(g) * epad;
@@ -528,6 +538,7 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
                 return;
             }
         }
+        if (threadIdx.x < tl.pad) st<NT>(dst + n + threadIdx.x, 0.0f);  // padding after the layer
         if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3)) {
             const uint32_t n4 = n >> 2;
             const v4f *s4 = reinterpret_cast<const v4f *>(src);
@@ -543,11 +554,12 @@ k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, u
         }
     } else {
         // many short layers: gather them into LDS, then one coalesced write of the run
-        stage_gather_offsets(dt, tl, s_rel);
+        stage_gather_offsets(dt, tl, s_rel, s_len);
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
             const uint32_t s = find_segment(s_rel, tl.nseg, k);
+            const uint32_t i = k - s_rel[s];
             const float *src = dt.src[static_cast<size_t>(tl.seg + s) * nw + g];
-            lds[k] = ld<NT>(src + (k - s_rel[s]));
+            lds[k] = i < s_len[s] ? ld<NT>(src + i) : 0.0f;  // zero in the padding between layers
         }
         __syncthreads();
         lds_to_global<NT>(lds, merged + (tl.start - base_off), tl.n);
@@ -595,7 +607,7 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
          float mu, int pace)
 {
     extern __shared__ float lds[];
-    __shared__ uint32_t s_rel[kMaxGatherSegs];
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
     const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
 
     if (tl.nseg == 1) {
@@ -639,14 +651,16 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
                 finish<STEP, NT, float>(lds[i], outp, wp, vp, i, lr, mu);
         }
     } else {
-        stage_gather_offsets(dt, tl, s_rel);
+        stage_gather_offsets(dt, tl, s_rel, s_len);
         global_to_lds<NT>(reduced + (tl.start - base_off), lds, tl.n);
         __syncthreads();
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
             const uint32_t s = find_segment(s_rel, tl.nseg, k);
             const uint32_t si = tl.seg + s;
+            const uint32_t i = k - s_rel[s];
+            if (i >= s_len[s]) continue;  // padding between two layers
             finish<STEP, NT, float>(lds[k], dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
-                                    STEP ? dt.v[si] : nullptr, k - s_rel[s], lr, mu);
+                                    STEP ? dt.v[si] : nullptr, i, lr, mu);
         }
     }
 }

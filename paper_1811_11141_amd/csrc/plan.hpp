@@ -60,6 +60,7 @@ struct Options {
     uint32_t small_elems = 512;
     int nontemporal = 1;
     int pace = -1;  // -1: chosen per launch from its size and N
+    uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4: every layer starts 16-byte aligned
     int long_tiles = -1;  // whole-plan fused reduce on double-length tiles: -1 by rule, 0 never, 1 always
 };
 

@@ -117,6 +117,9 @@ void finish_plan(mgwfbp_plan_t &pl)
         pl.off_in_group[l] = cur.elems;
         cur.layers.push_back(l);
         cur.elems += pl.p[l];
+        // optional: every layer starts on a multiple of pad_elems in the merged order
+        if (pl.opt.pad_elems > 1)
+            cur.elems = (cur.elems + pl.opt.pad_elems - 1) / pl.opt.pad_elems * pl.opt.pad_elems;
         if (!pl.merged[l]) {
             cur.plan_off = plan_off;
             plan_off += cur.elems;

@@ -81,6 +81,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         // layers shares gather tiles so that tiny tensors cost no workgroup each.  Gather
         // tiles and ragged tails run the general (slower) code path, so they are listed first:
         // workgroups are dispatched in order and the slow ones then overlap with the bulk.
+        const uint64_t pad = pl.opt.pad_elems > 1 ? pl.opt.pad_elems : 1;
+        auto padded_len = [pad](uint64_t n) { return (n + pad - 1) / pad * pad; };
         auto cut = [&](uint32_t tile_len, std::vector<TileDev> &slow, std::vector<TileDev> &full) {
             uint32_t s = g.seg_begin;
             while (s < g.seg_end) {
@@ -92,6 +94,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                         t.seg = s;
                         t.nseg = 1;
                         t.n = static_cast<uint32_t>(std::min<uint64_t>(tile_len, sd.n - st));
+                        // the last piece also owns the padding that follows the layer
+                        if (st + t.n == sd.n) t.pad = static_cast<uint32_t>(padded_len(sd.n) - sd.n);
                         (t.n == tile_len ? full : slow).push_back(t);
                     }
                     ++s;
@@ -102,16 +106,22 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                 t.seg = s;
                 uint64_t n = 0;
                 uint32_t cnt = 0;
+                // n counts the run in the merged order, padding between the layers included
                 while (s < g.seg_end && pl.segs[s].n < small && cnt < kMaxGatherSegs &&
-                       n + pl.segs[s].n <= gather_cap) {
-                    n += pl.segs[s].n;
+                       (cnt == 0 || n + padded_len(pl.segs[s].n) <= gather_cap)) {
+                    n += padded_len(pl.segs[s].n);
                     ++cnt;
                     ++s;
                 }
                 t.nseg = cnt;
                 t.n = static_cast<uint32_t>(n);
-                if (cnt == 1) t.start = 0;  // a lone short layer is an ordinary direct tile
-                else g.needs_lds = true;
+                if (cnt == 1) {  // a lone short layer is an ordinary direct tile
+                    t.start = 0;
+                    t.n = static_cast<uint32_t>(sd.n);
+                    t.pad = static_cast<uint32_t>(padded_len(sd.n) - sd.n);
+                } else {
+                    g.needs_lds = true;
+                }
                 slow.push_back(t);
             }
         };

@@ -38,13 +38,14 @@ int main(void)
             mgwfbp_plan_set_option(pl, MGWFBP_OPT_TILE_ELEMS, tiles[rnd() % 4]);
             mgwfbp_plan_set_option(pl, MGWFBP_OPT_SMALL_ELEMS, smalls[rnd() % 7]);
             mgwfbp_plan_set_option(pl, MGWFBP_OPT_LONG_TILES, (int)(rnd() % 3) - 1);
+            mgwfbp_plan_set_option(pl, MGWFBP_OPT_PAD_ELEMS, (rnd() & 1) ? 4 : 0);
             mgwfbp_plan_info(pl, &ng, gol, off, NULL, &t1, &t2);
             uint64_t *ge = malloc(sizeof(uint64_t) * ng);
             double *mu = malloc(sizeof(double) * L), *gs = malloc(sizeof(double) * ng), *gf = malloc(sizeof(double) * ng);
             mgwfbp_plan_info(pl, NULL, NULL, NULL, ge, NULL, NULL);
             mgwfbp_plan_timeline(pl, mu, gs, gf);
             if (mgwfbp_plan_layout(pl, &ns, NULL, 0, &nt, NULL, 0) != MGWFBP_OK) bad++;
-            uint64_t *segs = malloc(sizeof(uint64_t) * 4 * (ns ? ns : 1)), *tl = malloc(sizeof(uint64_t) * 6 * (nt ? nt : 1));
+            uint64_t *segs = malloc(sizeof(uint64_t) * MGWFBP_LAYOUT_SEGMENT_COLS * (ns ? ns : 1)), *tl = malloc(sizeof(uint64_t) * MGWFBP_LAYOUT_TILE_COLS * (nt ? nt : 1));
             if (mgwfbp_plan_layout(pl, NULL, segs, ns, NULL, tl, nt) != MGWFBP_OK) bad++;
             if (nt > 1 && mgwfbp_plan_layout(pl, NULL, NULL, 0, NULL, tl, nt - 1) != MGWFBP_EINVAL) bad++;
             size_t wsb = 0;

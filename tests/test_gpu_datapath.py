@@ -588,6 +588,9 @@ def test_random_shapes_all_entry_points(mg, seed):
     pl = make_plan(mg, w, merged, tile=tile, small=small, nt=int(rng.integers(0, 2)))
     pl.set_option(mg.OPT_LONG_TILES, int(rng.integers(-1, 2)))
     misalign = bool(rng.integers(0, 2))
+    padded = bool(rng.integers(0, 2))
+    if padded:
+        pl.set_option(mg.OPT_PAD_ELEMS, 4)
     gen = torch.Generator(device="cuda").manual_seed(seed)
 
     def tensor(n, scale):
@@ -616,13 +619,14 @@ def test_random_shapes_all_entry_points(mg, seed):
     check_out("fused per group")
     pl.pack_reduce_unpack(workspace=alloc_ws(pl))
     check_out("materialised")
-    P = int(sum(sizes))
+    layers = [l for g in groups for l in g]
+    P = int(pl.info()["group_elems"].sum())
+    assert P == (padded_positions(w.p, layers)[1] if padded else int(sum(sizes)))
     mb = merged_buffer(P)
     pl.pack_reduce(mb)
     pl.unpack_update(mb)
     check_out("two halves")
-    layers = [l for g in groups for l in g]
-    assert_same(mb[:P].cpu().numpy(), od.pack(exp, layers), "merged buffer")
+    assert_same(mb[:P].cpu().numpy(), padded_pack(exp, w.p, layers) if padded else od.pack(exp, layers), "merged buffer")
     # three different routes to the update, each advancing (w, v) by one step
     pl.step(0.1, 0.9)
     od.merged_gradient_path(g_np, groups, w_np, v_np, 0.1, 0.9)
@@ -635,6 +639,105 @@ def test_random_shapes_all_entry_points(mg, seed):
     for l in range(L):
         assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l} (seed {seed})")
         assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l} (seed {seed})")
+
+
+# ---- padded merged layout --------------------------------------------------------------------
+
+def padded_positions(p, layers, pad=4):
+    """Element offset of each layer in a merged buffer whose layers start on multiples of pad."""
+    pos, off = {}, 0
+    for l in layers:
+        pos[l] = off
+        off += -(-int(p[l]) // pad) * pad
+    return pos, off
+
+
+def padded_pack(rep, p, layers, pad=4):
+    """What pack must produce with MGWFBP_OPT_PAD_ELEMS: each layer (the oracle's bit copy of it)
+    at its padded position, zeros in the padding."""
+    pos, total = padded_positions(p, layers, pad)
+    buf = np.zeros(total, dtype=rep[0].dtype)
+    for l in layers:
+        buf[pos[l]:pos[l] + int(p[l])] = od.pack(rep, [l])
+    return buf
+
+
+@pytest.mark.parametrize("seed,tile,small,n_workers", [
+    (0, 1024, 512, 4), (1, 2048, 0, 3), (2, 4096, 512, 8), (3, 4096, 1026, 2), (4, 8192, 2048, 16)])
+def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
+    rng = np.random.default_rng(300 + seed)
+    L = int(rng.integers(3, 30))
+    sizes = [int(rng.integers(1, 3000)) if rng.random() < 0.7 else int(rng.integers(3000, 60000)) for _ in range(L)]
+    w = wl.custom_workload(sizes, n_workers, sigma=1e-2)
+    merged = random_merged(rng, L)
+    groups = groups0(L, merged)
+    pl = make_plan(mg, w, merged, tile=tile, small=small)
+    pl.set_option(mg.OPT_PAD_ELEMS, 4)
+    inf = pl.info()
+    grads = wl.make_gradients(w, seed, "cuda")
+    g_np = [to_np(r) for r in grads]
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    wt, vt = wl.make_weights(w, seed, "cuda")
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    exp = od.merged_gradient_path(g_np, groups)
+    scopes = [(-1, [l for g in groups for l in g])] + [(k, g) for k, g in enumerate(groups)]
+    for scope, layers in scopes:
+        pos, E = padded_positions(w.p, layers)
+        assert E == (int(inf["group_elems"].sum()) if scope < 0 else int(inf["group_elems"][scope]))
+        # pack: N padded buffers, zeros in the padding
+        ws = alloc_ws(pl, scope)
+        epad = (E + 63) // 64 * 64
+        assert ws.numel() == (n_workers + 1) * epad
+        pl.pack(ws, group=scope)
+        torch.cuda.synchronize()
+        host = ws.cpu().numpy()
+        for g in range(n_workers):
+            assert np.array_equal(bits(host[g * epad:g * epad + E]), bits(padded_pack(g_np[g], w.p, layers))), (scope, g)
+        # reduce + unpack through the workspace
+        for t in out:
+            t.fill_(float("nan"))
+        pl.reduce(ws, group=scope)
+        pl.unpack(ws, group=scope)
+        torch.cuda.synchronize()
+        red = ws[n_workers * epad:n_workers * epad + E].cpu().numpy()
+        assert_same(red, padded_pack(exp, w.p, layers), f"reduced buffer scope {scope}")
+        for l in layers:
+            assert_same(out[l].cpu().numpy(), exp[l], f"unpack scope {scope} layer {l}")
+        # the two halves
+        mb = merged_buffer(E)
+        pl.pack_reduce(mb, group=scope)
+        torch.cuda.synchronize()
+        hb = mb.cpu().numpy()
+        assert_same(hb[:E], padded_pack(exp, w.p, layers), f"pack_reduce scope {scope}")
+        assert np.isnan(hb[E:]).all()
+        for t in out:
+            t.fill_(float("nan"))
+        pl.unpack_update(mb, group=scope)
+        torch.cuda.synchronize()
+        for l in range(L):
+            if l in layers:
+                assert_same(out[l].cpu().numpy(), exp[l], f"unpack_update scope {scope} layer {l}")
+            else:
+                assert bool(torch.isnan(out[l]).all())
+    # the fused pass does not see the layout; the update from a padded merged buffer does
+    for t in out:
+        t.fill_(float("nan"))
+    pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert_same(out[l].cpu().numpy(), exp[l], f"fused layer {l}")
+    E = int(inf["group_elems"].sum())
+    mb = merged_buffer(E)
+    pl.pack_reduce(mb)
+    pl.unpack_update(mb, update=True, lr=0.1, momentum=0.9)
+    pl.step(0.05, 0.8, workspace=alloc_ws(pl))
+    torch.cuda.synchronize()
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.1, 0.9)
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.05, 0.8)
+    for l in range(L):
+        assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l}")
+        assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l}")
 
 
 # ---- launch-shape tuning ---------------------------------------------------------------------

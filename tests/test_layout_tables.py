@@ -12,27 +12,42 @@ from paper_1811_11141_amd import binding as mg
 from paper_1811_11141_amd import workloads as wl
 
 
-def expected_segments(p, merged):
-    """[(layer0, n, plan offset, group)] in merged order, from the oracle's grouping."""
+def expected_segments(p, merged, pad=1):
+    """[(layer0, n, plan offset, group)] in merged order, from the oracle's grouping; with
+    pad > 1 every layer starts on a multiple of pad elements."""
     rows, off = [], 0
     for k, grp in enumerate(op.groups_from_merged(len(p), merged)):
         for l in grp:
             rows.append((l - 1, int(p[l - 1]), off, k))
-            off += int(p[l - 1])
+            off += -(-int(p[l - 1]) // pad) * pad
     return rows
 
 
-def check_layout(p, merged, tile, small, long_tiles=-1):
+def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
     L = len(p)
     pl = mg.mgwfbp_plan_explicit(p, np.ones(L), 0.0, 0.5, 1e-6, 2, merged)
+    t_iter = pl.info()["t_iter_ms"]
     pl.set_option(mg.OPT_TILE_ELEMS, tile)
     pl.set_option(mg.OPT_SMALL_ELEMS, small)
     pl.set_option(mg.OPT_LONG_TILES, long_tiles)
+    pl.set_option(mg.OPT_PAD_ELEMS, pad)
+    pq = max(pad, 1)
+    plen = lambda n: -(-n // pq) * pq
     lay = pl.layout()
     segs, tiles = lay["segments"], lay["tiles"]
-    exp = expected_segments(p, merged)
+    exp = expected_segments(p, merged, pq)
     assert [tuple(int(x) for x in r) for r in segs] == exp
-    P = int(np.sum(p))
+    P = sum(plen(int(x)) for x in p)                      # the merged order, padding included
+    inf = pl.info()
+    assert inf["t_iter_ms"] == t_iter                     # the cost model counts 4 * sum p bytes
+    assert int(inf["group_elems"].sum()) == P
+    for lyr, n, off, grp in exp:
+        assert int(inf["group_of_layer"][lyr]) == grp
+    gstart = {}
+    for lyr, n, off, grp in exp:
+        gstart.setdefault(grp, off)
+        assert int(inf["offset_in_group"][lyr]) == off - gstart[grp]
+        assert pad == 0 or off % pad == 0
     small_eff = min(small, tile)
     lists = sorted({int(x) for x in tiles[:, 4]})
     assert lists[:2] == [0, 1] and (2 in lists) == (long_tiles == 1 and tile == 4096)
@@ -41,7 +56,7 @@ def check_layout(p, merged, tile, small, long_tiles=-1):
         sel = tiles[tiles[:, 4] == which]
         assert len(sel) > 0
         last_group, seen_full_in_group = -1, False
-        for first, nseg, start, n, _, tlen in (tuple(int(x) for x in r) for r in sel):
+        for first, nseg, start, n, _, tlen, tpad in (tuple(int(x) for x in r) for r in sel):
             if which == 2:
                 assert tlen == 2 * tile and 1 <= n <= tlen
             else:
@@ -54,12 +69,14 @@ def check_layout(p, merged, tile, small, long_tiles=-1):
                 assert start + n <= sn, "direct tile stays inside its segment"
                 assert start % tlen == 0
                 assert n == tlen or start + n == sn, "only the last piece of a segment is ragged"
+                assert tpad == (plen(sn) - sn if start + n == sn else 0), "the last piece owns the layer's padding"
                 lo = soff + start
+                n += tpad
             else:
                 members = exp[first:first + nseg]
                 assert all(m[1] < small_eff for m in members), "gather tiles hold short layers only"
                 assert len({m[3] for m in members}) == 1, "a gather tile never crosses a group"
-                assert start == members[0][2] and n == sum(m[1] for m in members)
+                assert start == members[0][2] and n == sum(plen(m[1]) for m in members) and tpad == 0
                 assert n <= max(min(tile, 1024), small_eff)
                 grp = members[0][3]
                 lo = start
@@ -76,7 +93,7 @@ def check_layout(p, merged, tile, small, long_tiles=-1):
         if which == 0:
             # the shorter tiles are there to give a short launch enough workgroups
             for k, grp in enumerate(op.groups_from_merged(len(p), merged)):
-                ge = sum(int(p[l - 1]) for l in grp)
+                ge = sum(plen(int(p[l - 1])) for l in grp)
                 tl_k = {int(r[5]) for r in sel if exp[int(r[0])][3] == k}
                 assert len(tl_k) == 1
                 t_k = tl_k.pop()
@@ -127,6 +144,20 @@ def test_double_length_list_is_chosen_by_launch_size():
             assert n1 > 4096 and 2048 <= n2 <= 3584
             assert int(tiles[tiles[:, 4] == 2][:, 3].sum()) == w.P
         pl.destroy()
+
+
+@pytest.mark.parametrize("tile,small", [(1024, 0), (1024, 512), (4096, 512), (4096, 1026), (2048, 2048)])
+def test_layout_padded(tile, small):
+    """MGWFBP_OPT_PAD_ELEMS = 4: every layer starts on a multiple of four elements, the tiles
+    cover the padded merged order exactly once, the predicted times do not move."""
+    for seed in range(6):
+        rng = np.random.default_rng(50 + seed)
+        L = int(rng.integers(1, 30))
+        p = np.array([int(rng.integers(1, 3000)) if rng.random() < 0.7 else int(rng.integers(3000, 40000))
+                      for _ in range(L)], dtype=np.uint64)
+        merged = [l for l in range(2, L + 1) if rng.random() < 0.6]
+        check_layout(p, merged, tile, small, pad=4)
+        check_layout(p, merged, tile, small, long_tiles=1, pad=4)
 
 
 def test_layout_many_tiny_layers_split_gather_tiles():
