@@ -771,7 +771,7 @@ def test_tune_keeps_results_and_is_not_slower(mg, name):
     res = pl.tune(stream)
     assert res["candidate"] >= 0 and res["ms_per_launch"] > 0
     after = per_launch_us()
-    assert after <= before * 1.05, (before, after, res)
+    assert after <= before * 1.10, (before, after, res)
     for t in out:
         t.fill_(float("nan"))
     mb = merged_buffer(w.P)
