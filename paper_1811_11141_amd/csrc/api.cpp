@@ -177,6 +177,189 @@ int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, v
 
 using namespace mgwfbp;
 
+namespace {
+int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, float *const *w,
+                float *const *v)
+{
+    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+    if (!grads) return fail(MGWFBP_EINVAL, "grads is NULL");
+    if ((w == nullptr) != (v == nullptr)) return fail(MGWFBP_EINVAL, "w and v must be given together");
+    const int32_t L = pl->L, N = pl->N;
+    for (int64_t i = 0; i < static_cast<int64_t>(N) * L; ++i) {
+        if (!grads[i]) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is NULL");
+        if (reinterpret_cast<uintptr_t>(grads[i]) & 3u) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is not 4-byte aligned");
+    }
+    for (int32_t l = 0; l < L; ++l) {
+        if (out && (!out[l] || (reinterpret_cast<uintptr_t>(out[l]) & 3u)))
+            return fail(MGWFBP_EINVAL, "out[" + std::to_string(l) + "] is NULL or misaligned");
+        if (w && (!w[l] || !v[l] || ((reinterpret_cast<uintptr_t>(w[l]) | reinterpret_cast<uintptr_t>(v[l])) & 3u)))
+            return fail(MGWFBP_EINVAL, "w/v[" + std::to_string(l) + "] is NULL or misaligned");
+    }
+    release_device(pl);
+    pl->tuned = mgwfbp_plan_s::Tuned();
+
+    std::vector<const float *> src_tbl;
+    std::vector<float *> out_tbl, w_tbl, v_tbl;
+    try {
+        build_tables(*pl, grads, out, w, v, src_tbl, out_tbl, w_tbl, v_tbl);
+    } catch (const std::bad_alloc &) {
+        return fail(MGWFBP_ENOMEM, "out of host memory");
+    }
+
+    // one device allocation: [segs][tiles][src][out][w][v][clock word], each part 256-byte aligned
+    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
+    const size_t b_seg = up(pl->segs.size() * sizeof(SegDev));
+    const size_t b_tile = up(pl->tiles.size() * sizeof(TileDev));
+    const size_t b_src = up(src_tbl.size() * sizeof(void *));
+    const size_t b_ptr = up(pl->segs.size() * sizeof(void *));
+    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr + 256;
+    std::vector<char> host(total, 0);
+    size_t o = 0;
+    std::memcpy(host.data() + o, pl->segs.data(), pl->segs.size() * sizeof(SegDev));
+    const size_t o_seg = o; o += b_seg;
+    std::memcpy(host.data() + o, pl->tiles.data(), pl->tiles.size() * sizeof(TileDev));
+    const size_t o_tile = o; o += b_tile;
+    std::memcpy(host.data() + o, src_tbl.data(), src_tbl.size() * sizeof(void *));
+    const size_t o_src = o; o += b_src;
+    const size_t o_out = o; o += b_ptr;
+    const size_t o_w = o; o += b_ptr;
+    const size_t o_v = o; o += b_ptr;
+    const size_t o_clock = o;
+    if (out) std::memcpy(host.data() + o_out, out_tbl.data(), out_tbl.size() * sizeof(void *));
+    if (w) {
+        std::memcpy(host.data() + o_w, w_tbl.data(), w_tbl.size() * sizeof(void *));
+        std::memcpy(host.data() + o_v, v_tbl.data(), v_tbl.size() * sizeof(void *));
+    }
+
+    hipError_t e = hipGetDevice(&pl->device);
+    if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    e = hipMalloc(&pl->d_blob, total);
+    if (e != hipSuccess) {
+        pl->d_blob = nullptr;
+        return fail(e == hipErrorOutOfMemory ? MGWFBP_ENOMEM : MGWFBP_EHIP,
+                    std::string("hipMalloc of the plan tables: ") + hipGetErrorString(e));
+    }
+    e = hipMemcpy(pl->d_blob, host.data(), total, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        release_device(pl);
+        return fail(MGWFBP_EHIP, std::string("hipMemcpy of the plan tables: ") + hipGetErrorString(e));
+    }
+    char *d = static_cast<char *>(pl->d_blob);
+    pl->dt.segs = reinterpret_cast<const SegDev *>(d + o_seg);
+    pl->dt.tiles = reinterpret_cast<const TileDev *>(d + o_tile);
+    pl->dt.src = reinterpret_cast<const float *const *>(d + o_src);
+    pl->dt.out = out ? reinterpret_cast<float *const *>(d + o_out) : nullptr;
+    pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
+    pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
+    pl->d_clock = reinterpret_cast<uint64_t *>(d + o_clock);
+    pl->host_src = src_tbl;
+    pl->host_out = out_tbl;
+    pl->has_out = out != nullptr;
+    pl->has_wv = w != nullptr;
+    pl->bound = true;
+    return MGWFBP_OK;
+}
+}  // namespace
+
+namespace {
+int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chosen_ms)
+{
+    int rc = check_bound(pl, true, false);
+    if (rc) return rc;
+    for (const float *src : pl->host_src)
+        for (const float *o : pl->host_out)
+            if (src == o) return fail(MGWFBP_EINVAL, "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(MGWFBP_EHIP, "hipEventCreate failed");
+    }
+    // candidate launch shapes: (double-length list, pause, LDS bytes that cap the workgroups per
+    // CU at 16 / 13 / 12).  Index 0 is what the rules alone would do.
+    struct Cand { int use_long; int pace; uint32_t lds; };
+    std::vector<Cand> cands;
+    cands.push_back({-1, -1, 0});
+    for (int use_long = 0; use_long <= (pl->long_tile_count ? 1 : 0); ++use_long) {
+        for (int pace : {1, 4, 8, 12}) cands.push_back({use_long, pace, 0});
+        for (int pace : {2, 4}) cands.push_back({use_long, pace, 11000});
+        cands.push_back({use_long, 2, 12500});
+    }
+    const mgwfbp_plan_s::Tuned before = pl->tuned;
+    int best = 0;
+    double best_ms = 0.0;
+    hipError_t e = hipSuccess;
+    for (size_t c = 0; c < cands.size() && !rc && e == hipSuccess; ++c) {
+        if (cands[c].use_long < 0) {
+            pl->tuned = mgwfbp_plan_s::Tuned();
+        } else {
+            pl->tuned.valid = true;
+            pl->tuned.use_long = cands[c].use_long != 0;
+            pl->tuned.pace = cands[c].pace;
+            pl->tuned.occupancy_lds = cands[c].lds;
+        }
+        for (int i = 0; i < 2 && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        if (rc) break;
+        if ((e = hipEventRecord(e0, s)) != hipSuccess) break;
+        const int reps = 4;
+        for (int i = 0; i < reps && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        if (rc) break;
+        if ((e = hipEventRecord(e1, s)) != hipSuccess) break;
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) break;
+        float ms = 0.0f;
+        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) break;
+        const double per = static_cast<double>(ms) / reps;
+        // a candidate must beat the rules by more than the noise of four launches to replace them
+        if (c == 0 || per < best_ms * (best == 0 ? 0.99 : 1.0)) {
+            best = static_cast<int>(c);
+            best_ms = per;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc || e != hipSuccess) {
+        pl->tuned = before;
+        (void)hipStreamSynchronize(s);
+        return rc ? rc : fail(MGWFBP_EHIP, std::string("timing a candidate: ") + hipGetErrorString(e));
+    }
+    if (best == 0) {
+        pl->tuned = mgwfbp_plan_s::Tuned();
+    } else {
+        pl->tuned.valid = true;
+        pl->tuned.use_long = cands[best].use_long != 0;
+        pl->tuned.pace = cands[best].pace;
+        pl->tuned.occupancy_lds = cands[best].lds;
+    }
+    if (chosen) *chosen = best;
+    if (chosen_ms) *chosen_ms = best_ms;
+    return MGWFBP_OK;
+}
+}  // namespace
+
+namespace {
+int scaling_curve_impl(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
+                         int32_t algorithm, double alpha_ms, double beta, double gamma,
+                         int32_t n_points, const int32_t *n_workers, int32_t mode,
+                         double *t_iter_ms, double *speedup)
+{
+    if (n_points < 0 || (n_points > 0 && !n_workers)) return fail(MGWFBP_EINVAL, "bad n_points / n_workers");
+    for (int32_t i = 0; i < n_points; ++i) {
+        double a = 0, b = 0;
+        int rc = mgwfbp_table2_cost(algorithm, n_workers[i], alpha_ms, beta, gamma, &a, &b);
+        if (rc) return rc;
+        mgwfbp_plan_t *pl = nullptr;
+        if ((rc = mgwfbp_plan(L, p_elems, tb_ms, tf_ms, a, b, n_workers[i], mode, &pl))) return rc;
+        const double t = pl->t_iter;
+        double compute = tf_ms;  // t_f + t_b of one worker
+        for (int32_t l = 0; l < L; ++l) compute += tb_ms[l];
+        mgwfbp_plan_destroy(pl);
+        if (t_iter_ms) t_iter_ms[i] = t;
+        if (speedup) speedup[i] = t > 0 ? static_cast<double>(n_workers[i]) * compute / t : 0.0;
+    }
+    return MGWFBP_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int mgwfbp_plan(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
@@ -356,83 +539,7 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
 int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, float *const *w,
                 float *const *v)
 {
-    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
-    if (!grads) return fail(MGWFBP_EINVAL, "grads is NULL");
-    if ((w == nullptr) != (v == nullptr)) return fail(MGWFBP_EINVAL, "w and v must be given together");
-    const int32_t L = pl->L, N = pl->N;
-    for (int64_t i = 0; i < static_cast<int64_t>(N) * L; ++i) {
-        if (!grads[i]) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is NULL");
-        if (reinterpret_cast<uintptr_t>(grads[i]) & 3u) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is not 4-byte aligned");
-    }
-    for (int32_t l = 0; l < L; ++l) {
-        if (out && (!out[l] || (reinterpret_cast<uintptr_t>(out[l]) & 3u)))
-            return fail(MGWFBP_EINVAL, "out[" + std::to_string(l) + "] is NULL or misaligned");
-        if (w && (!w[l] || !v[l] || ((reinterpret_cast<uintptr_t>(w[l]) | reinterpret_cast<uintptr_t>(v[l])) & 3u)))
-            return fail(MGWFBP_EINVAL, "w/v[" + std::to_string(l) + "] is NULL or misaligned");
-    }
-    release_device(pl);
-    pl->tuned = mgwfbp_plan_s::Tuned();
-
-    std::vector<const float *> src_tbl;
-    std::vector<float *> out_tbl, w_tbl, v_tbl;
-    try {
-        build_tables(*pl, grads, out, w, v, src_tbl, out_tbl, w_tbl, v_tbl);
-    } catch (const std::bad_alloc &) {
-        return fail(MGWFBP_ENOMEM, "out of host memory");
-    }
-
-    // one device allocation: [segs][tiles][src][out][w][v][clock word], each part 256-byte aligned
-    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
-    const size_t b_seg = up(pl->segs.size() * sizeof(SegDev));
-    const size_t b_tile = up(pl->tiles.size() * sizeof(TileDev));
-    const size_t b_src = up(src_tbl.size() * sizeof(void *));
-    const size_t b_ptr = up(pl->segs.size() * sizeof(void *));
-    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr + 256;
-    std::vector<char> host(total, 0);
-    size_t o = 0;
-    std::memcpy(host.data() + o, pl->segs.data(), pl->segs.size() * sizeof(SegDev));
-    const size_t o_seg = o; o += b_seg;
-    std::memcpy(host.data() + o, pl->tiles.data(), pl->tiles.size() * sizeof(TileDev));
-    const size_t o_tile = o; o += b_tile;
-    std::memcpy(host.data() + o, src_tbl.data(), src_tbl.size() * sizeof(void *));
-    const size_t o_src = o; o += b_src;
-    const size_t o_out = o; o += b_ptr;
-    const size_t o_w = o; o += b_ptr;
-    const size_t o_v = o; o += b_ptr;
-    const size_t o_clock = o;
-    if (out) std::memcpy(host.data() + o_out, out_tbl.data(), out_tbl.size() * sizeof(void *));
-    if (w) {
-        std::memcpy(host.data() + o_w, w_tbl.data(), w_tbl.size() * sizeof(void *));
-        std::memcpy(host.data() + o_v, v_tbl.data(), v_tbl.size() * sizeof(void *));
-    }
-
-    hipError_t e = hipGetDevice(&pl->device);
-    if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
-    e = hipMalloc(&pl->d_blob, total);
-    if (e != hipSuccess) {
-        pl->d_blob = nullptr;
-        return fail(e == hipErrorOutOfMemory ? MGWFBP_ENOMEM : MGWFBP_EHIP,
-                    std::string("hipMalloc of the plan tables: ") + hipGetErrorString(e));
-    }
-    e = hipMemcpy(pl->d_blob, host.data(), total, hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        release_device(pl);
-        return fail(MGWFBP_EHIP, std::string("hipMemcpy of the plan tables: ") + hipGetErrorString(e));
-    }
-    char *d = static_cast<char *>(pl->d_blob);
-    pl->dt.segs = reinterpret_cast<const SegDev *>(d + o_seg);
-    pl->dt.tiles = reinterpret_cast<const TileDev *>(d + o_tile);
-    pl->dt.src = reinterpret_cast<const float *const *>(d + o_src);
-    pl->dt.out = out ? reinterpret_cast<float *const *>(d + o_out) : nullptr;
-    pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
-    pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
-    pl->d_clock = reinterpret_cast<uint64_t *>(d + o_clock);
-    pl->host_src = src_tbl;
-    pl->host_out = out_tbl;
-    pl->has_out = out != nullptr;
-    pl->has_wv = w != nullptr;
-    pl->bound = true;
-    return MGWFBP_OK;
+    return guarded([&]() -> int { return bind_impl(pl, grads, out, w, v); });
 }
 
 int mgwfbp_workspace_bytes(const mgwfbp_plan_t *pl, int32_t group, size_t *bytes)
@@ -494,75 +601,7 @@ int mgwfbp_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t work
 
 int mgwfbp_tune(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chosen_ms)
 {
-    int rc = check_bound(pl, true, false);
-    if (rc) return rc;
-    for (const float *src : pl->host_src)
-        for (const float *o : pl->host_out)
-            if (src == o) return fail(MGWFBP_EINVAL, "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
-        if (e0) (void)hipEventDestroy(e0);
-        return fail(MGWFBP_EHIP, "hipEventCreate failed");
-    }
-    // candidate launch shapes: (double-length list, pause, LDS bytes that cap the workgroups per
-    // CU at 16 / 13 / 12).  Index 0 is what the rules alone would do.
-    struct Cand { int use_long; int pace; uint32_t lds; };
-    std::vector<Cand> cands;
-    cands.push_back({-1, -1, 0});
-    for (int use_long = 0; use_long <= (pl->long_tile_count ? 1 : 0); ++use_long) {
-        for (int pace : {1, 4, 8, 12}) cands.push_back({use_long, pace, 0});
-        for (int pace : {2, 4}) cands.push_back({use_long, pace, 11000});
-        cands.push_back({use_long, 2, 12500});
-    }
-    const mgwfbp_plan_s::Tuned before = pl->tuned;
-    int best = 0;
-    double best_ms = 0.0;
-    hipError_t e = hipSuccess;
-    for (size_t c = 0; c < cands.size() && !rc && e == hipSuccess; ++c) {
-        if (cands[c].use_long < 0) {
-            pl->tuned = mgwfbp_plan_s::Tuned();
-        } else {
-            pl->tuned.valid = true;
-            pl->tuned.use_long = cands[c].use_long != 0;
-            pl->tuned.pace = cands[c].pace;
-            pl->tuned.occupancy_lds = cands[c].lds;
-        }
-        for (int i = 0; i < 2 && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
-        if (rc) break;
-        if ((e = hipEventRecord(e0, s)) != hipSuccess) break;
-        const int reps = 4;
-        for (int i = 0; i < reps && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
-        if (rc) break;
-        if ((e = hipEventRecord(e1, s)) != hipSuccess) break;
-        if ((e = hipEventSynchronize(e1)) != hipSuccess) break;
-        float ms = 0.0f;
-        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) break;
-        const double per = static_cast<double>(ms) / reps;
-        // a candidate must beat the rules by more than the noise of four launches to replace them
-        if (c == 0 || per < best_ms * (best == 0 ? 0.99 : 1.0)) {
-            best = static_cast<int>(c);
-            best_ms = per;
-        }
-    }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (rc || e != hipSuccess) {
-        pl->tuned = before;
-        (void)hipStreamSynchronize(s);
-        return rc ? rc : fail(MGWFBP_EHIP, std::string("timing a candidate: ") + hipGetErrorString(e));
-    }
-    if (best == 0) {
-        pl->tuned = mgwfbp_plan_s::Tuned();
-    } else {
-        pl->tuned.valid = true;
-        pl->tuned.use_long = cands[best].use_long != 0;
-        pl->tuned.pace = cands[best].pace;
-        pl->tuned.occupancy_lds = cands[best].lds;
-    }
-    if (chosen) *chosen = best;
-    if (chosen_ms) *chosen_ms = best_ms;
-    return MGWFBP_OK;
+    return guarded([&]() -> int { return tune_impl(pl, hip_stream, chosen, chosen_ms); });
 }
 
 namespace {
@@ -674,21 +713,10 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
                          int32_t n_points, const int32_t *n_workers, int32_t mode,
                          double *t_iter_ms, double *speedup)
 {
-    if (n_points < 0 || (n_points > 0 && !n_workers)) return fail(MGWFBP_EINVAL, "bad n_points / n_workers");
-    for (int32_t i = 0; i < n_points; ++i) {
-        double a = 0, b = 0;
-        int rc = mgwfbp_table2_cost(algorithm, n_workers[i], alpha_ms, beta, gamma, &a, &b);
-        if (rc) return rc;
-        mgwfbp_plan_t *pl = nullptr;
-        if ((rc = mgwfbp_plan(L, p_elems, tb_ms, tf_ms, a, b, n_workers[i], mode, &pl))) return rc;
-        const double t = pl->t_iter;
-        double compute = tf_ms;  // t_f + t_b of one worker
-        for (int32_t l = 0; l < L; ++l) compute += tb_ms[l];
-        mgwfbp_plan_destroy(pl);
-        if (t_iter_ms) t_iter_ms[i] = t;
-        if (speedup) speedup[i] = t > 0 ? static_cast<double>(n_workers[i]) * compute / t : 0.0;
-    }
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        return scaling_curve_impl(L, p_elems, tb_ms, tf_ms, algorithm, alpha_ms, beta, gamma, n_points,
+                                  n_workers, mode, t_iter_ms, speedup);
+    });
 }
 
 void mgwfbp_plan_destroy(mgwfbp_plan_t *pl)

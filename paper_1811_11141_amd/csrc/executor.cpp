@@ -121,7 +121,8 @@ int read_t_iter(const mgwfbp_plan_t *pl, double *t_iter_ms)
 
 }  // namespace
 
-extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+namespace {
+int run_iteration_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
                                     float momentum, void *compute_stream, void *comm_stream,
                                     double *group_ready_ms, double *group_start_ms,
                                     double *group_finish_ms, double *t_iter_ms)
@@ -189,6 +190,18 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
     if (t_iter_ms) return read_t_iter(pl, t_iter_ms);
     return MGWFBP_OK;
 }
+}  // namespace
+
+extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                    float momentum, void *compute_stream, void *comm_stream,
+                                    double *group_ready_ms, double *group_start_ms,
+                                    double *group_finish_ms, double *t_iter_ms)
+{
+    return guarded([&]() -> int {
+        return run_iteration_impl(pl, tb_ms, update, lr, momentum, compute_stream, comm_stream,
+                                  group_ready_ms, group_start_ms, group_finish_ms, t_iter_ms);
+    });
+}
 
 // ---- the same iteration as a HIP graph -------------------------------------------------------
 
@@ -198,9 +211,10 @@ struct mgwfbp_iteration_s {
     hipGraphExec_t exec = nullptr;
 };
 
-extern "C" int mgwfbp_iteration_capture(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
-                                        float momentum, void *compute_stream, void *comm_stream,
-                                        mgwfbp_iteration_t **out)
+namespace {
+int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                           float momentum, void *compute_stream, void *comm_stream,
+                           mgwfbp_iteration_t **out)
 {
     if (!out) {
         set_error("out is NULL");
@@ -263,6 +277,16 @@ extern "C" int mgwfbp_iteration_capture(mgwfbp_plan_t *pl, const double *tb_ms, 
     }
     *out = it;
     return MGWFBP_OK;
+}
+}  // namespace
+
+extern "C" int mgwfbp_iteration_capture(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                        float momentum, void *compute_stream, void *comm_stream,
+                                        mgwfbp_iteration_t **out)
+{
+    return guarded([&]() -> int {
+        return iteration_capture_impl(pl, tb_ms, update, lr, momentum, compute_stream, comm_stream, out);
+    });
 }
 
 extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream, double *t_iter_ms)

@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -120,6 +121,27 @@ struct mgwfbp_plan_s {
 namespace mgwfbp {
 
 void set_error(const std::string &msg);
+
+// Runs f and turns any C++ exception into a status code: nothing may propagate through the C ABI.
+template <class F>
+int guarded(F f) noexcept
+{
+    try {
+        return f();
+    } catch (const std::bad_alloc &) {
+        try {
+            set_error("out of host memory");
+        } catch (...) {
+        }
+        return MGWFBP_ENOMEM;
+    } catch (...) {
+        try {
+            set_error("unexpected C++ exception");
+        } catch (...) {
+        }
+        return MGWFBP_EHIP;
+    }
+}
 
 // planner.cpp
 double simulate(const mgwfbp_plan_t &pl, const std::vector<uint8_t> &merged,
