@@ -282,3 +282,27 @@ def test_speedup_eq4_eq5():
     tf, tb, tc = 1.5, 6.5, 2.0
     assert op.speedup(8, tf, tb, tf + tb + tc) == pytest.approx(8 / (1 + tc / (tf + tb)), rel=1e-12)
     assert op.speedup(16, tf, tb, tf + tb) == 16.0
+
+
+def test_workload_generators_reproduce_the_architectures():
+    """Shape statistics of the four CNN-shaped sets (tensor counts, totals, extremes, how many
+    tiny tensors, share of the largest layer): what the standard architectures give."""
+    expect = {  # name: (L, P, min, max, tensors < 10 K, tensors < 1 K, largest / P)
+        "resnet50": (161, 25_557_032, 64, 2_359_296, 109, 84, 0.092),
+        "googlenet": (128, 13_378_280, 16, 2_097_152, 70, 59, 0.157),
+        "alexnet": (16, 61_100_840, 64, 37_748_736, 8, 5, 0.618),     # fc6 = 9216 x 4096
+        "vgg16": (32, 138_357_544, 64, 102_760_448, 17, 13, 0.743),   # fc6 = 25088 x 4096
+    }
+    for name, (L, P, lo, hi, n10k, n1k, share) in expect.items():
+        w = wl.cnn_workload(name)
+        p = w.p
+        assert (w.L, w.P, int(p.min()), int(p.max())) == (L, P, lo, hi), name
+        assert (int((p < 10_000).sum()), int((p < 1_000).sum())) == (n10k, n1k), name
+        assert abs(float(p.max()) / P - share) < 1e-3, name
+        assert int((p % 4 != 0).sum()) == 0, "every tensor length is a multiple of four elements"
+        assert w.n_workers == (16 if name == "vgg16" else 8)
+        assert np.all(w.tb_ms > 0) and len(w.tb_ms) == L
+    # deterministic: the same seed gives the same bits
+    a = wl.make_gradients(wl.tiny_workload(3), 3, "cpu")
+    b = wl.make_gradients(wl.tiny_workload(3), 3, "cpu")
+    assert all(np.array_equal(x.numpy().view(np.uint32), y.numpy().view(np.uint32)) for ra, rb in zip(a, b) for x, y in zip(ra, rb))
