@@ -322,8 +322,9 @@ int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t updat
  *   mgwfbp_iteration_replay   launches the graph on `hip_stream`.  t_iter_ms == NULL: returns
  *       at once (asynchronous).  Otherwise waits for the stream and reports the time from the
  *       start of the backward pass to the end of the last group, read from the device clock.
- *   mgwfbp_iteration_destroy  frees the graph.  Destroy it before re-binding or destroying
- *       the plan; replays of one plan must not overlap.
+ *   mgwfbp_iteration_destroy  frees the graph.  Destroy it before destroying the plan.  After
+ *       a new mgwfbp_bind the graph is stale: replay then returns MGWFBP_ESTATE.  Replays of
+ *       one plan must not overlap.
  */
 typedef struct mgwfbp_iteration_s mgwfbp_iteration_t; /* opaque */
 int mgwfbp_iteration_capture(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,

@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import weakref
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -131,6 +132,7 @@ class Plan:
         self.L, self.N = L, N
         self.p = p
         self._keep = None
+        self._graphs = []          # weak references to the iteration graphs captured from this plan
 
     # ---- read back -------------------------------------------------------------------
     def info(self) -> dict:
@@ -282,9 +284,16 @@ class Plan:
         _check(_lib.mgwfbp_iteration_capture(
             self._h, None if tb is None else tb.ctypes.data_as(C.POINTER(C.c_double)), int(update), lr,
             momentum, C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)), C.byref(h)))
-        return IterationGraph(h.value, self)
+        it = IterationGraph(h.value, self)
+        self._graphs.append(weakref.ref(it))
+        return it
 
     def destroy(self) -> None:
+        for ref in self._graphs:      # a graph must not outlive the tables it points into
+            it = ref()
+            if it is not None:
+                it.destroy()
+        self._graphs = []
         if self._h:
             _lib.mgwfbp_plan_destroy(self._h)
             self._h = C.c_void_p(0)

@@ -86,6 +86,7 @@ void release_device(mgwfbp_plan_t *pl)
     pl->d_clock = nullptr;
     pl->dt = DeviceTables();
     pl->bound = false;
+    ++pl->binding_generation;  // graphs captured against the old tables must not run again
 }
 
 // long_ok: the caller's kernel has the double-length fast path (the fused pass without update)

@@ -207,6 +207,7 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
 
 struct mgwfbp_iteration_s {
     mgwfbp_plan_t *plan = nullptr;
+    uint64_t binding_generation = 0;  // of the plan at capture: the graph holds table addresses
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
@@ -254,6 +255,7 @@ int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t updat
         return MGWFBP_ENOMEM;
     }
     it->plan = pl;
+    it->binding_generation = pl->binding_generation;
     if ((e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal)) != hipSuccess) {
         delete it;
         return hip_fail("hipStreamBeginCapture", e);
@@ -295,8 +297,8 @@ extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream,
         set_error("iteration handle is NULL");
         return MGWFBP_EINVAL;
     }
-    if (!it->plan->bound) {
-        set_error("the plan was re-bound or destroyed after the capture");
+    if (!it->plan->bound || it->plan->binding_generation != it->binding_generation) {
+        set_error("the plan was re-bound after the capture: capture the iteration again");
         return MGWFBP_ESTATE;
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -166,7 +166,15 @@ def test_iteration_graph_argument_errors(mg):
         pl.capture_iteration(s1, s2, update=True)          # no w, v
     it = pl.capture_iteration(s1, s2, tb_ms=[0.05, 0.05])
     assert it.replay(s1) >= 0.095
-    it.destroy()
+    # a new binding replaces the device tables the graph points into: the graph is stale
+    pl.bind(grads, [torch.empty_like(t) for t in grads[0]])
+    with pytest.raises(mg.MgwfbpError) as ei:
+        it.replay(s1)
+    assert ei.value.code == mg.ESTATE
+    it2 = pl.capture_iteration(s1, s2, tb_ms=[0.05, 0.05])
+    assert it2.replay(s1) >= 0.095
+    pl.destroy()                      # takes its graphs with it
+    assert not it2._h
 
 
 def test_calibrated_schedule_ranks_plans_like_the_model(mg):
