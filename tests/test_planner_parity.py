@@ -335,3 +335,17 @@ def test_experiments_scaling_table_is_host_only_and_consistent():
             assert m["not_overlapped_ms"][i] == pytest.approx(m["t_iter_ms"][i] - tf - tb_total, abs=1e-9)
             assert m["not_overlapped_ms"][i] >= -1e-9
         assert tab["modes"]["optimal"]["t_iter_ms"][i] <= min(t_wfbp, t_rule) * (1 + 1e-12)
+
+
+def test_tie_between_equal_plans_keeps_the_smaller_groups(golden):
+    """include/mgwfbp.h documents the tie rule of the optimal mode: among plans of equal t_iter
+    the one with smaller groups.  The hand-worked tie case (merging layer 2 into 1 or not both
+    give 5.0 ms) must therefore come back unmerged, like Theorem 1's strict inequality."""
+    c = [x for x in golden["hand_worked_traces"]["cases"] if x["note"].startswith("exact tie")][0]
+    args = (c["p"], c["tb_ms"], 0.0, c["a_ms"], c["b_ms_per_byte"])
+    assert op.simulate(*args, [2]) == op.simulate(*args, []) == c["t_iter"]
+    for mode in (mg.MODE_OPTIMAL, mg.MODE_PAPER_GREEDY):
+        pl = mg.mgwfbp_plan(np.array(c["p"], dtype=np.uint64), np.array(c["tb_ms"]), 0.0, c["a_ms"],
+                            c["b_ms_per_byte"], 4, mode)
+        assert pl.merged_layers() == [] and pl.info()["n_groups"] == 2
+        assert pl.info()["t_iter_ms"] == c["t_iter"]
