@@ -179,3 +179,32 @@ def test_layout_cnn_sets_default_options():
         merged = pl.merged_layers()
         assert [tuple(int(x) for x in r) for r in lay["segments"]] == expected_segments(w.p, merged)
         pl.destroy()
+
+
+def test_layout_thresholds_exactly():
+    """The three size thresholds of the table builder at their edges."""
+    def lists_of(p, merged, **opts):
+        pl = mg.mgwfbp_plan_explicit(np.array(p, dtype=np.uint64), np.ones(len(p)), 0.0, 0.5, 1e-6, 4, merged)
+        for k, v in opts.items():
+            pl.set_option(k, v)
+        t = pl.layout()["tiles"]
+        pl.destroy()
+        return t
+
+    # a gather tile holds at most 1024 elements: 511 + 511 fit, the next 8 do not
+    t = lists_of([8, 511, 511], [2, 3])
+    own = t[t[:, 4] == 0]
+    assert [(int(r[1]), int(r[3])) for r in own] == [(2, 1022), (1, 8)]
+    t = lists_of([2, 511, 511], [2, 3])
+    assert [(int(r[1]), int(r[3])) for r in t[t[:, 4] == 0]] == [(3, 1024)]
+    # a group's own list keeps 4096-element tiles from 2048 tiles on, and halves below
+    for n_tiles, tlen in ((2048, 4096), (2047, 2048), (1024, 2048), (1023, 1024)):
+        t = lists_of([n_tiles * 4096], [])
+        own = t[t[:, 4] == 0]
+        assert {int(x) for x in own[:, 5]} == {tlen}, (n_tiles, tlen)
+    # double-length tiles by default only when they make one batch (<= 3584 workgroups) and the
+    # ordinary ones do not (> 4096); kept for the tuner (list 3) when merely long enough
+    for n_long, which in ((3584, 2), (3585, 3), (2049, 2), (2048, 3), (1000, None)):
+        t = lists_of([n_long * 8192], [])
+        ids = {int(x) for x in t[:, 4]} - {0, 1}
+        assert ids == ({which} if which else set()), (n_long, ids)
