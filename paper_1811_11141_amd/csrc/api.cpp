@@ -43,7 +43,8 @@ int make_plan(int32_t L, const uint64_t *p, const double *tb, double tf, double 
     for (int32_t l = 0; l < L; ++l) {
         if (p[l] == 0) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] is 0");
         if (p[l] > (1ull << 40)) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] too large");
-        if (!good_time(tb[l])) return fail(MGWFBP_EINVAL, "tb_ms[" + std::to_string(l) + "] must be finite and >= 0");
+        if (!good_time(tb[l]))
+            return fail(MGWFBP_EINVAL, "tb_ms[" + std::to_string(l) + "] must be finite and >= 0");
     }
     mgwfbp_plan_t *pl = new (std::nothrow) mgwfbp_plan_t();
     if (!pl) return fail(MGWFBP_ENOMEM, "out of host memory");
@@ -130,7 +131,8 @@ uint64_t padded(uint64_t elems) { return (elems + 63) & ~uint64_t(63); }
 int check_ws(const mgwfbp_plan_t *pl, const LaunchScope &sc, void *ws, size_t bytes)
 {
     if (!ws) return fail(MGWFBP_EINVAL, "workspace is NULL");
-    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(MGWFBP_EINVAL, "workspace must be 256-byte aligned");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u)
+        return fail(MGWFBP_EINVAL, "workspace must be 256-byte aligned");
     const size_t need = static_cast<size_t>(pl->N + 1) * padded(sc.elems) * sizeof(float);
     if (bytes < need)
         return fail(MGWFBP_EINVAL, "workspace too small: need " + std::to_string(need) + " bytes");
@@ -188,7 +190,8 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     const int32_t L = pl->L, N = pl->N;
     for (int64_t i = 0; i < static_cast<int64_t>(N) * L; ++i) {
         if (!grads[i]) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is NULL");
-        if (reinterpret_cast<uintptr_t>(grads[i]) & 3u) return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is not 4-byte aligned");
+        if (reinterpret_cast<uintptr_t>(grads[i]) & 3u)
+            return fail(MGWFBP_EINVAL, "grads[" + std::to_string(i) + "] is not 4-byte aligned");
     }
     for (int32_t l = 0; l < L; ++l) {
         if (out && (!out[l] || (reinterpret_cast<uintptr_t>(out[l]) & 3u)))
@@ -269,7 +272,9 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
     if (rc) return rc;
     for (const float *src : pl->host_src)
         for (const float *o : pl->host_out)
-            if (src == o) return fail(MGWFBP_EINVAL, "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
+            if (src == o)
+                return fail(MGWFBP_EINVAL,
+                            "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
@@ -303,7 +308,8 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
         if (rc) break;
         if ((e = hipEventRecord(e0, s)) != hipSuccess) break;
         const int reps = 4;
-        for (int i = 0; i < reps && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        for (int i = 0; i < reps && !rc; ++i)
+            rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
         if (rc) break;
         if ((e = hipEventRecord(e1, s)) != hipSuccess) break;
         if ((e = hipEventSynchronize(e1)) != hipSuccess) break;
@@ -609,9 +615,11 @@ namespace {
 int check_merged(const LaunchScope &sc, void *merged, size_t bytes)
 {
     if (!merged) return fail(MGWFBP_EINVAL, "merged is NULL");
-    if (reinterpret_cast<uintptr_t>(merged) & 255u) return fail(MGWFBP_EINVAL, "merged must be 256-byte aligned");
+    if (reinterpret_cast<uintptr_t>(merged) & 255u)
+        return fail(MGWFBP_EINVAL, "merged must be 256-byte aligned");
     if (bytes < sc.elems * sizeof(float))
-        return fail(MGWFBP_EINVAL, "merged buffer too small: need " + std::to_string(sc.elems * sizeof(float)) + " bytes");
+        return fail(MGWFBP_EINVAL, "merged buffer too small: need " +
+                                       std::to_string(sc.elems * sizeof(float)) + " bytes");
     return MGWFBP_OK;
 }
 }  // namespace
@@ -654,7 +662,8 @@ int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_el
     if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
     if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) ||
         (n_elems & 3u) || (stride_elems & 3u) || stride_elems < n_elems)
-        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples of 4, stride >= n_elems");
+        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples "
+                                   "of 4, stride >= n_elems");
     return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
 }
 

@@ -30,7 +30,8 @@ struct Events {
     }
     int make(hipEvent_t *out, bool timed = true)
     {
-        const hipError_t e = timed ? hipEventCreate(out) : hipEventCreateWithFlags(out, hipEventDisableTiming);
+        const hipError_t e =
+            timed ? hipEventCreate(out) : hipEventCreateWithFlags(out, hipEventDisableTiming);
         if (e != hipSuccess) {
             set_error(std::string("hipEventCreate: ") + hipGetErrorString(e));
             return MGWFBP_EHIP;
@@ -100,10 +101,13 @@ int enqueue_iteration(mgwfbp_plan_t *pl, const double *tb, bool update, float lr
         const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
         if ((rc = launch_spin_until(elapsed_ms, pl->d_clock, cs))) return rc;
         if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) return hip_fail("hipEventRecord", e);
-        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
-        if (g_start && (e = hipEventRecord((*g_start)[k], ms)) != hipSuccess) return hip_fail("hipEventRecord", e);
+        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess)
+            return hip_fail("hipStreamWaitEvent", e);
+        if (g_start && (e = hipEventRecord((*g_start)[k], ms)) != hipSuccess)
+            return hip_fail("hipEventRecord", e);
         if ((rc = run_scope(pl, static_cast<int32_t>(k), update, lr, momentum, nullptr, 0, ms))) return rc;
-        if (g_finish && (e = hipEventRecord((*g_finish)[k], ms)) != hipSuccess) return hip_fail("hipEventRecord", e);
+        if (g_finish && (e = hipEventRecord((*g_finish)[k], ms)) != hipSuccess)
+            return hip_fail("hipEventRecord", e);
     }
     // groups run in order on the communication stream: its end is the end of the iteration (Eq. 8)
     return launch_spin(0.0, ms, pl->d_clock + 1);

@@ -115,7 +115,8 @@ struct mgwfbp_plan_s {
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
     uint64_t binding_generation = 0;  // bumped whenever the device tables are released or replaced
-    uint64_t *d_clock = nullptr;  // two words at its end: device clock at the start and at the end of an iteration
+    // two words at the end of d_blob: device clock at the start and at the end of an iteration
+    uint64_t *d_clock = nullptr;
     mgwfbp::DeviceTables dt;
 };
 
