@@ -122,7 +122,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                 } else {
                     g.needs_lds = true;
                 }
-                slow.push_back(t);
+                // (a lone layer of exactly one tile length runs the fast code like any full tile)
+                (t.nseg == 1 && t.n == tile_len ? full : slow).push_back(t);
             }
         };
         // A launch of this group alone is short: below about 2048 workgroups it cannot fill the

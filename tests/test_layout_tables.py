@@ -208,3 +208,11 @@ def test_layout_thresholds_exactly():
         t = lists_of([n_long * 8192], [])
         ids = {int(x) for x in t[:, 4]} - {0, 1}
         assert ids == ({which} if which else set()), (n_long, ids)
+
+
+def test_layout_lone_short_layer_of_exactly_one_tile_length():
+    """Found by a long property run: two short layers that do not fit one gather tile become lone
+    direct tiles; the one that is exactly one tile long counts as a full tile (listed after the
+    ragged one)."""
+    p = np.array([1] * 11 + [2049, 2048], dtype=np.uint64)
+    check_layout(p, [13], 8192, 4096)
