@@ -230,6 +230,26 @@ def main():
         extra["per_group_graph"] = {"groups": n_groups, "us_per_step": round(us, 2),
                                     "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
         del graphs
+        # the update without writing the averaged gradients out (out[] not bound): N + 4 units
+        alt = []
+        for st in sets:
+            pa = new_plan()
+            pa.bind(st["grads"], None, st["w"], st["v"])
+            alt.append(pa)
+        for i in range(w2):
+            alt[i % n_sets].step(0.1, 0.9, stream=stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(k2):
+            alt[i % n_sets].step(0.1, 0.9, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / k2
+        extra["step_without_out"] = {"us_per_step": round(us, 2),
+                                     "GBps_algorithmic": round(4 * (N + 4) * P / (us * 1e-6) / 1e9, 1)}
+        for pa in alt:
+            pa.destroy()
         # the same pass after mgwfbp_tune (set-up, untimed) has picked the launch shape
         if not args.tune and args.variant == "fused":
             alt, picks = [], []
