@@ -70,9 +70,11 @@ enum {
     MGWFBP_OPT_NONTEMPORAL = 3, /* 1: streaming (non-temporal) loads and stores; 0: plain            */
     MGWFBP_OPT_PACE = 4,        /* pause between two loads of a wave, units of ~64 clocks, 0..16;
                                    -1 (default): chosen per launch from its size and N           */
-    MGWFBP_OPT_LONG_TILES = 5,  /* whole-plan fused reduce pass on tiles of 2 * tile_elems (only for
-                                   tile_elems = 4096): 1 always, 0 never, -1 (default) when that puts
-                                   every workgroup on the chip at once and tile_elems does not      */
+    MGWFBP_OPT_LONG_TILES = 5,  /* tile length of the whole-plan fused reduce pass (only next to
+                                   tile_elems = 4096).  -1 (default): the length among 4096, 5120,
+                                   6144, 7168, 8192 that fills the chip's batches of workgroups best
+                                   for this plan's size; 0: tile_elems; 1 or 8192, 5120, 6144, 7168:
+                                   that length                                                     */
     MGWFBP_OPT_PAD_ELEMS = 6    /* layout of the merged buffers.  0 (default): the layers of a group
                                    follow each other without padding, as the cost model counts them
                                    (Condition 3).  4: every layer starts on a 16-byte boundary; the
@@ -150,9 +152,9 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             one: the tile gathers whole short segments and `start` is its offset in the
  *             plan-wide merged order.
  *             list 0: the per-group lists (group after group); list 1: the second copy used
- *             by whole-plan launches; list 2 or 3 (when built): the whole plan in
- *             double-length tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses
- *             it by default, 3 if only mgwfbp_tune may select it.
+ *             by whole-plan launches; list 2 or 3 (when built): the whole plan in longer
+ *             tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses it by default,
+ *             3 if only mgwfbp_tune may select it.
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too
  *             few workgroups).

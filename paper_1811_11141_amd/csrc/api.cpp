@@ -201,6 +201,11 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     }
     release_device(pl);
     pl->tuned = mgwfbp_plan_s::Tuned();
+    // the device that owns the tables; its size enters the choice of tile lengths
+    if (hipGetDevice(&pl->device) != hipSuccess) return fail(MGWFBP_EHIP, "hipGetDevice failed: no usable HIP device");
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, pl->device) == hipSuccess && cus > 0)
+        pl->n_cus = cus;
 
     std::vector<const float *> src_tbl;
     std::vector<float *> out_tbl, w_tbl, v_tbl;
@@ -235,8 +240,7 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
         std::memcpy(host.data() + o_v, v_tbl.data(), v_tbl.size() * sizeof(void *));
     }
 
-    hipError_t e = hipGetDevice(&pl->device);
-    if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    hipError_t e = hipSuccess;
     e = hipMalloc(&pl->d_blob, total);
     if (e != hipSuccess) {
         pl->d_blob = nullptr;
@@ -485,7 +489,8 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
         }
         return MGWFBP_OK;
     case MGWFBP_OPT_LONG_TILES:
-        if (value < -1 || value > 1) return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0 or 1");
+        if (!(value >= -1 && value <= 1) && value != 5120 && value != 6144 && value != 7168 && value != 8192)
+            return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0, 1, 5120, 6144, 7168 or 8192");
         pl->opt.long_tiles = static_cast<int>(value);
         return MGWFBP_OK;
     default: return fail(MGWFBP_EINVAL, "unknown option key");

@@ -329,7 +329,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
     // register addresses the whole tile.  Each wave walks its own contiguous U KiB.
     // Pieces 8 and up (U = 16) sit 8 KiB further on: the scalar base is moved instead.
     constexpr int BIAS = U * 1024 > 4096 ? 4096 : 0;
-    static_assert(U <= 8 || U == 16, "piece offsets must fit the immediate");
+    static_assert(U >= 1 && U <= 16, "piece offsets must fit the immediate plus one base step");
     const uint32_t vo = (threadIdx.x >> 6) * (U * 1024u) + (threadIdx.x & 63u) * 16u + BIAS;
 #define MGWFBP_OFF(u) (((u) % 8) * 1024 - BIAS)
 #define MGWFBP_HI(u) (((u) / 8) * 8192)
@@ -737,7 +737,11 @@ void fused_launch_u(int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s, 
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
         if (u == 8) { if (deep) MGWFBP_LAUNCH(8, 8); else MGWFBP_LAUNCH(8, 1); return; }
         if constexpr (!STEP) {
+            // the longer tiles of the alternative whole-plan list (reduce pass only)
             if (u == 16) { if (deep) MGWFBP_LAUNCH(16, 8); else MGWFBP_LAUNCH(16, 1); return; }
+            if (u == 10) { MGWFBP_LAUNCH(10, 1); return; }
+            if (u == 12) { MGWFBP_LAUNCH(12, 1); return; }
+            if (u == 14) { MGWFBP_LAUNCH(14, 1); return; }
         }
     }
     MGWFBP_LAUNCH(0, 1);
@@ -780,10 +784,17 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
         return;
     }
     if constexpr (NW > 0) {
-        if (u == 16 && !deep) {  // double-length tiles, chosen by launch_reduce
-            k_reduce<NW, true, 16, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
-            return;
-        }
+        // longer tiles, chosen by launch_reduce
+#define MGWFBP_REDUCE_LONG(UU)                                                                  \
+    if (u == UU && !deep) {                                                                      \
+        k_reduce<NW, true, UU, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace); \
+        return;                                                                                  \
+    }
+        MGWFBP_REDUCE_LONG(10)
+        MGWFBP_REDUCE_LONG(12)
+        MGWFBP_REDUCE_LONG(14)
+        MGWFBP_REDUCE_LONG(16)
+#undef MGWFBP_REDUCE_LONG
     }
     with_shape(NW > 0, u, deep, [&](auto uc, auto dc) {
         k_reduce<NW, true, decltype(uc)::value, decltype(dc)::value>
@@ -863,12 +874,13 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
 {
     if (sc.elems == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // contiguous buffers need no tile table; the same rule as for the fused pass picks
-    // double-length tiles when they put the whole launch on the chip at once
+    // contiguous buffers need no tile table; the same rule as for the fused pass picks the tile
+    // length that fills the chip's batches of workgroups best
     uint32_t tile = sc.tile_elems;
-    if (tile == 4096 && pl.opt.long_tiles != 0 && pl.opt.nontemporal) {
-        const uint64_t n1 = (sc.elems + 4095) / 4096, n2 = (sc.elems + 8191) / 8192;
-        if (n1 > 4096 && n2 <= 3584 && n2 >= 2048) tile = 8192;
+    if (tile == 4096 && pl.opt.long_tiles == -1 && pl.opt.nontemporal) {
+        uint64_t counts[kTileChoices];
+        for (int c = 0; c < kTileChoices; ++c) counts[c] = (sc.elems + kTileChoice[c] - 1) / kTileChoice[c];
+        tile = kTileChoice[best_tile_choice(pl.N, pl.n_cus, counts)];
     }
     const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
     const float inv_n = 1.0f / static_cast<float>(pl.N);

@@ -62,7 +62,8 @@ struct Options {
     int nontemporal = 1;
     int pace = -1;  // -1: chosen per launch from its size and N
     uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4: every layer starts 16-byte aligned
-    int long_tiles = -1;  // whole-plan fused reduce on double-length tiles: -1 by rule, 0 never, 1 always
+    int long_tiles = -1;  // tile length of the whole-plan fused reduce pass: -1 by rule, 0 = tile_elems,
+                          // 1 = 8192, or 5120 / 6144 / 7168 / 8192 elements
 };
 
 struct GroupInfo {
@@ -98,8 +99,8 @@ struct mgwfbp_plan_s {
     int device = -1;
     bool all_needs_lds = false;
     uint32_t all_tile_begin = 0, all_tile_count = 0;  // whole-plan ordering of the tiles
-    // third list: the whole plan cut into tiles of twice the length, for the fused reduce pass
-    // when that puts every workgroup on the chip at once (0 tiles = not built)
+    // third list: the whole plan cut into longer tiles, for the fused reduce pass when that fills
+    // the chip's batches of workgroups better (0 tiles = not built)
     uint32_t long_tile_begin = 0, long_tile_count = 0, long_tile_elems = 0;
     std::vector<const float *> host_src;  // host copies of the bound pointers (alias checks)
     std::vector<float *> host_out;
@@ -114,6 +115,7 @@ struct mgwfbp_plan_s {
     std::vector<mgwfbp::SegDev> segs;
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
+    int n_cus = 256;  // compute units of the device the plan is bound on (MI355X until bound)
     uint64_t binding_generation = 0;  // bumped whenever the device tables are released or replaced
     // two words at the end of d_blob: device clock at the start and at the end of an iteration
     uint64_t *d_clock = nullptr;
@@ -161,6 +163,18 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                   float *const *w, float *const *v, std::vector<const float *> &src_tbl,
                   std::vector<float *> &out_tbl, std::vector<float *> &w_tbl,
                   std::vector<float *> &v_tbl);
+
+// Tile lengths the fused reduce pass can run on its fast path (8, 10, 12, 14, 16 pieces per lane)
+// and the rule that picks one for a launch.  tables.cpp
+constexpr int kTileChoices = 5;
+constexpr uint32_t kTileChoice[kTileChoices] = {4096, 5120, 6144, 7168, 8192};
+// Workgroups of the fused reduce kernel one compute unit holds at once (from its register use;
+// a test checks the table against the compiled code).
+int fused_workgroups_per_cu(int n_workers, uint32_t tile_elems);
+// Predicted efficiency (0..1] of a launch of `workgroups` when `resident` fit the chip at once.
+double launch_fill_efficiency(uint64_t workgroups, uint64_t resident, int n_cus);
+// Index into kTileChoice of the best tile length for the given workgroup counts per choice.
+int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTileChoices]);
 
 // kernels.hip
 struct LaunchScope {

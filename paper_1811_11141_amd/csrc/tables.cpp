@@ -4,6 +4,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <cmath>
 
 namespace mgwfbp {
 
@@ -12,6 +13,58 @@ namespace {
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
+
+// The fused reduce kernel needs 38-61 VGPRs up to 14 pieces per lane (8 waves per SIMD, 16
+// workgroups of two waves per compute unit) and 69 with 16 pieces (7 waves, 14 workgroups); with
+// 16 workers it holds 93 SGPRs, which also allows 7 waves only.
+int fused_workgroups_per_cu(int n_workers, uint32_t tile_elems)
+{
+    return (n_workers >= 16 || tile_elems >= 8192) ? 14 : 16;
+}
+
+// A workgroup lives for as long as its chain of N * (pieces per lane) dependent loads, tens of
+// microseconds, and the workgroups of a launch start in batches of `resident`.  Measured on
+// MI355X (single tensors of 3 k to 34 k tiles, N = 8 and 16, five tile lengths; start and end
+// times of every workgroup recorded with the device clock):
+//   * full batches run at the same rate whatever their number;
+//   * a last batch filled to at least ~65 % costs its share; one filled less costs as much as a
+//     65 % one, because a workgroup running on a nearly empty chip is bound by latency (a few
+//     stragglers cost most of a batch; a launch of exactly k batches still has them, since the
+//     first workgroups start before the rest and finish out of step);
+//   * a launch that fits the chip at once streams best with 11-13 workgroups per compute unit
+//     (5600-6600 waves in flight); up to 95 % of the slots it loses ~3 %, beyond that ~6 %, and
+//     below 11 per unit there is too little in flight.
+double launch_fill_efficiency(uint64_t workgroups, uint64_t resident, int n_cus)
+{
+    if (workgroups == 0 || resident == 0) return 1.0;
+    const double w = static_cast<double>(workgroups), s = static_cast<double>(resident);
+    if (w <= s) {
+        const double lo = 11.0 * n_cus, hi = 13.0 * n_cus;
+        if (w < lo) return 0.5 + 0.5 * w / lo;
+        if (w <= hi) return 1.0;
+        return w <= 0.95 * s ? 0.97 : 0.94;
+    }
+    const double x = w / s, k = std::floor(x), f = x - k;
+    return x / (k + std::max(f, 0.65));
+}
+
+int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTileChoices])
+{
+    int best = 0;
+    double best_eff = 0.0;
+    for (int c = 0; c < kTileChoices; ++c) {
+        // a launch of fewer than 2048 workgroups is too short to stream: not a candidate
+        if (c > 0 && workgroups[c] < 2048) break;
+        const uint64_t resident = static_cast<uint64_t>(fused_workgroups_per_cu(n_workers, kTileChoice[c])) * n_cus;
+        const double eff = launch_fill_efficiency(workgroups[c], resident, n_cus);
+        // a longer tile must promise at least 2 % to replace a shorter one
+        if (c == 0 || eff > best_eff + 0.02) {
+            best = c;
+            best_eff = eff;
+        }
+    }
+    return best;
+}
 
 void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
                   float *const *w, float *const *v, std::vector<const float *> &src_tbl,
@@ -24,9 +77,10 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     // elements one gather tile may hold: a few per lane, since each costs a table search;
     // small <= tile, so no tile of any kind exceeds tile_elems (the LDS staging size)
     const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
-    std::vector<TileDev> all_slow, all_full, long_slow, long_full;
-    // double-length tiles exist for 16 pieces per lane only (8192 elements)
-    const uint32_t long_tile = tile == 4096 && pl.opt.long_tiles != 0 ? 8192u : 0u;
+    std::vector<TileDev> all_slow, all_full;
+    // the longer tile lengths the fused reduce pass may use instead (only next to 4096)
+    const bool longer_ok = tile == 4096 && pl.opt.long_tiles != 0;
+    std::vector<TileDev> alt_slow[kTileChoices], alt_full[kTileChoices];
 
     pl.segs.clear();
     pl.tiles.clear();
@@ -141,7 +195,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         pl.tiles.insert(pl.tiles.end(), full.begin(), full.end());
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
         cut(tile, all_slow, all_full);
-        if (long_tile) cut(long_tile, long_slow, long_full);
+        if (longer_ok)
+            for (int c = 1; c < kTileChoices; ++c) cut(kTileChoice[c], alt_slow[c], alt_full[c]);
         pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
     }
     // A second copy of the tile list for whole-plan launches: every slow tile of every group
@@ -150,23 +205,46 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     pl.tiles.insert(pl.tiles.end(), all_slow.begin(), all_slow.end());
     pl.tiles.insert(pl.tiles.end(), all_full.begin(), all_full.end());
     pl.all_tile_count = static_cast<uint32_t>(all_slow.size() + all_full.size());
-    // A third copy in double-length tiles.  A workgroup lives for as long as its chain of
-    // N * (pieces per lane) dependent loads, tens of microseconds, so a launch of a few
-    // batches of workgroups ends with a partly filled batch that costs almost a full one.  When
-    // the double-length tiles put the whole launch on the chip at once (7 waves per SIMD fit:
-    // 3584 workgroups) and the ordinary tiles do not (more than 4096), the fused reduce pass
-    // uses this list; it is not long enough to keep the chip busy below 2048 workgroups.
+    // A third copy in longer tiles for the fused reduce pass, whose fast path exists for 8 to 16
+    // pieces per lane: the length that fills the batches of workgroups best (see
+    // launch_fill_efficiency), or the one the option names.  It is the default for whole-plan
+    // reduce launches when the rule prefers it to the 4096-element list; otherwise it is only
+    // kept, when long enough, for mgwfbp_tune to try.
     pl.long_tile_begin = static_cast<uint32_t>(pl.tiles.size());
     pl.long_tile_count = 0;
-    pl.long_tile_elems = long_tile;
-    const size_t n_long = long_slow.size() + long_full.size();
-    const bool by_rule = pl.all_tile_count > 4096 && n_long <= 3584 && n_long >= 2048;
-    pl.long_by_default = long_tile && (pl.opt.long_tiles == 1 || by_rule);
-    // kept also when the rule says no but the launch would be long enough: mgwfbp_tune may pick it
-    if (long_tile && (pl.opt.long_tiles == 1 || n_long >= 2048)) {
-        pl.tiles.insert(pl.tiles.end(), long_slow.begin(), long_slow.end());
-        pl.tiles.insert(pl.tiles.end(), long_full.begin(), long_full.end());
-        pl.long_tile_count = static_cast<uint32_t>(n_long);
+    pl.long_tile_elems = 0;
+    pl.long_by_default = false;
+    if (longer_ok) {
+        uint64_t counts[kTileChoices];
+        counts[0] = pl.all_tile_count;
+        for (int c = 1; c < kTileChoices; ++c) counts[c] = alt_slow[c].size() + alt_full[c].size();
+        int pick = 0;
+        if (pl.opt.long_tiles == -1) {
+            pick = best_tile_choice(pl.N, pl.n_cus, counts);
+            pl.long_by_default = pick != 0;
+            if (pick == 0) {  // nothing beats 4096: keep the best of the others for the tuner
+                double best_eff = 0.0;
+                for (int c = 1; c < kTileChoices && counts[c] >= 2048; ++c) {
+                    const uint64_t res = static_cast<uint64_t>(fused_workgroups_per_cu(pl.N, kTileChoice[c])) * pl.n_cus;
+                    const double eff = launch_fill_efficiency(counts[c], res, pl.n_cus);
+                    if (eff > best_eff) {
+                        best_eff = eff;
+                        pick = c;
+                    }
+                }
+            }
+        } else {
+            const uint32_t want = pl.opt.long_tiles == 1 ? 8192u : static_cast<uint32_t>(pl.opt.long_tiles);
+            for (int c = 1; c < kTileChoices; ++c)
+                if (kTileChoice[c] == want) pick = c;
+            pl.long_by_default = pick != 0;
+        }
+        if (pick != 0) {
+            pl.tiles.insert(pl.tiles.end(), alt_slow[pick].begin(), alt_slow[pick].end());
+            pl.tiles.insert(pl.tiles.end(), alt_full[pick].begin(), alt_full[pick].end());
+            pl.long_tile_count = static_cast<uint32_t>(counts[pick]);
+            pl.long_tile_elems = kTileChoice[pick];
+        }
     }
 }
 

@@ -23,7 +23,7 @@ SRC = os.path.join(libbuild.CSRC, "kernels.hip")
 
 
 @pytest.fixture(scope="module")
-def isa_lines():
+def isa_text():
     flags = [f for f in libbuild.FLAGS if f not in ("-shared", "-fPIC")]
     with tempfile.TemporaryDirectory() as td:
         out = os.path.join(td, "kernels.s")
@@ -32,7 +32,12 @@ def isa_lines():
                              capture_output=True, text=True)
         assert res.returncode == 0, res.stderr[-2000:]
         with open(out) as f:
-            lines = [l.rstrip() for l in f if l.startswith("\t") and not l.strip().startswith((";", "."))]
+            return f.read()
+
+
+@pytest.fixture(scope="module")
+def isa_lines(isa_text):
+    lines = [l.rstrip() for l in isa_text.splitlines() if l.startswith("\t") and not l.strip().startswith((";", "."))]
     assert len(lines) > 10000
     return lines
 
@@ -94,3 +99,24 @@ def test_scalar_unit_only_reads_memory(isa_lines):
     allowed = ("s_load_dword", "s_buffer_load_dword", "s_memrealtime", "s_memtime")
     bad = [m for m in scalar_mem if not m.startswith(allowed)]
     assert not bad, bad
+
+
+def test_workgroups_per_compute_unit_table_matches_the_compiled_kernels(isa_text):
+    """The launch rules assume how many workgroups of the fused reduce kernel a compute unit
+    holds: 16 (8 waves per SIMD) up to 14 pieces per lane, 14 (7 waves) with 16 pieces or with 16
+    workers.  Recompute that from the registers the compiled kernels use: 512 VGPRs per SIMD in
+    granules of 8; 800 SGPRs per SIMD, granules of 16, six more than the kernel's own count for
+    VCC, flat-scratch and XNACK; at most 8 waves."""
+    meta = re.findall(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.sgpr_count:\s+(\d+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", isa_text)
+    regs = {name: (int(sg), int(vg)) for name, sg, vg in meta}
+    seen = 0
+    for nw in (1, 2, 4, 8, 16):
+        for u in (8, 10, 12, 14, 16):
+            key = [k for k in regs if f"k_fusedILi{nw}ELi{u}ELb0ELb1ELi1E" in k]
+            assert len(key) == 1, (nw, u, key)
+            sg, vg = regs[key[0]]
+            waves = min(8, 512 // (-(-vg // 8) * 8), 800 // (-(-(sg + 6) // 16) * 16))
+            expect = 14 if (nw >= 16 or u == 16) else 16
+            assert 2 * waves == expect, (nw, u, sg, vg, waves)
+            seen += 1
+    assert seen == 25
