@@ -89,7 +89,7 @@ enum {
  * which the paper derives from benchmarks of the first iterations).
  *
  *   L              number of learnable layers (>= 1)
- *   p_elems        host [L]   parameters per layer, each >= 1
+ *   p_elems        host [L]   parameters per layer, each >= 1, at most 2^40 in total
  *   tb_ms          host [L]   backward time of each layer, finite and >= 0
  *   tf_ms          forward time (a pure offset of the timeline), finite and >= 0
  *   a_ms, b_ms_per_byte       all-reduce cost T_ar(M) = a + b*M (Eq. 9), finite and >= 0

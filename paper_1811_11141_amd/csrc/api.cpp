@@ -3,8 +3,10 @@
 // contract of every call.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -30,47 +32,46 @@ int fail(int code, const std::string &msg)
 
 bool good_time(double x) { return std::isfinite(x) && x >= 0.0; }
 
+// Checks the model description and fills the parts of a plan that do not depend on the merge
+// decision.  Exceptions (allocation failure) propagate to the guarded() wrapper of the caller.
 int make_plan(int32_t L, const uint64_t *p, const double *tb, double tf, double a, double b,
-              int32_t N, mgwfbp_plan_t **out)
+              int32_t N, std::unique_ptr<mgwfbp_plan_t> &out)
 {
-    if (!out) return fail(MGWFBP_EINVAL, "out is NULL");
-    *out = nullptr;
     if (L < 1 || L > (1 << 20)) return fail(MGWFBP_EINVAL, "L must be in [1, 2^20]");
     if (N < 1 || N > 1024) return fail(MGWFBP_EINVAL, "N must be in [1, 1024]");
     if (!p || !tb) return fail(MGWFBP_EINVAL, "p_elems or tb_ms is NULL");
     if (!good_time(tf) || !good_time(a) || !good_time(b))
         return fail(MGWFBP_EINVAL, "tf_ms, a_ms and b_ms_per_byte must be finite and >= 0");
+    // 2^40 elements (4 TiB of fp32) in total keeps every byte count below, times N + 1 <= 1025
+    // workspace copies, far inside 64 bits
+    const uint64_t kMaxTotal = 1ull << 40;
+    uint64_t total = 0;
     for (int32_t l = 0; l < L; ++l) {
         if (p[l] == 0) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] is 0");
-        if (p[l] > (1ull << 40)) return fail(MGWFBP_EINVAL, "p_elems[" + std::to_string(l) + "] too large");
+        if (p[l] > kMaxTotal || (total += p[l]) > kMaxTotal)
+            return fail(MGWFBP_EINVAL, "p_elems[0.." + std::to_string(l) + "] exceed 2^40 elements in total");
         if (!good_time(tb[l]))
             return fail(MGWFBP_EINVAL, "tb_ms[" + std::to_string(l) + "] must be finite and >= 0");
     }
-    mgwfbp_plan_t *pl = new (std::nothrow) mgwfbp_plan_t();
-    if (!pl) return fail(MGWFBP_ENOMEM, "out of host memory");
-    try {
-        pl->L = L;
-        pl->N = N;
-        pl->p.assign(p, p + L);
-        pl->tb.assign(tb, tb + L);
-        pl->tf = tf;
-        pl->a = a;
-        pl->b = b;
-        // mu_b(l) = tau_b(l) + t_b(l) with tau_b from Eq. 6: accumulate from the top layer down
-        pl->mu_b.assign(L, 0.0);
-        double t = tf;
-        for (int32_t l = L - 1; l >= 0; --l) {
-            t = t + tb[l];
-            pl->mu_b[l] = t;
-        }
-        pl->merged.assign(L, 0);
-        // 8 float4 per lane and worker in the fused kernel
-        pl->opt.tile_elems = 4096;
-    } catch (const std::bad_alloc &) {
-        delete pl;
-        return fail(MGWFBP_ENOMEM, "out of host memory");
+    std::unique_ptr<mgwfbp_plan_t> pl(new mgwfbp_plan_t());
+    pl->L = L;
+    pl->N = N;
+    pl->p.assign(p, p + L);
+    pl->tb.assign(tb, tb + L);
+    pl->tf = tf;
+    pl->a = a;
+    pl->b = b;
+    // mu_b(l) = tau_b(l) + t_b(l) with tau_b from Eq. 6: accumulate from the top layer down
+    pl->mu_b.assign(L, 0.0);
+    double t = tf;
+    for (int32_t l = L - 1; l >= 0; --l) {
+        t = t + tb[l];
+        pl->mu_b[l] = t;
     }
-    *out = pl;
+    pl->merged.assign(L, 0);
+    // 8 float4 per lane and worker in the fused kernel
+    pl->opt.tile_elems = 4096;
+    out = std::move(pl);
     return MGWFBP_OK;
 }
 
@@ -274,11 +275,14 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
 {
     int rc = check_bound(pl, true, false);
     if (rc) return rc;
-    for (const float *src : pl->host_src)
+    {
+        std::vector<const float *> srcs(pl->host_src);
+        std::sort(srcs.begin(), srcs.end());
         for (const float *o : pl->host_out)
-            if (src == o)
+            if (std::binary_search(srcs.begin(), srcs.end(), o))
                 return fail(MGWFBP_EINVAL,
                             "mgwfbp_tune repeats the pass: out[] must not alias a gradient tensor");
+    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
@@ -376,14 +380,13 @@ extern "C" {
 int mgwfbp_plan(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
                 double a_ms, double b_ms_per_byte, int32_t N, int32_t mode, mgwfbp_plan_t **out)
 {
-    if (mode < MGWFBP_MODE_OPTIMAL || mode > MGWFBP_MODE_SINGLE) {
-        if (out) *out = nullptr;
-        return fail(MGWFBP_EINVAL, "unknown mode");
-    }
-    int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, out);
-    if (rc) return rc;
-    mgwfbp_plan_t *pl = *out;
-    try {
+    if (!out) return guarded([]() -> int { return fail(MGWFBP_EINVAL, "out is NULL"); });
+    *out = nullptr;
+    return guarded([&]() -> int {
+        if (mode < MGWFBP_MODE_OPTIMAL || mode > MGWFBP_MODE_SINGLE) return fail(MGWFBP_EINVAL, "unknown mode");
+        std::unique_ptr<mgwfbp_plan_t> pl;
+        int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, pl);
+        if (rc) return rc;
         switch (mode) {
         case MGWFBP_MODE_OPTIMAL: plan_optimal(*pl, pl->merged); break;
         case MGWFBP_MODE_PAPER_GREEDY: plan_paper_greedy(*pl, pl->merged); break;
@@ -394,114 +397,106 @@ int mgwfbp_plan(int32_t L, const uint64_t *p_elems, const double *tb_ms, double 
             break;
         }
         finish_plan(*pl);
-    } catch (const std::bad_alloc &) {
-        delete pl;
-        *out = nullptr;
-        return fail(MGWFBP_ENOMEM, "out of host memory");
-    }
-    return MGWFBP_OK;
+        *out = pl.release();
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_plan_explicit(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,
                          double a_ms, double b_ms_per_byte, int32_t N, const uint8_t *merged,
                          mgwfbp_plan_t **out)
 {
-    if (!merged) {
-        if (out) *out = nullptr;
-        return fail(MGWFBP_EINVAL, "merged is NULL");
-    }
-    int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, out);
-    if (rc) return rc;
-    mgwfbp_plan_t *pl = *out;
-    if (merged[0]) {
-        delete pl;
-        *out = nullptr;
-        return fail(MGWFBP_EINVAL, "merged[0] must be 0: the lowest layer has nothing below it");
-    }
-    try {
+    if (!out) return guarded([]() -> int { return fail(MGWFBP_EINVAL, "out is NULL"); });
+    *out = nullptr;
+    return guarded([&]() -> int {
+        if (!merged) return fail(MGWFBP_EINVAL, "merged is NULL");
+        std::unique_ptr<mgwfbp_plan_t> pl;
+        int rc = make_plan(L, p_elems, tb_ms, tf_ms, a_ms, b_ms_per_byte, N, pl);
+        if (rc) return rc;
+        if (merged[0])
+            return fail(MGWFBP_EINVAL, "merged[0] must be 0: the lowest layer has nothing below it");
         for (int32_t l = 0; l < L; ++l) pl->merged[l] = merged[l] ? 1 : 0;
         finish_plan(*pl);
-    } catch (const std::bad_alloc &) {
-        delete pl;
-        *out = nullptr;
-        return fail(MGWFBP_ENOMEM, "out of host memory");
-    }
-    return MGWFBP_OK;
+        *out = pl.release();
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_plan_info(const mgwfbp_plan_t *pl, int32_t *n_groups, int32_t *group_of_layer,
                      uint64_t *offset_in_group, uint64_t *group_elems, double *t_iter_ms,
                      double *t_iter_wfbp_ms)
 {
-    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
-    if (n_groups) *n_groups = static_cast<int32_t>(pl->groups.size());
-    if (group_of_layer) std::memcpy(group_of_layer, pl->group_of_layer.data(), sizeof(int32_t) * pl->L);
-    if (offset_in_group) std::memcpy(offset_in_group, pl->off_in_group.data(), sizeof(uint64_t) * pl->L);
-    if (group_elems)
-        for (size_t k = 0; k < pl->groups.size(); ++k) group_elems[k] = pl->groups[k].elems;
-    if (t_iter_ms) *t_iter_ms = pl->t_iter;
-    if (t_iter_wfbp_ms) *t_iter_wfbp_ms = pl->t_iter_wfbp;
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+        if (n_groups) *n_groups = static_cast<int32_t>(pl->groups.size());
+        if (group_of_layer) std::memcpy(group_of_layer, pl->group_of_layer.data(), sizeof(int32_t) * pl->L);
+        if (offset_in_group) std::memcpy(offset_in_group, pl->off_in_group.data(), sizeof(uint64_t) * pl->L);
+        if (group_elems)
+            for (size_t k = 0; k < pl->groups.size(); ++k) group_elems[k] = pl->groups[k].elems;
+        if (t_iter_ms) *t_iter_ms = pl->t_iter;
+        if (t_iter_wfbp_ms) *t_iter_wfbp_ms = pl->t_iter_wfbp;
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_plan_timeline(const mgwfbp_plan_t *pl, double *mu_b, double *group_start,
                          double *group_finish)
 {
-    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
-    if (mu_b) std::memcpy(mu_b, pl->mu_b.data(), sizeof(double) * pl->L);
-    for (size_t k = 0; k < pl->groups.size(); ++k) {
-        if (group_start) group_start[k] = pl->groups[k].start_ms;
-        if (group_finish) group_finish[k] = pl->groups[k].finish_ms;
-    }
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+        if (mu_b) std::memcpy(mu_b, pl->mu_b.data(), sizeof(double) * pl->L);
+        for (size_t k = 0; k < pl->groups.size(); ++k) {
+            if (group_start) group_start[k] = pl->groups[k].start_ms;
+            if (group_finish) group_finish[k] = pl->groups[k].finish_ms;
+        }
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
 {
-    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
-    if (pl->bound) return fail(MGWFBP_ESTATE, "options must be set before mgwfbp_bind");
-    switch (key) {
-    case MGWFBP_OPT_TILE_ELEMS:
-        // upper bound: a tile is staged whole in LDS by the pack / unpack kernels (32 KiB)
-        if (value < 1024 || value > 8192 || (value % 1024) != 0)
-            return fail(MGWFBP_EINVAL, "tile_elems must be a multiple of 1024 in [1024, 8192]");
-        pl->opt.tile_elems = static_cast<uint32_t>(value);
-        return MGWFBP_OK;
-    case MGWFBP_OPT_SMALL_ELEMS:
-        if (value < 0 || value > 8192) return fail(MGWFBP_EINVAL, "small_elems must be in [0, 8192]");
-        pl->opt.small_elems = static_cast<uint32_t>(value);
-        return MGWFBP_OK;
-    case MGWFBP_OPT_NONTEMPORAL:
-        if (value != 0 && value != 1) return fail(MGWFBP_EINVAL, "nontemporal must be 0 or 1");
-        pl->opt.nontemporal = static_cast<int>(value);
-        return MGWFBP_OK;
-    case MGWFBP_OPT_PACE:
-        if (value < -1 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [-1, 16]");
-        pl->opt.pace = static_cast<int>(value);
-        return MGWFBP_OK;
-    case MGWFBP_OPT_PAD_ELEMS:
-        if (value != 0 && value != 4) return fail(MGWFBP_EINVAL, "pad_elems must be 0 or 4");
-        pl->opt.pad_elems = static_cast<uint32_t>(value);
-        try {
+    return guarded([&]() -> int {
+        if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
+        if (pl->bound) return fail(MGWFBP_ESTATE, "options must be set before mgwfbp_bind");
+        switch (key) {
+        case MGWFBP_OPT_TILE_ELEMS:
+            // upper bound: a tile is staged whole in LDS by the pack / unpack kernels (32 KiB)
+            if (value < 1024 || value > 8192 || (value % 1024) != 0)
+                return fail(MGWFBP_EINVAL, "tile_elems must be a multiple of 1024 in [1024, 8192]");
+            pl->opt.tile_elems = static_cast<uint32_t>(value);
+            return MGWFBP_OK;
+        case MGWFBP_OPT_SMALL_ELEMS:
+            if (value < 0 || value > 8192) return fail(MGWFBP_EINVAL, "small_elems must be in [0, 8192]");
+            pl->opt.small_elems = static_cast<uint32_t>(value);
+            return MGWFBP_OK;
+        case MGWFBP_OPT_NONTEMPORAL:
+            if (value != 0 && value != 1) return fail(MGWFBP_EINVAL, "nontemporal must be 0 or 1");
+            pl->opt.nontemporal = static_cast<int>(value);
+            return MGWFBP_OK;
+        case MGWFBP_OPT_PACE:
+            if (value < -1 || value > 16) return fail(MGWFBP_EINVAL, "pace must be in [-1, 16]");
+            pl->opt.pace = static_cast<int>(value);
+            return MGWFBP_OK;
+        case MGWFBP_OPT_PAD_ELEMS:
+            if (value != 0 && value != 4) return fail(MGWFBP_EINVAL, "pad_elems must be 0 or 4");
+            pl->opt.pad_elems = static_cast<uint32_t>(value);
             finish_plan(*pl);  // offsets and group sizes follow the layout
-        } catch (const std::bad_alloc &) {
-            return fail(MGWFBP_ENOMEM, "out of host memory");
+            return MGWFBP_OK;
+        case MGWFBP_OPT_LONG_TILES:
+            if (!(value >= -1 && value <= 1) && value != 5120 && value != 6144 && value != 7168 && value != 8192)
+                return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0, 1, 5120, 6144, 7168 or 8192");
+            pl->opt.long_tiles = static_cast<int>(value);
+            return MGWFBP_OK;
+        default: return fail(MGWFBP_EINVAL, "unknown option key");
         }
-        return MGWFBP_OK;
-    case MGWFBP_OPT_LONG_TILES:
-        if (!(value >= -1 && value <= 1) && value != 5120 && value != 6144 && value != 7168 && value != 8192)
-            return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0, 1, 5120, 6144, 7168 or 8192");
-        pl->opt.long_tiles = static_cast<int>(value);
-        return MGWFBP_OK;
-    default: return fail(MGWFBP_EINVAL, "unknown option key");
-    }
+    });
 }
 
 int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *segments,
                        size_t segments_cap, uint64_t *n_tiles, uint64_t *tiles, size_t tiles_cap)
 {
-    if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
-    try {
+    return guarded([&]() -> int {
+        if (!pl) return fail(MGWFBP_EINVAL, "plan is NULL");
         // the tables are built on a copy, from placeholder pointers that are only inspected for
         // their alignment and never dereferenced; the copy owns no device memory
         mgwfbp_plan_t tmp = *pl;
@@ -537,15 +532,14 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
                     r[4] = tmp.long_by_default ? 2 : 3;
                     r[5] = tmp.long_tile_elems;
                 }
-                if (!r[4])
-                    for (const GroupInfo &g : tmp.groups)
-                        if (i >= g.tile_begin && i < g.tile_end) r[5] = g.tile_elems;
             }
+            // the per-group lists carry their own (possibly halved) tile length
+            for (const GroupInfo &g : tmp.groups)
+                for (size_t i = g.tile_begin; i < g.tile_end; ++i)
+                    tiles[MGWFBP_LAYOUT_TILE_COLS * i + 5] = g.tile_elems;
         }
-    } catch (const std::bad_alloc &) {
-        return fail(MGWFBP_ENOMEM, "out of host memory");
-    }
-    return MGWFBP_OK;
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, float *const *w,
@@ -556,59 +550,71 @@ int mgwfbp_bind(mgwfbp_plan_t *pl, const float *const *grads, float *const *out,
 
 int mgwfbp_workspace_bytes(const mgwfbp_plan_t *pl, int32_t group, size_t *bytes)
 {
-    if (!pl || !bytes) return fail(MGWFBP_EINVAL, "plan or bytes is NULL");
-    uint64_t elems;
-    if (group == -1) elems = pl->total_elems;
-    else if (group >= 0 && group < static_cast<int32_t>(pl->groups.size())) elems = pl->groups[group].elems;
-    else return fail(MGWFBP_EINVAL, "group out of range");
-    *bytes = static_cast<size_t>(pl->N + 1) * padded(elems) * sizeof(float);
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        if (!pl || !bytes) return fail(MGWFBP_EINVAL, "plan or bytes is NULL");
+        uint64_t elems;
+        if (group == -1) elems = pl->total_elems;
+        else if (group >= 0 && group < static_cast<int32_t>(pl->groups.size())) elems = pl->groups[group].elems;
+        else return fail(MGWFBP_EINVAL, "group out of range");
+        *bytes = static_cast<size_t>(pl->N + 1) * padded(elems) * sizeof(float);
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace,
                               size_t workspace_bytes, void *hip_stream)
 {
-    return run_scope(pl, group, false, 0.0f, 0.0f, workspace, workspace_bytes, hip_stream);
+    return guarded([&]() -> int {
+        return run_scope(pl, group, false, 0.0f, 0.0f, workspace, workspace_bytes, hip_stream);
+    });
 }
 
 int mgwfbp_step(mgwfbp_plan_t *pl, int32_t group, float lr, float momentum, void *workspace,
                 size_t workspace_bytes, void *hip_stream)
 {
-    return run_scope(pl, group, true, lr, momentum, workspace, workspace_bytes, hip_stream);
+    return guarded([&]() -> int {
+        return run_scope(pl, group, true, lr, momentum, workspace, workspace_bytes, hip_stream);
+    });
 }
 
 int mgwfbp_pack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
                 void *hip_stream)
 {
-    int rc = check_bound(pl, false, false);
-    if (rc) return rc;
-    LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
-    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
-    return launch_pack(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        LaunchScope sc{};
+        if ((rc = scope_of(pl, group, sc))) return rc;
+        if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+        return launch_pack(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+    });
 }
 
 int mgwfbp_reduce(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
                   void *hip_stream)
 {
-    int rc = check_bound(pl, false, false);
-    if (rc) return rc;
-    LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
-    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
-    return launch_reduce(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        LaunchScope sc{};
+        if ((rc = scope_of(pl, group, sc))) return rc;
+        if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+        return launch_reduce(*pl, sc, static_cast<float *>(workspace), padded(sc.elems), hip_stream);
+    });
 }
 
 int mgwfbp_unpack(mgwfbp_plan_t *pl, int32_t group, void *workspace, size_t workspace_bytes,
                   void *hip_stream)
 {
-    int rc = check_bound(pl, true, false);
-    if (rc) return rc;
-    LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
-    if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
-    const float *reduced = static_cast<float *>(workspace) + static_cast<uint64_t>(pl->N) * padded(sc.elems);
-    return launch_unpack(*pl, sc, reduced, false, 0.0f, 0.0f, hip_stream);
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, true, false);
+        if (rc) return rc;
+        LaunchScope sc{};
+        if ((rc = scope_of(pl, group, sc))) return rc;
+        if ((rc = check_ws(pl, sc, workspace, workspace_bytes))) return rc;
+        const float *reduced = static_cast<float *>(workspace) + static_cast<uint64_t>(pl->N) * padded(sc.elems);
+        return launch_unpack(*pl, sc, reduced, false, 0.0f, 0.0f, hip_stream);
+    });
 }
 
 int mgwfbp_tune(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chosen_ms)
@@ -632,95 +638,107 @@ int check_merged(const LaunchScope &sc, void *merged, size_t bytes)
 int mgwfbp_pack_reduce(mgwfbp_plan_t *pl, int32_t group, void *merged, size_t merged_bytes,
                        void *hip_stream)
 {
-    int rc = check_bound(pl, false, false);
-    if (rc) return rc;
-    LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc, true))) return rc;
-    if ((rc = check_merged(sc, merged, merged_bytes))) return rc;
-    return launch_fused(*pl, sc, false, 0.0f, 0.0f, hip_stream, static_cast<float *>(merged));
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        LaunchScope sc{};
+        if ((rc = scope_of(pl, group, sc, true))) return rc;
+        if ((rc = check_merged(sc, merged, merged_bytes))) return rc;
+        return launch_fused(*pl, sc, false, 0.0f, 0.0f, hip_stream, static_cast<float *>(merged));
+    });
 }
 
 int mgwfbp_unpack_update(mgwfbp_plan_t *pl, int32_t group, const void *merged, size_t merged_bytes,
                          int32_t update, float lr, float momentum, void *hip_stream)
 {
-    int rc = check_bound(pl, !update, update != 0);
-    if (rc) return rc;
-    if (update && (!std::isfinite(lr) || !std::isfinite(momentum)))
-        return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
-    LaunchScope sc{};
-    if ((rc = scope_of(pl, group, sc))) return rc;
-    if ((rc = check_merged(sc, const_cast<void *>(merged), merged_bytes))) return rc;
-    return launch_unpack(*pl, sc, static_cast<const float *>(merged), update != 0, lr, momentum, hip_stream);
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, !update, update != 0);
+        if (rc) return rc;
+        if (update && (!std::isfinite(lr) || !std::isfinite(momentum)))
+            return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
+        LaunchScope sc{};
+        if ((rc = scope_of(pl, group, sc))) return rc;
+        if ((rc = check_merged(sc, const_cast<void *>(merged), merged_bytes))) return rc;
+        return launch_unpack(*pl, sc, static_cast<const float *>(merged), update != 0, lr, momentum, hip_stream);
+    });
 }
 
 int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream)
 {
-    if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
-    if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) || (n_elems & 3u))
-        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned and n_elems a multiple of 4");
-    return launch_probe_copy(src, dst, n_elems, hip_stream);
+    return guarded([&]() -> int {
+        if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
+        if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) || (n_elems & 3u))
+            return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned and n_elems a multiple of 4");
+        return launch_probe_copy(src, dst, n_elems, hip_stream);
+    });
 }
 
 int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_elems,
                          uint64_t n_elems, float *dst, void *hip_stream)
 {
-    if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
-    if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) ||
-        (n_elems & 3u) || (stride_elems & 3u) || stride_elems < n_elems)
-        return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples "
-                                   "of 4, stride >= n_elems");
-    return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
+    return guarded([&]() -> int {
+        if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
+        if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) ||
+            (n_elems & 3u) || (stride_elems & 3u) || stride_elems < n_elems)
+            return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples "
+                                       "of 4, stride >= n_elems");
+        return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
+    });
 }
 
 int mgwfbp_fit_cost(int32_t n, const double *bytes, const double *ms, double *a_ms,
                     double *b_ms_per_byte)
 {
-    if (!bytes || !ms || !a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
-    if (n < 2) return fail(MGWFBP_EINVAL, "need at least two measurements");
-    double sx = 0, sy = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        if (!std::isfinite(bytes[i]) || !std::isfinite(ms[i]) || bytes[i] < 0)
-            return fail(MGWFBP_EINVAL, "measurements must be finite, sizes >= 0");
-        sx += bytes[i];
-        sy += ms[i];
-    }
-    const double mx = sx / n, my = sy / n;
-    double sxx = 0, sxy = 0, sxx0 = 0, sxy0 = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        sxx += (bytes[i] - mx) * (bytes[i] - mx);
-        sxy += (bytes[i] - mx) * (ms[i] - my);
-        sxx0 += bytes[i] * bytes[i];
-        sxy0 += bytes[i] * ms[i];
-    }
-    if (!(sxx > 0)) return fail(MGWFBP_EINVAL, "need at least two distinct message sizes");
-    double b = sxy / sxx;
-    double a = my - b * mx;
-    if (a < 0) {  // refit through the origin
-        a = 0;
-        b = sxy0 / sxx0;
-    }
-    if (b < 0) b = 0;
-    *a_ms = a;
-    *b_ms_per_byte = b;
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        if (!bytes || !ms || !a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
+        if (n < 2) return fail(MGWFBP_EINVAL, "need at least two measurements");
+        double sx = 0, sy = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            if (!std::isfinite(bytes[i]) || !std::isfinite(ms[i]) || bytes[i] < 0)
+                return fail(MGWFBP_EINVAL, "measurements must be finite, sizes >= 0");
+            sx += bytes[i];
+            sy += ms[i];
+        }
+        const double mx = sx / n, my = sy / n;
+        double sxx = 0, sxy = 0, sxx0 = 0, sxy0 = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            sxx += (bytes[i] - mx) * (bytes[i] - mx);
+            sxy += (bytes[i] - mx) * (ms[i] - my);
+            sxx0 += bytes[i] * bytes[i];
+            sxy0 += bytes[i] * ms[i];
+        }
+        if (!(sxx > 0)) return fail(MGWFBP_EINVAL, "need at least two distinct message sizes");
+        double b = sxy / sxx;
+        double a = my - b * mx;
+        if (a < 0) {  // refit through the origin
+            a = 0;
+            b = sxy0 / sxx0;
+        }
+        if (b < 0) b = 0;
+        *a_ms = a;
+        *b_ms_per_byte = b;
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_table2_cost(int32_t algorithm, int32_t N, double alpha, double beta, double gamma,
                        double *a_ms, double *b_ms_per_byte)
 {
-    if (!a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
-    if (N < 1) return fail(MGWFBP_EINVAL, "N must be >= 1");
-    if (!good_time(alpha) || !good_time(beta) || !good_time(gamma))
-        return fail(MGWFBP_EINVAL, "alpha, beta, gamma must be finite and >= 0");
-    const double n = static_cast<double>(N), lg = std::log2(n);
-    switch (algorithm) {
-    case 0: *a_ms = 2 * alpha * lg; *b_ms_per_byte = (2 * beta + gamma) * lg; break;
-    case 1: *a_ms = alpha * lg; *b_ms_per_byte = (beta + gamma) * lg; break;
-    case 2: *a_ms = 2 * alpha * lg; *b_ms_per_byte = 2 * beta - (2 * beta + gamma) / n + gamma; break;
-    case 3: *a_ms = 2 * (n - 1) * alpha; *b_ms_per_byte = 2 * (n - 1) / n * beta + (n - 1) / n * gamma; break;
-    default: return fail(MGWFBP_EINVAL, "algorithm must be 0..3");
-    }
-    return MGWFBP_OK;
+    return guarded([&]() -> int {
+        if (!a_ms || !b_ms_per_byte) return fail(MGWFBP_EINVAL, "NULL argument");
+        if (N < 1) return fail(MGWFBP_EINVAL, "N must be >= 1");
+        if (!good_time(alpha) || !good_time(beta) || !good_time(gamma))
+            return fail(MGWFBP_EINVAL, "alpha, beta, gamma must be finite and >= 0");
+        const double n = static_cast<double>(N), lg = std::log2(n);
+        switch (algorithm) {
+        case 0: *a_ms = 2 * alpha * lg; *b_ms_per_byte = (2 * beta + gamma) * lg; break;
+        case 1: *a_ms = alpha * lg; *b_ms_per_byte = (beta + gamma) * lg; break;
+        case 2: *a_ms = 2 * alpha * lg; *b_ms_per_byte = 2 * beta - (2 * beta + gamma) / n + gamma; break;
+        case 3: *a_ms = 2 * (n - 1) * alpha; *b_ms_per_byte = 2 * (n - 1) / n * beta + (n - 1) / n * gamma; break;
+        default: return fail(MGWFBP_EINVAL, "algorithm must be 0..3");
+        }
+        return MGWFBP_OK;
+    });
 }
 
 int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms, double tf_ms,

@@ -297,20 +297,22 @@ extern "C" int mgwfbp_iteration_capture(mgwfbp_plan_t *pl, const double *tb_ms, 
 
 extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream, double *t_iter_ms)
 {
-    if (!it || !it->exec) {
-        set_error("iteration handle is NULL");
-        return MGWFBP_EINVAL;
-    }
-    if (!it->plan->bound || it->plan->binding_generation != it->binding_generation) {
-        set_error("the plan was re-bound after the capture: capture the iteration again");
-        return MGWFBP_ESTATE;
-    }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = hipGraphLaunch(it->exec, s);
-    if (e != hipSuccess) return hip_fail("hipGraphLaunch", e);
-    if (!t_iter_ms) return MGWFBP_OK;
-    if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail("hipStreamSynchronize", e);
-    return read_t_iter(it->plan, t_iter_ms);
+    return guarded([&]() -> int {
+        if (!it || !it->exec) {
+            set_error("iteration handle is NULL");
+            return MGWFBP_EINVAL;
+        }
+        if (!it->plan->bound || it->plan->binding_generation != it->binding_generation) {
+            set_error("the plan was re-bound after the capture: capture the iteration again");
+            return MGWFBP_ESTATE;
+        }
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
+        hipError_t e = hipGraphLaunch(it->exec, s);
+        if (e != hipSuccess) return hip_fail("hipGraphLaunch", e);
+        if (!t_iter_ms) return MGWFBP_OK;
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail("hipStreamSynchronize", e);
+        return read_t_iter(it->plan, t_iter_ms);
+    });
 }
 
 extern "C" void mgwfbp_iteration_destroy(mgwfbp_iteration_t *it)

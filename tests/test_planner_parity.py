@@ -233,6 +233,10 @@ def test_error_paths():
     assert call(out=None) == mg.EINVAL
     assert call(pp=(C.c_uint64 * 3)(10, 0, 30)) == mg.EINVAL and "p_elems[1]" in mg.last_error()
     assert call(tt=(C.c_double * 3)(1.0, -2.0, 1.0)) == mg.EINVAL
+    # sizes whose byte counts would leave 64 bits: one layer, or the sum, beyond 2^40 elements
+    assert call(pp=(C.c_uint64 * 3)(10, 2**40 + 1, 30)) == mg.EINVAL and "2^40" in mg.last_error()
+    assert call(pp=(C.c_uint64 * 3)(2**39, 2**39, 1)) == mg.EINVAL and "p_elems[0..2]" in mg.last_error()
+    assert call(pp=(C.c_uint64 * 3)(2**64 - 1, 2**64 - 1, 2)) == mg.EINVAL
     assert h.value is None
     assert call() == mg.OK and h.value
     # launches before bind are a state error; no kernel is launched
