@@ -805,20 +805,24 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
 }  // namespace
 
 namespace {
-// Pause between two loads of a wave (MGWFBP_OPT_PACE; -1 = chosen here).  Measured on MI355X:
-// a launch of a few thousand workgroups (ResNet-50, GoogLeNet sized) is fastest with almost no
-// pause, because a slower workgroup lengthens the partly filled last batch; long launches gain
-// from thinning the request stream (AlexNet sized, N = 8: +2.5 % at 12; VGG-16 sized: N = 16
-// +4 % at 8, N = 8 +5 % at 12-16).  The update kernel pauses only in its gradient phase and
-// peaks earlier (4).  Copies (pack, unpack) keep the small values they were tuned with.
+// Pause between two loads of a wave (MGWFBP_OPT_PACE; -1 = chosen here).  Measured on MI355X over
+// launches of 3 k to 40 k workgroups: a launch that fits the chip in about one and a half batches
+// of resident workgroups (ResNet-50, GoogLeNet sized) is fastest with almost no pause, because a
+// slower workgroup lengthens the partly filled last batch; from about 1.6 batches on, thinning the
+// request stream gains (N = 8: +3 to +5 % at 12 around 8 k workgroups, +2.5 % AlexNet sized;
+// N = 16: +1.5 % at 8 around 7 k, +4 % VGG-16 sized; more than that loses again).  The update
+// kernel pauses only in its gradient phase: N = 8 gains 1-2 % at 8 on long launches, N = 16
+// peaks at 4.  Copies (pack, unpack) keep the small values they were tuned with.
 enum class Stream { reduce, update, copy };
 int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
 {
     if (pl.opt.pace >= 0) return pl.opt.pace;
-    const bool long_launch = workgroups >= 8192;
     switch (kind) {
-    case Stream::reduce: return !long_launch ? 2 : pl.N >= 16 ? 8 : 12;
-    case Stream::update: return !long_launch ? 2 : 4;
+    case Stream::reduce:
+        if (workgroups < 6656) return 2;
+        if (pl.N >= 16) return 8;
+        return workgroups < 7680 ? 8 : 12;
+    case Stream::update: return workgroups < 8192 ? 2 : pl.N >= 16 ? 4 : 8;
     default: return pl.N >= 16 ? 4 : 1;
     }
 }
