@@ -137,6 +137,38 @@ def test_fused_worker_counts(mg, n_workers):
         assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l}")
 
 
+@pytest.mark.parametrize("n_workers", [64, 1024])
+def test_many_workers_up_to_the_maximum(mg, n_workers):
+    """Run-time-N path at large N (1024 is the most mgwfbp_plan accepts): the fused pass, the
+    update and the materialised chain, whose pack launches one grid row per worker."""
+    w = wl.custom_workload([5000, 1, 64, 3, 12289, 4096, 1023, 7], n_workers, sigma=1e-2)
+    merged = [8, 7, 4, 3]
+    pl = make_plan(mg, w, merged, tile=2048, small=512)
+    grads = wl.make_gradients(w, 900 + n_workers, "cuda")
+    out = [torch.empty_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 6, "cuda")
+    for t in vt:
+        t.normal_(0, 0.01)
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    g_np = [to_np(r) for r in grads]
+    exp = od.merged_gradient_path(g_np, groups0(w.L, merged), w_np, v_np, lr=0.05, mu=0.8)
+    for l in range(w.L):
+        assert_same(out[l].cpu().numpy(), exp[l], f"fused avg layer {l}")
+    for t in out:
+        t.zero_()
+    ws = torch.empty(pl.workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    pl.pack_reduce_unpack(workspace=ws)
+    pl.step(0.05, 0.8)
+    torch.cuda.synchronize()
+    for l in range(w.L):
+        assert_same(out[l].cpu().numpy(), exp[l], f"materialised avg layer {l}")
+        assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l}")
+        assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l}")
+
+
 @pytest.mark.parametrize("tile,small", [(1024, 0), (1024, 1024), (4096, 2048), (8192, 2048), (8192, 8192)])
 def test_fused_tilings(mg, tile, small):
     """Several tiles per layer with ragged tails, lone short layers, long runs of tiny layers."""
