@@ -49,7 +49,12 @@ double simulate(const mgwfbp_plan_t &pl, const std::vector<uint8_t> &merged,
 // everything from layer k upwards has been sent, given that a message ends at layer k.  A
 // message covering layers k..j starts at max(best[j+1], mu_b[k]) and that start is monotone
 // in best[j+1], so the optimal prefix is also the optimal prefix of the whole plan.
-// O(L^2) time, the cost the paper quotes for Algorithm 1.
+// O(L^2) time at worst, the cost the paper quotes for Algorithm 1.  Growing the message upwards
+// makes it longer (bytes only grow) while its start can never drop below mu_b[k], so the search
+// for layer k stops as soon as a message that starts at mu_b[k] could no longer beat the best
+// one found: with compute-bound stretches in the net that is after a few layers, which keeps
+// nets of a million layers plannable.  The bound is evaluated with the same expression as the
+// candidates (floating-point addition is monotone), so the result is the unpruned one.
 void plan_optimal(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged)
 {
     const int32_t L = pl.L;
@@ -61,7 +66,9 @@ void plan_optimal(const mgwfbp_plan_t &pl, std::vector<uint8_t> &merged)
         uint64_t bytes = 0;
         for (int32_t j = k; j < L; ++j) {
             bytes += kBytesPerParam * pl.p[j];
-            const double t = std::max(best[j + 1], pl.mu_b[k]) + t_ar(pl, bytes);
+            const double cost = t_ar(pl, bytes);
+            if (!(pl.mu_b[k] + cost < best_t)) break;  // no longer message can be strictly better
+            const double t = std::max(best[j + 1], pl.mu_b[k]) + cost;
             if (t < best_t) {  // strict: on a tie keep the smaller group
                 best_t = t;
                 best_j = j;

@@ -353,3 +353,50 @@ def test_tie_between_equal_plans_keeps_the_smaller_groups(golden):
                             c["b_ms_per_byte"], 4, mode)
         assert pl.merged_layers() == [] and pl.info()["n_groups"] == 2
         assert pl.info()["t_iter_ms"] == c["t_iter"]
+
+
+def _exhaustive_recurrence(p, tb, tf, a, b):
+    """Eq. 19-23 as a recurrence over 'the lowest layer of a message', every candidate message
+    tried (no early exit), ties to the shorter message.  Returns (t_iter, merged layers)."""
+    L = len(p)
+    mu_b = op.backward_finish(tb, tf)
+    best = [0.0] * (L + 1)
+    top = [0] * L
+    for k in range(L - 1, -1, -1):
+        best_t, best_j, n_bytes = float("inf"), k, 0
+        for j in range(k, L):
+            n_bytes += op.BYTES_PER_PARAM * p[j]
+            t = max(best[j + 1], mu_b[k]) + op.t_ar(a, b, n_bytes)
+            if t < best_t:
+                best_t, best_j = t, j
+        best[k], top[k] = best_t, best_j
+    merged, k = [], 0
+    while k < L:
+        merged += list(range(k + 2, top[k] + 2))      # paper numbering: layers k+2 .. top+1 ride down
+        k = top[k] + 1
+    return best[0], sorted(merged)
+
+
+def test_early_exit_of_the_exact_planner_changes_nothing():
+    """The library stops growing a message once no longer one can be strictly better.  The same
+    recurrence without any early exit (checked here against brute force first) must give the same
+    merged set, also where many plans tie exactly (small-integer times) and on nets far beyond
+    brute force in the compute-bound, mixed and communication-bound regimes."""
+    rng = np.random.default_rng(77)
+    for _ in range(60):                                   # the exhaustive recurrence is itself exact
+        L = int(rng.integers(1, 11))
+        p = [int(x) for x in rng.integers(1, 6, L)]
+        tb = [float(x) for x in rng.integers(0, 4, L)]
+        a, b = float(rng.integers(0, 4)), float(rng.choice([0.0, 0.25, 0.5]))
+        t, merged = _exhaustive_recurrence(p, tb, 0.0, a, b)
+        assert t == op.brute_force(p, tb, 0.0, a, b)[0] == op.simulate(p, tb, 0.0, a, b, merged)
+        pl = mg.mgwfbp_plan(np.array(p, dtype=np.uint64), np.array(tb), 0.0, a, b, 4, mg.MODE_OPTIMAL)
+        assert sorted(pl.merged_layers()) == merged and pl.info()["t_iter_ms"] == t
+    for L, a, b in ((300, 0.5, 1e-6), (300, 0.5, 1e-4), (300, 5.0, 1e-3), (257, 0.0, 1e-5), (400, 30.0, 0.0)):
+        for _ in range(3):
+            p = [int(x) for x in np.round(2 ** rng.uniform(6, 16, L))]
+            tb = [float(x) for x in rng.uniform(0.1, 2, L)]
+            tf = float(rng.uniform(0, 3))
+            t, merged = _exhaustive_recurrence(p, tb, tf, a, b)
+            pl = mg.mgwfbp_plan(np.array(p, dtype=np.uint64), np.array(tb), tf, a, b, 8, mg.MODE_OPTIMAL)
+            assert sorted(pl.merged_layers()) == merged and pl.info()["t_iter_ms"] == t
