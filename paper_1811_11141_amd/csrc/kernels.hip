@@ -809,8 +809,8 @@ namespace {
 // launches of 3 k to 40 k workgroups: a launch that fits the chip in about one and a half batches
 // of resident workgroups (ResNet-50, GoogLeNet sized) is fastest with almost no pause, because a
 // slower workgroup lengthens the partly filled last batch; from about 1.6 batches on, thinning the
-// request stream gains (N = 8: +3 to +5 % at 12 around 8 k workgroups, +2.5 % AlexNet sized;
-// N = 16: +1.5 % at 8 around 7 k, +4 % VGG-16 sized; more than that loses again).  The update
+// request stream gains (N = 8: +3 to +5 % at 12 near 8 k workgroups, +2.5 % AlexNet sized;
+// N = 16: +1.5 % at 8 near 7 k, +4 % VGG-16 sized; more than that loses again).  The update
 // kernel pauses only in its gradient phase: N = 8 gains 1-2 % at 8 on long launches, N = 16
 // peaks at 4.  Copies (pack, unpack) keep the small values they were tuned with.
 enum class Stream { reduce, update, copy };
