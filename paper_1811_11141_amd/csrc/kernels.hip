@@ -13,8 +13,9 @@
 // bulk of the bytes, run fast_tile(): 128-bit streaming loads and stores written out as
 // instructions, one load in flight per wave at full occupancy, stores after all loads.  The
 // rest (ragged tails, misaligned tensors, gather tiles of many tiny layers, run-time N) runs
-// compiler-scheduled loops that issue the N loads of an element before the first add.  Arithmetic order is fixed (worker 0 first, one rounding per operation; the file
-// is compiled with -ffp-contract=off) so results are reproducible bit for bit.
+// compiler-scheduled loops that issue the N loads of an element before the first add.
+// Arithmetic order is fixed (worker 0 first, one rounding per operation; the file is compiled
+// with -ffp-contract=off) so results are reproducible bit for bit.
 #include <hip/hip_runtime.h>
 
 #include <utility>
