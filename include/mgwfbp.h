@@ -33,6 +33,8 @@
  *     Update arithmetic: v = mu*v + g; w = w - lr*v, each operation rounded separately.
  *     Pack and unpack are bit copies.
  *   - A plan handle must not be used from two threads at once.
+ *   - Launches read the plan's device tables while they run: wait for the streams they were
+ *     enqueued on before calling mgwfbp_bind again or mgwfbp_plan_destroy.
  *   - mgwfbp_bind places the plan's tables on the current device; later launches must be made
  *     with that device current (MGWFBP_ESTATE otherwise).
  */
