@@ -77,13 +77,18 @@ enum {
                                    6144, 7168, 8192 that fills the chip's batches of workgroups best
                                    for this plan's size; 0: tile_elems; 1 or 8192, 5120, 6144, 7168:
                                    that length                                                     */
-    MGWFBP_OPT_PAD_ELEMS = 6    /* layout of the merged buffers.  0 (default): the layers of a group
+    MGWFBP_OPT_PAD_ELEMS = 6,   /* layout of the merged buffers.  0 (default): the layers of a group
                                    follow each other without padding, as the cost model counts them
                                    (Condition 3).  4: every layer starts on a 16-byte boundary; the
                                    1-3 padding elements after a layer are written as zeros by pack and
                                    mgwfbp_pack_reduce and skipped by unpack.  offset_in_group,
                                    group_elems, workspace and merged-buffer sizes follow the layout;
                                    the predicted times do not change                               */
+    MGWFBP_OPT_UPDATE_WGS_PER_CU = 7 /* workgroups of the update kernel (mgwfbp_step without
+                                   workspace) one compute unit may hold.  -1 (default): chosen per
+                                   launch so that its batches of resident workgroups fill well;
+                                   0: whatever the kernel's registers allow (14; 12 for N = 16);
+                                   8, 9, 10, 11: that many.  Results do not depend on it            */
 };
 
 /*

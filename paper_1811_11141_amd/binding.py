@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libmgwfbp.so")
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
 OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES, OPT_PAD_ELEMS = 1, 2, 3, 4, 5, 6
+OPT_UPDATE_WGS_PER_CU = 7
 
 EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",

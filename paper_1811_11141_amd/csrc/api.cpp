@@ -207,6 +207,9 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, pl->device) == hipSuccess && cus > 0)
         pl->n_cus = cus;
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, pl->device) == hipSuccess && lds > 0)
+        pl->lds_per_cu = static_cast<uint32_t>(lds);
 
     std::vector<const float *> src_tbl;
     std::vector<float *> out_tbl, w_tbl, v_tbl;
@@ -289,8 +292,8 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
         if (e0) (void)hipEventDestroy(e0);
         return fail(MGWFBP_EHIP, "hipEventCreate failed");
     }
-    // candidate launch shapes: (double-length list, pause, LDS bytes that cap the workgroups per
-    // CU at 16 / 13 / 12).  Index 0 is what the rules alone would do.
+    // candidate launch shapes: (longer-tile list, pause, unused LDS bytes that cap the workgroups
+    // per CU at 11 / 10 instead of 16 or 14).  Index 0 is what the rules alone would do.
     struct Cand { int use_long; int pace; uint32_t lds; };
     std::vector<Cand> cands;
     cands.push_back({-1, -1, 0});
@@ -486,6 +489,11 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
             if (!(value >= -1 && value <= 1) && value != 5120 && value != 6144 && value != 7168 && value != 8192)
                 return fail(MGWFBP_EINVAL, "long_tiles must be -1, 0, 1, 5120, 6144, 7168 or 8192");
             pl->opt.long_tiles = static_cast<int>(value);
+            return MGWFBP_OK;
+        case MGWFBP_OPT_UPDATE_WGS_PER_CU:
+            if (value != -1 && value != 0 && !(value >= 8 && value <= 11))
+                return fail(MGWFBP_EINVAL, "update_wgs_per_cu must be -1, 0, 8, 9, 10 or 11");
+            pl->opt.update_wgs_per_cu = static_cast<int>(value);
             return MGWFBP_OK;
         default: return fail(MGWFBP_EINVAL, "unknown option key");
         }

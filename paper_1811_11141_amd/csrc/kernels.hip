@@ -832,7 +832,6 @@ int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
                  void *stream, float *merged_out)
 {
-    const int pace = sc.pace >= 0 ? sc.pace : pace_for(pl, step ? Stream::update : Stream::reduce, sc.n_tiles);
     const uint64_t base_off = sc.base_off;
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -843,12 +842,21 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     // 256 CUs x 4 SIMDs x 8 waves = 8192 wave slots = 4096 workgroups; below about half of that
     // the launch cannot saturate HBM with one load per wave and is bound by latency instead
     const bool deep = sc.n_tiles < 2048;
+    // the update runs on one tile length; what it can choose per launch is the workgroups per CU
+    const uint32_t occupancy_lds = step && !sc.occupancy_lds && nt && u == 8
+        ? update_occupancy_lds(pl.N, pl.n_cus, pl.lds_per_cu, sc.n_tiles, pl.opt.update_wgs_per_cu)
+        : sc.occupancy_lds;
+    // fewer workgroups per CU already thin the request stream: a capped update launch keeps the
+    // short pause whatever its length (measured: the long-launch pause on top costs 3-5 %)
+    const int pace = sc.pace >= 0 ? sc.pace
+                     : step && occupancy_lds && pl.opt.pace < 0 ? 2
+                     : pace_for(pl, step ? Stream::update : Stream::reduce, sc.n_tiles);
     if (step) {
-        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
-        else fused_dispatch<true, false>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        if (nt) fused_dispatch<true, true>(pl.N, u, deep, grid, occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<true, false>(pl.N, u, deep, grid, occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     } else {
-        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
-        else fused_dispatch<false, false>(pl.N, u, deep, grid, sc.occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        if (nt) fused_dispatch<false, true>(pl.N, u, deep, grid, occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
+        else fused_dispatch<false, false>(pl.N, u, deep, grid, occupancy_lds, s, pl.dt, sc.tile_begin, inv_n, lr, mu, pace, merged_out, base_off);
     }
     return check_launch("fused kernel launch");
 }

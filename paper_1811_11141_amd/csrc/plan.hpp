@@ -64,6 +64,7 @@ struct Options {
     uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4: every layer starts 16-byte aligned
     int long_tiles = -1;  // tile length of the whole-plan fused reduce pass: -1 by rule, 0 = tile_elems,
                           // 1 = 8192, or 5120 / 6144 / 7168 / 8192 elements
+    int update_wgs_per_cu = -1;  // update kernel: -1 by rule, 0 uncapped, 8..11 forced
 };
 
 struct GroupInfo {
@@ -116,6 +117,7 @@ struct mgwfbp_plan_s {
     std::vector<mgwfbp::TileDev> tiles;
     void *d_blob = nullptr;  // one device allocation holding every table
     int n_cus = 256;  // compute units of the device the plan is bound on (MI355X until bound)
+    uint32_t lds_per_cu = 160u * 1024u;  // LDS bytes per compute unit of that device
     uint64_t binding_generation = 0;  // bumped whenever the device tables are released or replaced
     // two words at the end of d_blob: device clock at the start and at the end of an iteration
     uint64_t *d_clock = nullptr;
@@ -175,6 +177,12 @@ int fused_workgroups_per_cu(int n_workers, uint32_t tile_elems);
 double launch_fill_efficiency(uint64_t workgroups, uint64_t resident, int n_cus);
 // Index into kTileChoice of the best tile length for the given workgroup counts per choice.
 int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTileChoices]);
+
+// Unused dynamic LDS (bytes) that makes the update kernel's launch of `workgroups` fill the chip
+// best by lowering the workgroups per compute unit; 0 = none.  forced_per_cu: -1 = by the rule,
+// 0 = none, 8..11 = that many.  tables.cpp
+uint32_t update_occupancy_lds(int n_workers, int n_cus, uint32_t lds_per_cu, uint64_t workgroups,
+                              int forced_per_cu);
 
 // kernels.hip
 struct LaunchScope {

@@ -66,6 +66,56 @@ int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTil
     return best;
 }
 
+// The update kernel (k_fused with the SGD-momentum step) on 4096-element tiles.  It holds 14
+// workgroups per compute unit (68 registers: 7 waves per SIMD; 12 for N = 16 -- both numbers
+// are where the steps of the measured staircase fall), its fast path exists for this tile
+// length only, and size sweeps (3 k to 20 k workgroups, N = 8 and 16) show the same staircase as
+// the reduce pass: a launch that just overflows a batch of resident workgroups pays for most of
+// another batch -- here 0.3 of one plus 0.7 of its share -- so the efficiency swings between 64 %
+// and 80 % of peak with the size of the net.  What can be chosen per launch without another tile
+// list is the batch itself: unused dynamic LDS lowers the workgroups a compute unit holds
+// (11 000 / 12 500 / 14 000 / 16 000 bytes give 11 / 10 / 9 / 8 on gfx950's 160 KiB; checked by
+// where the dips of the sweeps fall), which moves the steps of the staircase.  With fewer
+// workgroups per unit the well-filled launch itself gets a little slower (peak column, measured).
+// Returns the LDS bytes to request; 0 = leave the launch alone.
+uint32_t update_occupancy_lds(int n_workers, int n_cus, uint32_t lds_per_cu, uint64_t workgroups,
+                              int forced_per_cu)
+{
+    if (lds_per_cu != 160u * 1024u) return 0;  // the byte counts below are for this LDS size
+    if (forced_per_cu == 0) return 0;
+    if (forced_per_cu > 0) {
+        switch (forced_per_cu) {
+        case 11: return 11000;
+        case 10: return 12500;
+        case 9: return 14000;
+        case 8: return 16000;
+        default: return 0;
+        }
+    }
+    if (n_workers != 1 && n_workers != 2 && n_workers != 4 && n_workers != 8 && n_workers != 16) return 0;
+    if (workgroups < 2048 || n_cus <= 0) return 0;  // short launches run the deeper-pipelined kernel
+    struct Choice { int per_cu; uint32_t lds; double peak; };
+    const Choice choices[] = {{n_workers >= 16 ? 12 : 14, 0, 1.0}, {11, 11000, 1.0}, {10, 12500, 0.985},
+                              {9, 14000, 0.955}, {8, 16000, 0.915}};
+    uint32_t best_lds = 0;
+    double best = 0.0;
+    for (const Choice &c : choices) {
+        if (c.lds != 0 && c.per_cu >= choices[0].per_cu) continue;
+        const double x = static_cast<double>(workgroups) / (static_cast<double>(c.per_cu) * n_cus);
+        const double k = std::floor(x), f = x - k;
+        double fill;
+        if (k < 1.0) fill = std::min(1.0, x / 0.8);
+        else fill = x / (k + (f > 0.0 ? 0.3 + 0.7 * f : 0.0));
+        const double eff = c.peak * fill;
+        // a cap must promise 2 % over the uncapped launch
+        if (c.lds == 0 || eff > best + (best_lds == 0 ? 0.02 : 0.0)) {
+            best = eff;
+            best_lds = c.lds;
+        }
+    }
+    return best_lds;
+}
+
 void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
                   float *const *w, float *const *v, std::vector<const float *> &src_tbl,
                   std::vector<float *> &out_tbl, std::vector<float *> &w_tbl,

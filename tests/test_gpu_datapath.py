@@ -169,6 +169,35 @@ def test_many_workers_up_to_the_maximum(mg, n_workers):
         assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l}")
 
 
+@pytest.mark.parametrize("per_cu", [-1, 0, 8, 9, 10, 11])
+def test_update_occupancy_option_changes_nothing_but_the_launch(mg, per_cu):
+    """MGWFBP_OPT_UPDATE_WGS_PER_CU asks for unused LDS to lower the workgroups per compute unit
+    of the update kernel (by rule from 2048 workgroups on, or forced): weights, momentum and the
+    averaged gradients must not depend on it."""
+    sizes = [4096 * 2100 + 12, 5, 4096 * 3, 70001, 333]      # 2123 tiles: the rule is consulted
+    w = wl.custom_workload(sizes, 4, sigma=1e-2)
+    merged = [3, 2]
+    pl = make_plan(mg, w, merged)
+    pl.set_option(mg.OPT_UPDATE_WGS_PER_CU, per_cu)
+    grads = wl.make_gradients(w, 4242, "cuda")
+    out = [torch.empty_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 8, "cuda")
+    for t in vt:
+        t.normal_(0, 0.01)
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    g_np = [to_np(r) for r in grads]
+    exp = None
+    for _ in range(2):                                        # two steps: v != 0 feeds back
+        pl.step(0.05, 0.9)
+        exp = od.merged_gradient_path(g_np, groups0(w.L, merged), w_np, v_np, lr=0.05, mu=0.9)
+    torch.cuda.synchronize()
+    for l in range(w.L):
+        assert_same(out[l].cpu().numpy(), exp[l], f"avg layer {l}")
+        assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l}")
+        assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l}")
+
+
 @pytest.mark.parametrize("tile,small", [(1024, 0), (1024, 1024), (4096, 2048), (8192, 2048), (8192, 8192)])
 def test_fused_tilings(mg, tile, small):
     """Several tiles per layer with ragged tails, lone short layers, long runs of tiny layers."""

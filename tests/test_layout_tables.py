@@ -3,6 +3,8 @@
 The oracle side is only the definition of the merged order: groups in communication order,
 layers inside a group from the highest down (Algorithm 2 pushes layers as their backward pass
 ends), offsets = running element counts without padding (Condition 3)."""
+import os
+
 import numpy as np
 import pytest
 from hypothesis import given, settings, strategies as st
@@ -10,6 +12,8 @@ from hypothesis import given, settings, strategies as st
 from oracle import planner as op
 from paper_1811_11141_amd import binding as mg
 from paper_1811_11141_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def expected_segments(p, merged, pad=1):
@@ -226,3 +230,48 @@ def test_layout_lone_short_layer_of_exactly_one_tile_length():
     ragged one)."""
     p = np.array([1] * 11 + [2049, 2048], dtype=np.uint64)
     check_layout(p, [13], 8192, 4096)
+
+
+def _launch_rules(tmp_path, *args):
+    import subprocess
+    exe = str(tmp_path / "launch_rules")
+    if not os.path.exists(exe):
+        csrc = os.path.join(ROOT, "paper_1811_11141_amd", "csrc")
+        cmd = ["g++", "-std=c++17", "-O1", "-I", csrc, "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__",
+               os.path.join(ROOT, "tests", "capi", "launch_rules.cpp"), os.path.join(csrc, "tables.cpp"), "-o", exe]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-3000:]
+    out = subprocess.run([exe, *[str(a) for a in args]], capture_output=True, text=True, check=True).stdout
+    return {int(a): int(b) for a, b in (ln.split() for ln in out.splitlines())}
+
+
+def test_update_kernel_occupancy_rule(tmp_path):
+    """Workgroups per compute unit of the update kernel, chosen per launch.  The rule may only
+    answer with the LDS sizes measured to give 11, 10, 9, 8 workgroups per unit; it leaves short
+    launches, other LDS sizes and worker counts without a fast path alone; and on the launch sizes
+    of the MI355X sweeps it caps exactly where the uncapped launch sat in a dip (N = 8: 4002, 4502,
+    5002, 5502, 7502, 8002, 11002 workgroups lost 4.5-7 % uncapped) and nowhere it sat on a peak
+    (3002, 6002, 6502, 9002, 10002)."""
+    KB160 = 160 * 1024
+    sizes = [100, 2047, 3002, 3502, 4002, 4502, 5002, 5502, 6002, 6502, 7002, 7502, 8002, 9002, 10002,
+             11002, 14002, 20002, 34002, 10**6]
+    for n in (1, 2, 4, 8, 16):
+        r = _launch_rules(tmp_path, "update", n, 256, KB160, -1, *sizes)
+        assert set(r.values()) <= {0, 11000, 12500, 14000, 16000}
+        assert r[100] == 0 and r[2047] == 0 and r[10**6] == 0
+    r8 = _launch_rules(tmp_path, "update", 8, 256, KB160, -1, *sizes)
+    assert all(r8[w] != 0 for w in (4002, 4502, 5002, 5502, 7502, 8002, 11002))
+    assert all(r8[w] == 0 for w in (3002, 3502, 6002, 6502, 9002, 10002, 14002, 20002, 34002))
+    r16 = _launch_rules(tmp_path, "update", 16, 256, KB160, -1, *sizes)
+    assert all(r16[w] != 0 for w in (3502, 4002, 4502, 5002, 6502, 7002, 7502, 8002))
+    assert all(r16[w] == 0 for w in (3002, 6002, 9002, 20002, 34002))
+    # left alone: run-time worker counts, another LDS size, the rule switched off
+    assert set(_launch_rules(tmp_path, "update", 3, 256, KB160, -1, *sizes).values()) == {0}
+    assert set(_launch_rules(tmp_path, "update", 8, 256, 64 * 1024, -1, *sizes).values()) == {0}
+    assert set(_launch_rules(tmp_path, "update", 8, 256, KB160, 0, *sizes).values()) == {0}
+    # forced: one fixed size whatever the launch
+    for per_cu, lds in ((11, 11000), (10, 12500), (9, 14000), (8, 16000)):
+        assert set(_launch_rules(tmp_path, "update", 8, 256, KB160, per_cu, *sizes).values()) == {lds}
+    # a chip with half the compute units reaches the same fill with half the workgroups
+    half = _launch_rules(tmp_path, "update", 8, 128, KB160, -1, 2001, 2251, 2501, 3001, 3251)
+    assert half[2501] == r8[5002] and half[3001] == r8[6002] and half[3251] == r8[6502]

@@ -249,6 +249,10 @@ def test_error_paths():
     assert lib.mgwfbp_plan_set_option(h, mg.OPT_TILE_ELEMS, 1000) == mg.EINVAL
     assert lib.mgwfbp_plan_set_option(h, mg.OPT_TILE_ELEMS, 4096) == mg.OK
     assert lib.mgwfbp_plan_set_option(h, 99, 1) == mg.EINVAL
+    for bad in (-2, 1, 7, 12):
+        assert lib.mgwfbp_plan_set_option(h, mg.OPT_UPDATE_WGS_PER_CU, bad) == mg.EINVAL
+    for good in (-1, 0, 8, 11):
+        assert lib.mgwfbp_plan_set_option(h, mg.OPT_UPDATE_WGS_PER_CU, good) == mg.OK
     assert lib.mgwfbp_plan_info(None, None, None, None, None, None, None) == mg.EINVAL
     merged = (C.c_uint8 * 3)(1, 0, 0)
     h2 = C.c_void_p()
