@@ -67,9 +67,10 @@ int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTil
 }
 
 // The update kernel (k_fused with the SGD-momentum step) on 4096-element tiles.  It holds 14
-// workgroups per compute unit (68 registers: 7 waves per SIMD; 12 for N = 16 -- both numbers
-// are where the steps of the measured staircase fall), its fast path exists for this tile
-// length only, and size sweeps (3 k to 20 k workgroups, N = 8 and 16) show the same staircase as
+// workgroups per compute unit (68 VGPRs: 7 waves per SIMD; 12 for N = 16, whose 105 SGPRs
+// allow 6 -- a test recomputes both from the compiled kernels, and both are where the steps
+// of the measured staircase fall), its fast path exists for this tile length only, and size
+// sweeps (3 k to 20 k workgroups, N = 8 and 16) show the same staircase as
 // the reduce pass: a launch that just overflows a batch of resident workgroups pays for most of
 // another batch -- here 0.3 of one plus 0.7 of its share -- so the efficiency swings between 64 %
 // and 80 % of peak with the size of the net.  What can be chosen per launch without another tile

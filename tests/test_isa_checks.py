@@ -102,21 +102,28 @@ def test_scalar_unit_only_reads_memory(isa_lines):
 
 
 def test_workgroups_per_compute_unit_table_matches_the_compiled_kernels(isa_text):
-    """The launch rules assume how many workgroups of the fused reduce kernel a compute unit
-    holds: 16 (8 waves per SIMD) up to 14 pieces per lane, 14 (7 waves) with 16 pieces or with 16
-    workers.  Recompute that from the registers the compiled kernels use: 512 VGPRs per SIMD in
-    granules of 8; 800 SGPRs per SIMD, granules of 16, six more than the kernel's own count for
-    VCC, flat-scratch and XNACK; at most 8 waves."""
+    """The launch rules assume how many workgroups a compute unit holds: the fused reduce kernel
+    16 (8 waves per SIMD) up to 14 pieces per lane, 14 (7 waves) with 16 pieces or with 16 workers;
+    the update kernel 14, and 12 with 16 workers.  Recompute that from the registers the compiled
+    kernels use: 512 VGPRs per SIMD in granules of 8; 800 SGPRs per SIMD in granules of 16, a wave
+    taking sixteen more than the kernel's own count (the allowance that reproduces the batch sizes
+    measured for both kernels); at most 8 waves."""
     meta = re.findall(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.sgpr_count:\s+(\d+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", isa_text)
     regs = {name: (int(sg), int(vg)) for name, sg, vg in meta}
+
+    def workgroups_per_cu(pattern):
+        key = [k for k in regs if pattern in k]
+        assert len(key) == 1, (pattern, key)
+        sg, vg = regs[key[0]]
+        waves = min(8, 512 // (-(-vg // 8) * 8), 800 // (-(-(sg + 16) // 16) * 16))
+        return 2 * waves, (sg, vg)
+
     seen = 0
     for nw in (1, 2, 4, 8, 16):
         for u in (8, 10, 12, 14, 16):
-            key = [k for k in regs if f"k_fusedILi{nw}ELi{u}ELb0ELb1ELi1E" in k]
-            assert len(key) == 1, (nw, u, key)
-            sg, vg = regs[key[0]]
-            waves = min(8, 512 // (-(-vg // 8) * 8), 800 // (-(-(sg + 6) // 16) * 16))
-            expect = 14 if (nw >= 16 or u == 16) else 16
-            assert 2 * waves == expect, (nw, u, sg, vg, waves)
+            got, why = workgroups_per_cu(f"k_fusedILi{nw}ELi{u}ELb0ELb1ELi1E")
+            assert got == (14 if (nw >= 16 or u == 16) else 16), (nw, u, why)
             seen += 1
+        got, why = workgroups_per_cu(f"k_fusedILi{nw}ELi8ELb1ELb1ELi1E")      # with the update
+        assert got == (12 if nw >= 16 else 14), (nw, why)
     assert seen == 25
