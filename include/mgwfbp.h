@@ -199,7 +199,8 @@ int mgwfbp_bind(mgwfbp_plan_t *plan, const float *const *grads, float *const *ou
  * between loads, workgroups per compute unit -- on the bound tensors, and keep the fastest for
  * later whole-plan launches of this plan (also for mgwfbp_pack_reduce).  How well a launch
  * fills the chip depends on its size in ways the built-in rules only approximate; the result
- * is the same whatever shape is chosen.  Runs the pass up to about 90 times on `hip_stream` and
+ * is the same whatever shape is chosen.  Runs the pass up to about 500 times on `hip_stream`
+ * (fewer when a launch is long: about 2 ms of launches per candidate, 4 to 32 of them) and
  * waits for it; out[] ends up holding the reduced gradients.  out[] must be bound and must not alias
  * a gradient tensor (the pass is repeated).  A new mgwfbp_bind discards the choice.
  *   chosen      out or NULL: index of the winning candidate (0 = the built-in rules)

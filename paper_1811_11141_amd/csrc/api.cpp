@@ -303,6 +303,30 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
         cands.push_back({use_long, 2, 12500});
     }
     const mgwfbp_plan_s::Tuned before = pl->tuned;
+    // launches timed per candidate: enough of them that the timed stretch is about 2 ms (4 to 32),
+    // so that short launches are not chosen on noise; sized from two launches under the rules
+    int reps = 4;
+    {
+        pl->tuned = mgwfbp_plan_s::Tuned();
+        hipError_t pe = hipSuccess;
+        rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+        if (!rc && (pe = hipEventRecord(e0, s)) == hipSuccess) {
+            for (int i = 0; i < 2 && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
+            float ms = 0.0f;
+            if (!rc && (pe = hipEventRecord(e1, s)) == hipSuccess && (pe = hipEventSynchronize(e1)) == hipSuccess &&
+                (pe = hipEventElapsedTime(&ms, e0, e1)) == hipSuccess && ms > 0.0f) {
+                const double want = 2.0 / (static_cast<double>(ms) / 2.0);
+                reps = want < 4.0 ? 4 : want > 32.0 ? 32 : static_cast<int>(want);
+            }
+        }
+        if (rc || pe != hipSuccess) {
+            pl->tuned = before;
+            (void)hipStreamSynchronize(s);
+            (void)hipEventDestroy(e0);
+            (void)hipEventDestroy(e1);
+            return rc ? rc : fail(MGWFBP_EHIP, std::string("timing the pass: ") + hipGetErrorString(pe));
+        }
+    }
     int best = 0;
     double best_ms = 0.0;
     hipError_t e = hipSuccess;
@@ -318,7 +342,6 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
         for (int i = 0; i < 2 && !rc; ++i) rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
         if (rc) break;
         if ((e = hipEventRecord(e0, s)) != hipSuccess) break;
-        const int reps = 4;
         for (int i = 0; i < reps && !rc; ++i)
             rc = run_scope(pl, -1, false, 0.0f, 0.0f, nullptr, 0, hip_stream);
         if (rc) break;
@@ -327,7 +350,7 @@ int tune_impl(mgwfbp_plan_t *pl, void *hip_stream, int32_t *chosen, double *chos
         float ms = 0.0f;
         if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) break;
         const double per = static_cast<double>(ms) / reps;
-        // a candidate must beat the rules by more than the noise of four launches to replace them
+        // a candidate must beat the rules by more than the noise of the timed stretch to replace them
         if (c == 0 || per < best_ms * (best == 0 ? 0.99 : 1.0)) {
             best = static_cast<int>(c);
             best_ms = per;
