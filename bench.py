@@ -69,6 +69,7 @@ def parse():
 
 def main():
     args = parse()
+    args.steps, args.warmup = max(1, args.steps), max(0, args.warmup)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the other workers are "
               "replicas in the same HBM); run it with --gpus 1", file=sys.stderr)
