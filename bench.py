@@ -162,6 +162,11 @@ def main():
                     "samples": int(d.size)}
         return ms, kern
 
+    # set-up, before the W warm-up steps: one pass over every rotating set, so that no set meets
+    # the kernel (code load, address translation of freshly allocated tensors) inside the timed steps
+    for i in range(n_sets):
+        run_step(args.variant, i)
+    torch.cuda.synchronize()
     ms_per_step, kern = timed(args.variant, args.steps, args.warmup, launch_events=True)
     bytes_step = alg_bytes[args.variant]
     value = bytes_step / (ms_per_step * 1e-3) / 1e9
