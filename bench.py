@@ -15,9 +15,10 @@ after mgwfbp_tune has timed a few launch shapes at set-up and kept the fastest (
 listed; 0 = the rules won); --tune 1 applies that to the timed plans themselves.
 
 Prints one JSON line.  `value` = algorithmic bytes 4*(N+1)*P per step / wall time per step.
-`roofline.achieved` = the same bytes / average kernel duration from HIP events recorded on the
-launch stream around every 8th launch of the timed region (an event pair costs ~5 us of
-stream time, so bracketing every launch would tax the whole-job figure by 3 %).
+`roofline.achieved` = the same bytes / average duration per launch from HIP events recorded on
+the launch stream: every timed step lies inside one bracket of 8 back-to-back steps, and a
+bracket's duration / 8 is the time per launch (an event pair costs ~5 us of stream time, so a
+pair around every single launch would tax both this figure and the whole-job one by 3 %).
 """
 from __future__ import annotations
 
@@ -135,31 +136,34 @@ def main():
             for k in range(n_groups):
                 pl.pack_reduce_unpack(group=k, stream=stream)
 
-    EVERY = 8  # launches per HIP-event pair
+    EVERY = 8  # consecutive steps bracketed by one HIP-event pair
 
     def timed(variant, steps, warmup, launch_events):
         for i in range(warmup):
             run_step(variant, i)
         torch.cuda.synchronize()
-        evs = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for i in range(0, steps, EVERY)} if launch_events else {}
+        # every step lies inside exactly one bracket of up to EVERY back-to-back steps; a bracket's
+        # duration / its steps is the time per launch without the cost of the event records
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+                min(EVERY, steps - i)) for i in range(0, steps, EVERY)] if launch_events else []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            ev = evs.get(i)
-            if ev:
-                ev[0].record(stream)
+            if evs and i % EVERY == 0:
+                evs[i // EVERY][0].record(stream)
             run_step(variant, warmup + i)
-            if ev:
-                ev[1].record(stream)
+            if evs and (i % EVERY == EVERY - 1 or i == steps - 1):
+                evs[i // EVERY][1].record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms = (t1 - t0) * 1e3 / steps
         kern = None
         if evs:
-            d = np.array([a.elapsed_time(b) for a, b in evs.values()])
-            kern = {"avg_ms": float(d.mean()), "median_ms": float(np.median(d)), "min_ms": float(d.min()),
-                    "samples": int(d.size)}
+            tot = np.array([a.elapsed_time(b) for a, b, _ in evs])
+            cnt = np.array([c for _, _, c in evs], dtype=np.float64)
+            per = tot / cnt
+            kern = {"avg_ms": float(tot.sum() / cnt.sum()), "median_ms": float(np.median(per)),
+                    "min_ms": float(per.min()), "samples": int(cnt.sum())}
         return ms, kern
 
     # set-up, before the W warm-up steps: one pass over every rotating set, so that no set meets
