@@ -68,7 +68,7 @@ enum {
 /* Tuning keys for mgwfbp_plan_set_option (before mgwfbp_bind). */
 enum {
     MGWFBP_OPT_TILE_ELEMS = 1,  /* elements of one layer handled by one workgroup; multiple of 1024, <= 8192 */
-    MGWFBP_OPT_SMALL_ELEMS = 2, /* layers shorter than this share gather tiles                      */
+    MGWFBP_OPT_SMALL_ELEMS = 2, /* layers shorter than this share gather tiles (default 64)         */
     MGWFBP_OPT_NONTEMPORAL = 3, /* 1: streaming (non-temporal) loads and stores; 0: plain            */
     MGWFBP_OPT_PACE = 4,        /* pause between two loads of a wave, units of ~64 clocks, 0..16;
                                    -1 (default): chosen per launch from its size and N           */

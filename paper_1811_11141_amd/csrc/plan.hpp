@@ -58,7 +58,7 @@ struct DeviceTables {
 
 struct Options {
     uint32_t tile_elems = 4096;
-    uint32_t small_elems = 512;
+    uint32_t small_elems = 64;
     int nontemporal = 1;
     int pace = -1;  // -1: chosen per launch from its size and N
     uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4: every layer starts 16-byte aligned

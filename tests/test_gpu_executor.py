@@ -46,12 +46,16 @@ def test_iteration_results_and_timeline(mg, seed, update):
     for l in range(w.L):
         assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
     # timeline: each stand-in ends at its layer's mu_b after time zero (Eq. 6).  Time zero is
-    # the device clock read by the gate kernel just before it ends, the reported times count
-    # from an event recorded after that kernel, so "never early" holds up to a few microseconds.
+    # the device clock read by the gate kernel just before it ends; the reported times count
+    # from an event recorded after that kernel (a few microseconds later, box dependent) and are
+    # taken with another clock (rates agree to a few parts in 10^4), so "never early" is checked
+    # up to 20 us plus 0.1 % -- small against the 50 us .. 1 ms a stand-in lasts.
+    def early(t):
+        return 0.02 + 1e-3 * t
     ready, gs, gf = tl["group_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
     mu_b = np.array(op.backward_finish(tb.tolist(), 0.0))
     mu_low = np.array([mu_b[grp[-1]] for grp in groups])      # mu_b of each group's lowest layer
-    assert np.all(ready >= mu_low - 5e-3)                     # never early
+    assert np.all(ready >= mu_low - early(mu_low))            # never early
     assert np.all(ready <= mu_low + 0.2)                      # absolute deadlines: gaps do not add up
     eps = 0.02
     for k, grp in enumerate(groups):
@@ -67,7 +71,7 @@ def test_iteration_results_and_timeline(mg, seed, update):
         light = pl.run_iteration(s_comp, s_comm, timeline=False)
         assert set(light) == {"t_iter_ms"}
         assert light["t_iter_ms"] <= tl["t_iter_ms"] + 0.2
-        assert light["t_iter_ms"] >= mu_b.max() - 5e-3
+        assert light["t_iter_ms"] >= mu_b.max() - early(mu_b.max())
         for l in range(w.L):
             assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
     # the reductions overlap the backward pass: every group but the last ends before the
@@ -141,7 +145,7 @@ def test_iteration_graph_replays(mg, update):
     backward = float(tb.sum())
     eager = pl.run_iteration(s_comp, s_comm, update=False, timeline=False)["t_iter_ms"] if not update else None
     for t in times:
-        assert backward - 5e-3 <= t <= backward + 0.2, (t, backward)
+        assert backward - (0.02 + 1e-3 * backward) <= t <= backward + 0.2, (t, backward)
         if eager is not None:
             assert abs(t - eager) < 0.2, (t, eager)
     it.destroy()

@@ -203,20 +203,25 @@ def test_layout_cnn_sets_default_options():
 
 def test_layout_thresholds_exactly():
     """The three size thresholds of the table builder at their edges."""
-    def lists_of(p, merged, **opts):
+    def lists_of(p, merged, opts=()):
         pl = mg.mgwfbp_plan_explicit(np.array(p, dtype=np.uint64), np.ones(len(p)), 0.0, 0.5, 1e-6, 4, merged)
-        for k, v in opts.items():
+        for k, v in opts:
             pl.set_option(k, v)
         t = pl.layout()["tiles"]
         pl.destroy()
         return t
 
     # a gather tile holds at most 1024 elements: 511 + 511 fit, the next 8 do not
-    t = lists_of([8, 511, 511], [2, 3])
+    small512 = [(mg.OPT_SMALL_ELEMS, 512)]
+    t = lists_of([8, 511, 511], [2, 3], small512)
     own = t[t[:, 4] == 0]
     assert [(int(r[1]), int(r[3])) for r in own] == [(2, 1022), (1, 8)]
-    t = lists_of([2, 511, 511], [2, 3])
+    t = lists_of([2, 511, 511], [2, 3], small512)
     assert [(int(r[1]), int(r[3])) for r in t[t[:, 4] == 0]] == [(3, 1024)]
+    # by default only layers under 64 elements share gather tiles
+    # (communication order: 63 | 64 | 63 + 8; a lone short layer is a direct tile)
+    t = lists_of([8, 63, 64, 63], [2, 3, 4])
+    assert [(int(r[1]), int(r[3])) for r in t[t[:, 4] == 0]] == [(1, 63), (1, 64), (2, 71)]
     # a group's own list keeps 4096-element tiles from 2048 tiles on, and halves below
     for n_tiles, tlen in ((2048, 4096), (2047, 2048), (1024, 2048), (1023, 1024)):
         t = lists_of([n_tiles * 4096], [])
