@@ -38,10 +38,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # scaled by what the same counters read for the library's plain copy probe.  Filled from the
 # summaries under profiles/; None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet50", "fused"): 920_968_000,      # profiles/k_fused_resnet50_n8_hbm_traffic.md
-    ("resnet50", "step"): 1_330_455_000,
-    ("vgg16", "fused"): 9_411_763_000,       # profiles/k_fused_vgg16_n16_hbm_traffic.md
-    ("vgg16", "step"): 11_627_806_000,
+    ("resnet50", "fused"): 920_979_000,      # profiles/k_fused_resnet50_n8_hbm_traffic.md
+    ("resnet50", "step"): 1_330_446_000,
+    ("vgg16", "fused"): 9_411_698_000,       # profiles/k_fused_vgg16_n16_hbm_traffic.md
+    ("vgg16", "step"): 11_627_816_000,
 }
 
 
