@@ -401,7 +401,9 @@ def main():
             extra["tiny_config_us_per_launch"] = {"median": round(float(np.median(lat)), 2),
                                                   "min": round(float(np.min(lat)), 2), "seeds": len(lat)}
             # the other gradient set the target names (VGG-16-shaped, N = 16), so that one default
-            # run carries both: fused pass and update, one set (9.4 GB per pass evicts itself)
+            # run carries both: fused pass and update, rules only, one set (9.4 GB per pass evicts
+            # itself).  Only this one: sets allocated after large blocks were freed measured 3 % slower
+            # than in a run of their own (AlexNet 340 against 333 us), so the others keep their own runs
             if args.workload == "resnet50" and torch.cuda.mem_get_info()[0] > 24e9:
                 extra["vgg16_n16"] = other_workload(mg, wl, torch, "vgg16", stream, dev)
         except Exception as e:
@@ -423,32 +425,39 @@ def main():
     print(json.dumps(result))
 
 
-def other_workload(mg, wl, torch, name, stream, dev, launches=20):
-    """Fused pass and update on another workload, rules only, timed with events on `stream`."""
+def other_workload(mg, wl, torch, name, stream, dev, launches=20, sets=1):
+    """Fused pass and update on another workload, rules only, timed with events on `stream`;
+    `sets` independently allocated gradient sets are rotated (one is enough when a pass moves
+    far more than the 256 MB Infinity Cache holds)."""
     w = wl.cnn_workload(name)
-    grads = wl.make_gradients(w, wl.BASE_SEED + 7000, dev)
-    out = [torch.empty_like(t) for t in grads[0]]
-    wt, vt = wl.make_weights(w, wl.BASE_SEED + 7, dev)
-    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
-    pl.bind(grads, out, wt, vt)
-    res = {"P": int(w.P), "n_workers": int(w.n_workers), "groups": pl.info()["n_groups"]}
-    for key, units, call in (("fused", w.n_workers + 1, lambda: pl.pack_reduce_unpack(stream=stream)),
-                             ("step", w.n_workers + 5, lambda: pl.step(0.1, 0.9, stream=stream))):
-        for _ in range(3):
-            call()
+    plans, keep = [], []
+    for s in range(sets):
+        grads = wl.make_gradients(w, wl.BASE_SEED + 7000 + s, dev)
+        out = [torch.empty_like(t) for t in grads[0]]
+        wt, vt = wl.make_weights(w, wl.BASE_SEED + 7 + s, dev)
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+        pl.bind(grads, out, wt, vt)
+        plans.append(pl)
+        keep.append((grads, out, wt, vt))
+    res = {"P": int(w.P), "n_workers": int(w.n_workers), "groups": plans[0].info()["n_groups"], "rotating_sets": sets}
+    for key, units, call in (("fused", w.n_workers + 1, lambda pl: pl.pack_reduce_unpack(stream=stream)),
+                             ("step", w.n_workers + 5, lambda pl: pl.step(0.1, 0.9, stream=stream))):
+        for i in range(2 * sets + 1):
+            call(plans[i % sets])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record(stream)
-        for _ in range(launches):
-            call()
+        for i in range(launches):
+            call(plans[i % sets])
         e1.record(stream)
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / launches
         gbps = 4 * units * w.P / (us * 1e-6) / 1e9
         res[key] = {"us_per_step": round(us, 2), "GBps_algorithmic": round(gbps, 1),
                     "frac_of_peak": round(gbps / 8000.0, 4)}
-    pl.destroy()
-    del grads, out, wt, vt
+    for pl in plans:
+        pl.destroy()
+    del keep
     torch.cuda.empty_cache()
     return res
 
