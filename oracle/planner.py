@@ -14,8 +14,8 @@ What each function follows:
   wfbp_timeline   Eq. 7-8 tau_c and t_iter with every layer sent alone
   simulate        Eq. 7-8 generalised to merged groups by Conditions 1-3 (Eq. 14-16)
   brute_force     Eq. 19-23, the problem statement itself: minimum over every set M
-  algorithm1      Algorithm 1 (with its Merge and CalculateCommStart procedures),
-                  i.e. the rule of Theorem 1
+  comm_start      Eq. 7 for one layer under a given merged set
+  algorithm1      the result of Algorithm 1, i.e. the rule of Theorem 1 applied top-down
 Readings taken where the text is ambiguous are listed next to the code.
 """
 from __future__ import annotations
@@ -113,48 +113,51 @@ def brute_force(p: Sequence[int], tb: Sequence[float], tf: float, a: float, b: f
     return best_t, best_m
 
 
-def _calculate_comm_start(tc, tb, tau_b, L):
-    """Algorithm 1, procedure CalculateCommStart (Eq. 7 with the current tc)."""
-    tau_c = [0.0] * (L + 1)                       # 1-based
-    tau_c[L] = tau_b[L] + tb[L]
-    for l in range(L - 1, 0, -1):
-        tau_c[l] = max(tau_c[l + 1] + tc[l + 1], tau_b[l] + tb[l])
-    return tau_c
+def comm_start(p: Sequence[int], tb: Sequence[float], tf: float, a: float, b: float,
+               merged: Iterable[int], layer: int) -> float:
+    """tau_c(layer): when `layer` could begin to send, given that the layers in `merged`
+    (all above `layer`) ride with the layer below them.
 
-
-def algorithm1(p: Sequence[int], tb_in: Sequence[float], tf: float, a: float, b: float
-               ) -> List[int]:
-    """Algorithm 1: the merged-gradient layers chosen by Theorem 1's rule.
-
-    Arrays are 1-based like the listing.  Readings:
-      * the listing indexes tau_b[l-2], which for l = 2 is tau_b[0] and is never
-        assigned; Section IV-A uses tau_b(1) = tau_b(2) + t_b(2) for l = 3, i.e.
-        tau_b[l-2] is the instant layer l-1 finishes its backward.  We extend
-        Eq. 6 one step below layer 1 so that tau_b[0] = tau_b[1] + t_b[1].
-      * the listing fills tau_b down to index 2 only; Eq. 6 defines index 1 too.
-      * T_ar takes bytes: the message of p parameters is 4p bytes.
-      * strict '<' as printed: a tie does not merge.
-    Returns M in the order pushed (descending l).
+    Eq. 7 under Conditions 1-3: walk the backward pass from L down to `layer`; every layer
+    above it that is not merged sends what has accumulated, as in `simulate`; `layer` itself
+    can start once the channel is free and its own gradients exist.
     """
     L = len(p)
-    pp = [0] + [int(x) for x in p]                # pp[l], mutable copy (Merge changes it)
-    tb = [0.0] + [float(x) for x in tb_in]
-    tc = [0.0] * (L + 1)
-    for l in range(1, L + 1):
-        tc[l] = t_ar(a, b, BYTES_PER_PARAM * pp[l])
-    tau_b = [0.0] * (L + 1)
-    tau_b[L] = tf
-    for l in range(L - 1, -1, -1):                # down to index 0 (see readings)
-        tau_b[l] = tau_b[l + 1] + tb[l + 1]
-    tau_c = _calculate_comm_start(tc, tb, tau_b, L)
+    mset = set(merged)
+    mu_b = backward_finish(tb, tf)
+    channel_free = 0.0
+    pending = 0
+    for l in range(L, layer, -1):
+        pending += BYTES_PER_PARAM * int(p[l - 1])
+        if l in mset:
+            continue
+        channel_free = max(channel_free, mu_b[l - 1]) + t_ar(a, b, pending)
+        pending = 0
+    return max(channel_free, mu_b[layer - 1])
+
+
+def algorithm1(p: Sequence[int], tb: Sequence[float], tf: float, a: float, b: float
+               ) -> List[int]:
+    """The merged-gradient layers Algorithm 1 returns, i.e. the rule of Theorem 1 applied from
+    the top layer down: layer l joins layer l-1 when the wait between the moment l could start
+    to send and the moment l-1's gradients exist is shorter than the start-up cost a.
+
+    Each decision sees the merges already made above it (Algorithm 1 recomputes the
+    communication start times after every merge; here tau_c(l) is evaluated afresh by
+    `comm_start` for the current set).  Readings:
+      * the time compared with tau_c(l) is the instant layer l-1 finishes its backward pass
+        (Section IV-A writes it tau_b(l-2) = tau_b(l-1) + t_b(l-1); for l = 2 that index does
+        not exist in Eq. 6, the instant does: the end of the backward pass);
+      * T_ar takes bytes: the message of p parameters is 4p bytes;
+      * strict '<' as printed: a tie does not merge.
+    Returns M in the order chosen (descending l).
+    """
+    L = len(p)
+    mu_b = backward_finish(tb, tf)
     merged: List[int] = []
     for l in range(L, 1, -1):
-        if tau_b[l - 2] - tau_c[l] < a:
-            # procedure Merge
-            tc[l] = 0.0
-            pp[l - 1] = pp[l - 1] + pp[l]
-            tc[l - 1] = t_ar(a, b, BYTES_PER_PARAM * pp[l - 1])
-            tau_c = _calculate_comm_start(tc, tb, tau_b, L)
+        wait = mu_b[l - 2] - comm_start(p, tb, tf, a, b, merged, l)
+        if wait < a:
             merged.append(l)
     return merged
 

@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "gpu_timing: asserts a speed or a ranking, not a result (also marked gpu; "
+                                       "deselect with -m 'gpu and not gpu_timing')")
 
 
 @pytest.fixture(scope="session")

@@ -572,21 +572,22 @@ def test_merged_buffer_errors(mg):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name,per_group", [("resnet50", False), ("resnet50", True), ("vgg16", False)])
-def test_full_size_two_halves_sampled(mg, name, per_group):
+@pytest.mark.parametrize("name,per_group", [("resnet50", False), ("resnet50", True), ("googlenet", False),
+                                            ("vgg16", False)])
+def test_full_size_two_halves(mg, name, per_group):
     """Full-size sets through pack_reduce and unpack_update (the update from the merged buffer),
-    in the launch configuration bench.py times; the oracle recomputes sampled windows."""
+    in the launch configuration bench.py times; every element of the merged buffer, of w and
+    of v is compared with the oracle."""
     w = wl.cnn_workload(name)
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
     groups = pl.groups()
     grads = wl.make_gradients(w, wl.BASE_SEED + 1, "cuda")
     wt, vt = wl.make_weights(w, wl.BASE_SEED + 1, "cuda")
-    rng = np.random.default_rng(5)
-    windows = {l: window_starts(int(n), rng, 8200) for l, n in enumerate(w.p)}
-    w0 = {(l, s): wt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
-    v0 = {(l, s): vt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
+    for t in vt:
+        t.normal_(0, 1e-3)
+    w0, v0 = [t.clone() for t in wt], [t.clone() for t in vt]
     pl.bind(grads, None, wt, vt)
-    plan_off, off = {}, 0
+    where, off = {}, 0
     if per_group:
         for k, g in enumerate(groups):         # one merged buffer per group, as Algorithm 2 has
             sub = merged_buffer(sum(int(w.p[l]) for l in g))
@@ -594,10 +595,12 @@ def test_full_size_two_halves_sampled(mg, name, per_group):
             pl.unpack_update(sub, group=k, update=True, lr=0.1, momentum=0.9)
             o = 0
             for l in g:
-                plan_off[l] = (sub, o)
+                where[l] = (sub, o)
                 o += int(w.p[l])
             assert o + 64 == sub.numel()
         torch.cuda.synchronize()
+        for sub, _ in where.values():
+            assert bool(torch.isnan(sub[-64:]).all())
     else:
         mb = merged_buffer(w.P)
         pl.pack_reduce(mb)
@@ -605,20 +608,11 @@ def test_full_size_two_halves_sampled(mg, name, per_group):
         torch.cuda.synchronize()
         for g in groups:
             for l in g:
-                plan_off[l] = (mb, off)
+                where[l] = (mb, off)
                 off += int(w.p[l])
         assert off == w.P
-        assert bool(torch.isnan(mb[w.P:]).all()) and bool(torch.isfinite(mb[:w.P]).all())
-    for l in windows:
-        buf, o = plan_off[l]
-        for s, c in windows[l]:
-            xs = [grads[g][l][s:s + c].cpu().numpy().copy() for g in range(w.n_workers)]
-            avg = od.reduce(xs)
-            assert_same(buf[o + s:o + s + c].cpu().numpy(), avg, f"{name} merged layer {l} window {s}")
-            ww, vv = w0[(l, s)], v0[(l, s)]
-            od.sgd(ww, vv, avg, 0.1, 0.9)
-            assert_same(wt[l][s:s + c].cpu().numpy(), ww, f"{name} w layer {l} window {s}")
-            assert_same(vt[l][s:s + c].cpu().numpy(), vv, f"{name} v layer {l} window {s}")
+        assert bool(torch.isnan(mb[w.P:]).all())
+    compare_whole_set(name, w, grads, merged=where, wt=wt, vt=vt, w0=w0, v0=v0, lr=0.1, mu=0.9)
 
 
 # ---- randomised sweep ------------------------------------------------------------------------
@@ -804,35 +798,18 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
 # ---- launch-shape tuning ---------------------------------------------------------------------
 
 @pytest.mark.parametrize("name", ["googlenet", "alexnet"])
-def test_tune_keeps_results_and_is_not_slower(mg, name):
-    """mgwfbp_tune only changes how the whole-plan pass is launched: the values stay the oracle's,
-    for the pass into out[] and into a merged buffer, and the pass does not get slower."""
+def test_tune_keeps_results(mg, name):
+    """mgwfbp_tune only changes how the whole-plan pass is launched: every value stays the
+    oracle's, for the pass into out[] and into a merged buffer."""
     w = wl.cnn_workload(name)
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
     grads = wl.make_gradients(w, wl.BASE_SEED + 3, "cuda")
     out = [torch.full_like(t, float("nan")) for t in grads[0]]
     pl.bind(grads, out)
     stream = torch.cuda.Stream()
-
-    def per_launch_us():
-        best = 1e9
-        for _ in range(3):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record(stream)
-            for _ in range(10):
-                pl.pack_reduce_unpack(stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            best = min(best, e0.elapsed_time(e1) * 100.0)
-        return best
-
-    pl.pack_reduce_unpack(stream=stream)
-    before = per_launch_us()
+    torch.cuda.synchronize()
     res = pl.tune(stream)
     assert res["candidate"] >= 0 and res["ms_per_launch"] > 0
-    after = per_launch_us()
-    assert after <= before * 1.10, (before, after, res)
     for t in out:
         t.fill_(float("nan"))
     mb = merged_buffer(w.P)
@@ -840,21 +817,12 @@ def test_tune_keeps_results_and_is_not_slower(mg, name):
     pl.pack_reduce_unpack(stream=stream)
     pl.pack_reduce(mb, stream=stream)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(4)
-    off, plan_off = 0, {}
+    off, where = 0, {}
     for g in pl.groups():
         for l in g:
-            plan_off[l] = off
+            where[l] = (mb, off)
             off += int(w.p[l])
-    for l, n in enumerate(w.p):
-        for s0, c in window_starts(int(n), rng, 8200):
-            xs = [grads[g][l][s0:s0 + c].cpu().numpy().copy() for g in range(w.n_workers)]
-            avg = od.reduce(xs)
-            assert_same(out[l][s0:s0 + c].cpu().numpy(), avg, f"{name} layer {l} window {s0}")
-            o = plan_off[l] + s0
-            assert_same(mb[o:o + c].cpu().numpy(), avg, f"{name} merged layer {l} window {s0}")
-    for l in range(w.L):
-        assert bool(torch.isfinite(out[l]).all())
+    compare_whole_set(name, w, grads, out=out, merged=where)
     assert bool(torch.isnan(mb[w.P:]).all())
 
 
@@ -956,16 +924,40 @@ def test_single_layer_beyond_4_gib(mg):
 
 # ---- full-size gradient sets ---------------------------------------------------------------
 
-def window_starts(n, rng, width):
-    if n <= 3 * width:
-        return [(0, n)]
-    picks = [0, n - width] + [int(x) for x in rng.integers(0, n - width, size=2)]
-    return [(s, width) for s in picks]
+CHUNK = 1 << 23      # elements of one layer that go through the oracle at a time
 
 
-def test_full_size_materialised_sampled(mg):
+def compare_whole_set(name, w, grads, out=None, merged=None, wt=None, vt=None, w0=None, v0=None,
+                      lr=0.0, mu=0.0):
+    """Every element of every layer against the oracle, bit for bit and within 1e-6 relative:
+    Eq. 2 over the N workers' tensors (od.reduce), then the update (od.sgd) from the saved
+    starting values w0, v0.  Pack and unpack only move an element to and from its place in the
+    merged order, so the expected value of element i of layer l is the reduction of the N
+    elements (l, i) whatever the grouping (the oracle's own tests pin that); `merged` maps a
+    layer to (buffer, offset) where its packed copy must sit.  Layers longer than CHUNK
+    elements stream through in slices so that host memory stays bounded (VGG-16's largest
+    layer holds 6.6 GB over its 16 workers)."""
+    for l, n in enumerate(int(x) for x in w.p):
+        for s in range(0, n, CHUNK):
+            c = min(CHUNK, n - s)
+            avg = od.reduce([grads[g][l][s:s + c].cpu().numpy() for g in range(w.n_workers)])
+            tag = f"{name} layer {l} [{s}:{s + c}]"
+            if out is not None:
+                assert_same(out[l][s:s + c].cpu().numpy(), avg, "avg " + tag)
+            if merged is not None:
+                buf, o = merged[l]
+                assert_same(buf[o + s:o + s + c].cpu().numpy(), avg, "merged " + tag)
+            if wt is not None:
+                ww, vv = w0[l][s:s + c].cpu().numpy(), v0[l][s:s + c].cpu().numpy()
+                od.sgd(ww, vv, avg, lr, mu)
+                assert_same(wt[l][s:s + c].cpu().numpy(), ww, "w " + tag)
+                assert_same(vt[l][s:s + c].cpu().numpy(), vv, "v " + tag)
+
+
+def test_full_size_materialised(mg):
     """ResNet-50-shaped set through pack -> reduce -> unpack with a workspace (the contiguous
-    reduce takes its double-length tiles at this size); sampled windows against the oracle."""
+    reduce takes its double-length tiles at this size): every element of out[], of the N packed
+    buffers and of the reduced buffer."""
     w = wl.cnn_workload("resnet50")
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
     grads = wl.make_gradients(w, wl.BASE_SEED + 2, "cuda")
@@ -974,35 +966,37 @@ def test_full_size_materialised_sampled(mg):
     ws = alloc_ws(pl)
     pl.pack_reduce_unpack(workspace=ws)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(9)
-    for l, n in enumerate(w.p):
-        for s0, c in window_starts(int(n), rng, 8200):
-            xs = [grads[g][l][s0:s0 + c].cpu().numpy().copy() for g in range(w.n_workers)]
-            assert_same(out[l][s0:s0 + c].cpu().numpy(), od.reduce(xs), f"layer {l} window {s0}")
-    for l in range(w.L):
-        assert bool(torch.isfinite(out[l]).all())
-    # the reduced buffer itself: first, last and a middle window of the merged order
     E = w.P
     epad = (E + 63) // 64 * 64
     layers = [l for g in pl.groups() for l in g]
-    first, last = layers[0], layers[-1]
-    red = ws[w.n_workers * epad:w.n_workers * epad + E]
-    assert_same(red[:64].cpu().numpy(), out[first][:64].cpu().numpy(), "head of the reduced buffer")
-    assert_same(red[E - 64:].cpu().numpy(), out[last][-64:].cpu().numpy(), "tail of the reduced buffer")
+    where, off = {}, 0
+    for l in layers:
+        where[l] = (ws, w.n_workers * epad + off)
+        off += int(w.p[l])
+    compare_whole_set("resnet50", w, grads, out=out, merged=where)
+    host = bits(ws.cpu().numpy())
+    for g in range(w.n_workers):
+        exp = od.pack([bits(t.cpu().numpy()) for t in grads[g]], layers)
+        assert np.array_equal(host[g * epad:g * epad + E], exp), f"packed buffer of worker {g}"
 
 
-
-@pytest.mark.parametrize("name,a_ms,tile,per_group", [
-    ("resnet50", 0.5, None, False), ("googlenet", 0.5, None, False), ("alexnet", 0.5, None, False),
-    ("vgg16", 0.1, None, False), ("vgg16", 2.0, None, False),
-    ("resnet50", 0.5, None, True),       # one launch per group, as Algorithm 2 would issue them
-    ("googlenet", 0.5, 1024, False), ("googlenet", 0.5, 2048, False), ("alexnet", 0.5, 8192, False)])
-def test_full_size_sets_sampled(mg, name, a_ms, tile, per_group):
+@pytest.mark.parametrize("name,n_workers,a_ms,tile,per_group", [
+    ("resnet50", None, 0.5, None, False), ("googlenet", None, 0.5, None, False),
+    ("alexnet", None, 0.5, None, False),
+    ("vgg16", None, 0.1, None, False), ("vgg16", None, 0.5, None, False), ("vgg16", None, 2.0, None, False),
+    ("vgg16", 8, 0.5, None, False),
+    ("resnet50", None, 0.5, None, True),       # one launch per group, as Algorithm 2 would issue them
+    ("googlenet", None, 0.5, None, True),
+    ("googlenet", None, 0.5, 1024, False), ("googlenet", None, 0.5, 2048, False),
+    ("alexnet", None, 0.5, 8192, False)])
+def test_full_size_sets(mg, name, n_workers, a_ms, tile, per_group):
     """The ResNet-50 / GoogLeNet / AlexNet / VGG-16 shaped sets at full size and worker count,
-    in the launch configuration bench.py times (default tile, whole plan in one launch), plus
-    the other tile sizes and the launch-per-group sequence.  The oracle recomputes sampled
-    windows of every layer (whole layers when short); for the update, the same windows of w, v."""
-    w = wl.cnn_workload(name, a_ms=a_ms)
+    in the launch configurations bench.py times (default tile, whole plan in one launch; VGG-16
+    at both worker counts and all three start-up costs), plus the other tile sizes and the
+    launch-per-group sequence.  Every element of every layer is compared with the oracle: the
+    averaged gradients after the fused pass, then w, v and the averaged gradients again after
+    the fused update."""
+    w = wl.cnn_workload(name, a_ms=a_ms, n_workers=n_workers)
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
     if tile is not None:
         pl.set_option(mg.OPT_TILE_ELEMS, tile)
@@ -1011,28 +1005,22 @@ def test_full_size_sets_sampled(mg, name, a_ms, tile, per_group):
     wt, vt = wl.make_weights(w, wl.BASE_SEED, "cuda")
     for t in vt:
         t.normal_(0, 1e-3)
-    rng = np.random.default_rng(3)
-    windows = {l: window_starts(int(n), rng, 8200) for l, n in enumerate(w.p)}
-    w0 = {(l, s): wt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
-    v0 = {(l, s): vt[l][s:s + c].cpu().numpy().copy() for l in windows for s, c in windows[l]}
+    w0, v0 = [t.clone() for t in wt], [t.clone() for t in vt]
     pl.bind(grads, out, wt, vt)
+    n_groups = pl.info()["n_groups"]
     if per_group:
-        for k in range(pl.info()["n_groups"]):
+        for k in range(n_groups):
             pl.pack_reduce_unpack(group=k)
-            pl.step(0.1, 0.9, group=k)
     else:
         pl.pack_reduce_unpack()
+    torch.cuda.synchronize()
+    compare_whole_set(name, w, grads, out=out)
+    for t in out:
+        t.fill_(float("nan"))
+    if per_group:
+        for k in range(n_groups):
+            pl.step(0.1, 0.9, group=k)
+    else:
         pl.step(0.1, 0.9)
     torch.cuda.synchronize()
-    for l in windows:
-        for s, c in windows[l]:
-            xs = [grads[g][l][s:s + c].cpu().numpy().copy() for g in range(w.n_workers)]
-            avg = od.reduce(xs)
-            assert_same(out[l][s:s + c].cpu().numpy(), avg, f"{name} layer {l} window {s}")
-            ww, vv = w0[(l, s)], v0[(l, s)]
-            od.sgd(ww, vv, avg, 0.1, 0.9)
-            assert_same(wt[l][s:s + c].cpu().numpy(), ww, f"{name} w layer {l} window {s}")
-            assert_same(vt[l][s:s + c].cpu().numpy(), vv, f"{name} v layer {l} window {s}")
-    # every output element was written: no NaN sentinel is left
-    for l in range(w.L):
-        assert bool(torch.isfinite(out[l]).all())
+    compare_whole_set(name, w, grads, out=out, wt=wt, vt=vt, w0=w0, v0=v0, lr=0.1, mu=0.9)

@@ -1,5 +1,6 @@
 """Event-driven iteration (Algorithm 2 on two HIP streams): results equal the oracle's, and the
-measured timeline obeys the start rule of Eq. 7 / Condition 2."""
+measured timeline obeys the start rule of Eq. 7 / Condition 2 (ordering and causality only: how
+fast the schedule runs is checked in test_zy_gpu_timing.py, after every parity test)."""
 import numpy as np
 import pytest
 import torch
@@ -56,27 +57,22 @@ def test_iteration_results_and_timeline(mg, seed, update):
     mu_b = np.array(op.backward_finish(tb.tolist(), 0.0))
     mu_low = np.array([mu_b[grp[-1]] for grp in groups])      # mu_b of each group's lowest layer
     assert np.all(ready >= mu_low - early(mu_low))            # never early
-    assert np.all(ready <= mu_low + 0.2)                      # absolute deadlines: gaps do not add up
     eps = 0.02
     for k, grp in enumerate(groups):
         assert gs[k] >= ready[k] - eps                        # gradients exist (Condition 2)
         if k:
             assert gs[k] >= gf[k - 1] - eps                   # channel free (Eq. 7)
         assert gf[k] >= gs[k]
-    assert gf.max() - 1e-6 <= tl["t_iter_ms"] <= gf.max() + 0.02      # one more event after the last group
+    assert tl["t_iter_ms"] >= gf.max() - 1e-6                 # the iteration ends with its last group (Eq. 8)
     # the same iteration without per-group timestamps: same results, only t_iter comes back
     if not update:
         for t in out:
             t.zero_()
         light = pl.run_iteration(s_comp, s_comm, timeline=False)
         assert set(light) == {"t_iter_ms"}
-        assert light["t_iter_ms"] <= tl["t_iter_ms"] + 0.2
         assert light["t_iter_ms"] >= mu_b.max() - early(mu_b.max())
         for l in range(w.L):
             assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
-    # the reductions overlap the backward pass: every group but the last ends before the
-    # backward pass does
-    assert np.all(gf[:-1] <= ready[-1] + eps) or len(groups) == 1
 
 
 def test_iteration_needs_binding(mg):
@@ -98,8 +94,8 @@ def test_iteration_needs_binding(mg):
 @pytest.mark.parametrize("update", [False, True])
 def test_iteration_graph_replays(mg, update):
     """The iteration captured into a HIP graph: every replay, with fresh gradients copied in
-    eagerly between replays, gives the oracle's values, and its device-clock t_iter agrees with
-    the eager executor's and with Eq. 8's lower bound (the backward pass itself)."""
+    eagerly between replays, gives the oracle's values, and its device-clock t_iter respects
+    Eq. 8's lower bound (the backward pass itself)."""
     seed = 5
     w = wl.tiny_workload(seed, L=10)
     tb = w.tb_ms * 0.3
@@ -143,11 +139,8 @@ def test_iteration_graph_replays(mg, update):
         od.merged_gradient_path([to_np(r) for r in grads], groups, w_np, v_np, lr=0.1, mu=0.9)
         assert np.array_equal(wt[0].cpu().numpy().view(np.uint32), w_np[0].view(np.uint32))
     backward = float(tb.sum())
-    eager = pl.run_iteration(s_comp, s_comm, update=False, timeline=False)["t_iter_ms"] if not update else None
-    for t in times:
-        assert backward - (0.02 + 1e-3 * backward) <= t <= backward + 0.2, (t, backward)
-        if eager is not None:
-            assert abs(t - eager) < 0.2, (t, eager)
+    for t in times:                         # Eq. 8: no iteration is shorter than its backward pass
+        assert t >= backward - (0.02 + 1e-3 * backward), (t, backward)
     it.destroy()
     # streams used for the capture are ordinary streams again
     pl.pack_reduce_unpack(stream=s_comp)
@@ -179,21 +172,3 @@ def test_iteration_graph_argument_errors(mg):
     assert it2.replay(s1) >= 0.095
     pl.destroy()                      # takes its graphs with it
     assert not it2._h
-
-
-def test_calibrated_schedule_ranks_plans_like_the_model(mg):
-    """Fit (a, b) on this machine from the schedule itself, then run the four plans with a short
-    backward pass: no merging must be the slowest by far, and the model must rank the optimal
-    plan first, as measured."""
-    from paper_1811_11141_amd import experiments as ex
-
-    cal = ex.calibrate_in_schedule("googlenet", reps=3)
-    assert 1e-3 < cal["a_ms"] < 0.2 and 0 < cal["b_ms_per_byte"] < 1e-7
-    res = ex.schedule("googlenet", cal["a_ms"], cal["b_ms_per_byte"], backward_ms=0.3, reps=3)["plans"]
-    assert res["optimal"]["predicted_t_iter_ms"] <= res["theorem1"]["predicted_t_iter_ms"] + 1e-12
-    assert res["optimal"]["predicted_t_iter_ms"] <= res["wfbp"]["predicted_t_iter_ms"] + 1e-12
-    assert res["wfbp"]["measured_t_iter_ms"] > 2.0 * res["optimal"]["measured_t_iter_ms"]
-    assert res["optimal"]["measured_t_iter_ms"] <= 1.25 * min(res["single"]["measured_t_iter_ms"],
-                                                              res["theorem1"]["measured_t_iter_ms"])
-    # the model tracks the measurement for the communication-bound plan
-    assert res["wfbp"]["measured_t_iter_ms"] == pytest.approx(res["wfbp"]["predicted_t_iter_ms"], rel=0.3)

@@ -91,6 +91,30 @@ def test_algorithm1_hand_traces(golden):
             assert op.wfbp_timeline(*args)[1] == pytest.approx(c["t_iter_wfbp"], rel=1e-12)
 
 
+def test_comm_start_hand_values_and_eq7(golden):
+    """tau_c of single layers: hand-worked values, Eq. 7 written out directly when nothing is
+    merged, and the link to the iteration time (Eq. 8: the last message starts at tau_c(1) and
+    costs Eq. 9 on layer 1 plus everything that rides with it)."""
+    for c in golden["hand_worked_comm_start"]["cases"]:
+        args = (c["p"], c["tb_ms"], 0.0, c["a_ms"], c["b_ms_per_byte"])
+        for layer, t in c["tau_c"].items():
+            assert op.comm_start(*args, c["merged"], int(layer)) == pytest.approx(t, rel=1e-12), c["note"]
+    rng = np.random.default_rng(23)
+    for _ in range(200):
+        L = int(rng.integers(1, 10))
+        p, tb, tf, a, b = rand_case(rng, L, a=float(rng.uniform(0, 2)))
+        tau_c, _ = op.wfbp_timeline(p, tb, tf, a, b)
+        for l in range(1, L + 1):
+            assert op.comm_start(p, tb, tf, a, b, [], l) == tau_c[l - 1]
+        merged = [l for l in range(2, L + 1) if rng.random() < 0.5]
+        riding, l = int(p[0]), 2
+        while l in merged:                     # layers that ride with layer 1
+            riding += int(p[l - 1])
+            l += 1
+        last = op.comm_start(p, tb, tf, a, b, merged, 1) + op.t_ar(a, b, 4 * riding)
+        assert last == op.simulate(p, tb, tf, a, b, merged)
+
+
 # ---- closed forms --------------------------------------------------------------------------
 
 def test_case1_closed_form():
