@@ -22,8 +22,9 @@
  *                    momentum buffer: v = mu*v + g ; w = w - eta*v.  With mu = 0
  *                    it is exactly the paper's update.
  *
- * `threads` > 1 splits the element loop statically over that many OpenMP
- * threads; each element is still computed by the same sequence of operations.
+ * `threads` > 1 splits the element loop of the current layer (pack, unpack) or of
+ * the whole buffer (reduce, update) statically over that many OpenMP threads;
+ * each element is still produced by the same sequence of operations.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -37,13 +38,16 @@
  * grads[l] points at layer l; p[l] is its element count. */
 void oracle_pack(const uint32_t *const *grads, const uint64_t *p,
                  const int32_t *group_layers, int32_t n_group_layers,
-                 uint32_t *merged)
+                 uint32_t *merged, int32_t threads)
 {
     uint64_t off = 0;
+    (void)threads;
     for (int32_t k = 0; k < n_group_layers; ++k) {
         int32_t l = group_layers[k];
-        for (uint64_t i = 0; i < p[l]; ++i)
-            merged[off + i] = grads[l][i];
+        int64_t n = (int64_t)p[l];
+#pragma omp parallel for schedule(static) num_threads(threads) if (threads > 1 && n > 32768)
+        for (int64_t i = 0; i < n; ++i)
+            merged[off + (uint64_t)i] = grads[l][i];
         off += p[l];
     }
 }
@@ -67,13 +71,16 @@ void oracle_reduce(const float *const *x, int32_t n_workers, uint64_t n_elems,
 /* Scatter one merged buffer back to the group's per-layer tensors, bit for bit. */
 void oracle_unpack(const uint32_t *merged, const uint64_t *p,
                    const int32_t *group_layers, int32_t n_group_layers,
-                   uint32_t *const *out)
+                   uint32_t *const *out, int32_t threads)
 {
     uint64_t off = 0;
+    (void)threads;
     for (int32_t k = 0; k < n_group_layers; ++k) {
         int32_t l = group_layers[k];
-        for (uint64_t i = 0; i < p[l]; ++i)
-            out[l][i] = merged[off + i];
+        int64_t n = (int64_t)p[l];
+#pragma omp parallel for schedule(static) num_threads(threads) if (threads > 1 && n > 32768)
+        for (int64_t i = 0; i < n; ++i)
+            out[l][i] = merged[off + (uint64_t)i];
         off += p[l];
     }
 }

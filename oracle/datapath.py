@@ -23,13 +23,13 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build_oracle(force=False))
         _lib.oracle_pack.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_uint64),
-                                     C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
+                                     C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_int32]
         _lib.oracle_pack.restype = None
         _lib.oracle_reduce.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_uint64,
                                        C.c_void_p, C.c_int32]
         _lib.oracle_reduce.restype = None
         _lib.oracle_unpack.argtypes = [C.c_void_p, C.POINTER(C.c_uint64),
-                                       C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p)]
+                                       C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p), C.c_int32]
         _lib.oracle_unpack.restype = None
         _lib.oracle_sgd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                                     C.c_float, C.c_float, C.c_int32]
@@ -50,7 +50,7 @@ def _check(a: np.ndarray, dtypes) -> None:
     assert a.dtype in dtypes and a.flags["C_CONTIGUOUS"], (a.dtype, a.flags)
 
 
-def pack(layers: Sequence[np.ndarray], group_layers: Sequence[int]) -> np.ndarray:
+def pack(layers: Sequence[np.ndarray], group_layers: Sequence[int], threads: int = 1) -> np.ndarray:
     """Layer buffer of one worker for one group; layers[l] is 0-based layer l (4-byte items)."""
     for a in layers:
         _check(a, (np.float32, np.uint32))
@@ -59,7 +59,7 @@ def pack(layers: Sequence[np.ndarray], group_layers: Sequence[int]) -> np.ndarra
     total = int(sum(int(p[l]) for l in gl))
     merged = np.empty(total, dtype=layers[0].dtype)
     lib().oracle_pack(_ptrs(layers), p.ctypes.data_as(C.POINTER(C.c_uint64)),
-                      gl.ctypes.data_as(C.POINTER(C.c_int32)), len(gl), merged.ctypes.data)
+                      gl.ctypes.data_as(C.POINTER(C.c_int32)), len(gl), merged.ctypes.data, threads)
     return merged
 
 
@@ -73,7 +73,8 @@ def reduce(buffers: Sequence[np.ndarray], threads: int = 1) -> np.ndarray:
     return out
 
 
-def unpack(merged: np.ndarray, out_layers: Sequence[np.ndarray], group_layers: Sequence[int]) -> None:
+def unpack(merged: np.ndarray, out_layers: Sequence[np.ndarray], group_layers: Sequence[int],
+           threads: int = 1) -> None:
     """Scatter `merged` into out_layers[l] for l in the group (in place)."""
     _check(merged, (np.float32, np.uint32))
     for a in out_layers:
@@ -82,7 +83,7 @@ def unpack(merged: np.ndarray, out_layers: Sequence[np.ndarray], group_layers: S
     gl = np.asarray(group_layers, dtype=np.int32)
     assert merged.size == sum(int(p[l]) for l in gl)
     lib().oracle_unpack(merged.ctypes.data, p.ctypes.data_as(C.POINTER(C.c_uint64)),
-                        gl.ctypes.data_as(C.POINTER(C.c_int32)), len(gl), _ptrs(out_layers))
+                        gl.ctypes.data_as(C.POINTER(C.c_int32)), len(gl), _ptrs(out_layers), threads)
 
 
 def sgd(w: np.ndarray, v: np.ndarray, g: np.ndarray, lr: float, mu: float, threads: int = 1) -> None:
@@ -104,9 +105,9 @@ def merged_gradient_path(grads: Sequence[Sequence[np.ndarray]], groups: Sequence
     L = len(grads[0])
     avg = [np.empty_like(grads[0][l]) for l in range(L)]
     for grp in groups:
-        buffers = [pack(grads[g], grp) for g in range(len(grads))]
+        buffers = [pack(grads[g], grp, threads) for g in range(len(grads))]
         reduced = reduce(buffers, threads)
-        unpack(reduced, avg, grp)
+        unpack(reduced, avg, grp, threads)
         if w is not None:
             for l in grp:
                 sgd(w[l], v[l], avg[l], lr, mu, threads)

@@ -103,10 +103,35 @@ def test_reduce_scale_is_multiplication_by_fp32_reciprocal():
     assert not np.array_equal(got, x / np.float32(3.0))
 
 
-def test_reduce_threads_do_not_change_bits():
+def test_threads_do_not_change_bits():
+    """Splitting the element loops over threads changes nothing: reduce, update, pack, unpack
+    and the whole path give the single-thread bits (layers on both sides of the size from
+    which pack and unpack split their copy loop)."""
     rng = np.random.default_rng(4)
     xs = [(rng.standard_normal(100003) * 1e-3).astype(np.float32) for _ in range(8)]
     assert np.array_equal(od.reduce(xs, 1), od.reduce(xs, 4))
+    sizes = [70001, 5, 32768, 32769, 1000, 200003]
+    layers = [rng.integers(0, 2 ** 32, size=n, dtype=np.uint64).astype(np.uint32) for n in sizes]
+    order = [5, 4, 3, 1, 0]
+    one, four = od.pack(layers, order, 1), od.pack(layers, order, 4)
+    assert np.array_equal(one, four) and np.array_equal(one, np.concatenate([layers[l] for l in order]))
+    outs = [[np.zeros(n, dtype=np.uint32) for n in sizes] for _ in range(2)]
+    od.unpack(one, outs[0], order, 1)
+    od.unpack(one, outs[1], order, 4)
+    for l in range(len(sizes)):
+        assert np.array_equal(outs[0][l], outs[1][l])
+        assert np.array_equal(outs[0][l], layers[l] if l in order else np.zeros(sizes[l], dtype=np.uint32))
+    grads = [[(rng.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(3)]
+    groups = [[5, 4], [3, 2, 1], [0]]
+    res = []
+    for threads in (1, 4):
+        w = [np.full(n, 0.5, dtype=np.float32) for n in sizes]
+        v = [np.full(n, 0.25, dtype=np.float32) for n in sizes]
+        avg = od.merged_gradient_path(grads, groups, w, v, lr=0.1, mu=0.9, threads=threads)
+        res.append((avg, w, v))
+    for a, b in zip(res[0], res[1]):
+        for x, y in zip(a, b):
+            assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
 
 
 def test_reduce_keeps_denormals():
