@@ -104,7 +104,6 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_
         sc.elems = pl->total_elems;
         sc.base_off = 0;
         sc.tile_elems = pl->opt.tile_elems;
-        sc.needs_lds = pl->all_needs_lds;
         const bool use_long = pl->tuned.valid ? pl->tuned.use_long : pl->long_by_default;
         if (long_ok && pl->long_tile_count && use_long) {
             sc.tile_begin = pl->long_tile_begin;
@@ -122,7 +121,6 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_
         sc.elems = g.elems;
         sc.base_off = g.plan_off;
         sc.tile_elems = g.tile_elems;
-        sc.needs_lds = g.needs_lds;
     }
     return MGWFBP_OK;
 }
@@ -486,7 +484,7 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
         if (pl->bound) return fail(MGWFBP_ESTATE, "options must be set before mgwfbp_bind");
         switch (key) {
         case MGWFBP_OPT_TILE_ELEMS:
-            // upper bound: a tile is staged whole in LDS by the pack / unpack kernels (32 KiB)
+            // upper bound: the longest tile the fused reduce pass has a fast path for
             if (value < 1024 || value > 8192 || (value % 1024) != 0)
                 return fail(MGWFBP_EINVAL, "tile_elems must be a multiple of 1024 in [1024, 8192]");
             pl->opt.tile_elems = static_cast<uint32_t>(value);

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <utility>
 
 #include "../../include/mgwfbp.h"
@@ -516,58 +517,6 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
 // Workspace: N packed replica buffers of `epad` floats each, then the reduced buffer.
 // `base_off` is the plan offset of the scope's first element (0 for the whole plan).
 
-template <bool NT, int U, int D>
-__global__ void __launch_bounds__(kBlock)
-k_pack(DeviceTables dt, uint32_t tile_begin, int nw, float *ws, uint64_t epad, uint64_t base_off,
-       int pace)
-{
-    extern __shared__ float lds[];
-    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
-    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
-    const uint32_t g = blockIdx.y;
-    float *merged = ws + static_cast<uint64_t>(g) * epad;
-
-    if (tl.nseg == 1) {
-        const SegDev sg = load_seg(dt.segs + tl.seg);
-        const float *src = table_load(dt.src + static_cast<size_t>(tl.seg) * nw + g) + tl.start;
-        const uint64_t moff = sg.plan_off - base_off + tl.start;
-        float *dst = merged + moff;
-        const uint32_t n = tl.n;
-        if constexpr (U > 0) {
-            if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3) && n == U * kBlock * 4) {
-                fast_tile<1, U, false, D, false>([src](int) { return src; }, dst, nullptr, nullptr,
-                                                 1.0f, 0.0f, 0.0f, pace);
-                return;
-            }
-        }
-        if (threadIdx.x < tl.pad) st<NT>(dst + n + threadIdx.x, 0.0f);  // padding after the layer
-        if ((sg.flags & SEG_SRC_ALIGNED) && !(moff & 3)) {
-            const uint32_t n4 = n >> 2;
-            const v4f *s4 = reinterpret_cast<const v4f *>(src);
-            v4f *d4 = reinterpret_cast<v4f *>(dst);
-            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) st<NT>(d4 + i, ld<NT>(s4 + i));
-            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) st<NT>(dst + i, ld<NT>(src + i));
-        } else {
-            // the two sides disagree on 16-byte alignment: realign through LDS so that both
-            // the loads and the stores are 128 bits wide
-            global_to_lds<NT>(src, lds, n);
-            __syncthreads();
-            lds_to_global<NT>(lds, dst, n);
-        }
-    } else {
-        // many short layers: gather them into LDS, then one coalesced write of the run
-        stage_gather_offsets(dt, tl, s_rel, s_len);
-        for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
-            const uint32_t s = find_segment(s_rel, tl.nseg, k);
-            const uint32_t i = k - s_rel[s];
-            const float *src = dt.src[static_cast<size_t>(tl.seg + s) * nw + g];
-            lds[k] = i < s_len[s] ? ld<NT>(src + i) : 0.0f;  // zero in the padding between layers
-        }
-        __syncthreads();
-        lds_to_global<NT>(lds, merged + (tl.start - base_off), tl.n);
-    }
-}
-
 template <int NW, bool NT, int U, int D>
 __global__ void __launch_bounds__(kBlock)
 k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float inv_n, int pace)
@@ -603,15 +552,148 @@ k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float 
     }
 }
 
-template <bool STEP, bool NT, int U, int D>
-__global__ void __launch_bounds__(kBlock)
-k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t base_off, float lr,
-         float mu, int pace)
-{
-    extern __shared__ float lds[];
-    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
-    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
+// ------------------------------------------------------------------------------------------
+// Copy-like steps in small pieces
+// ------------------------------------------------------------------------------------------
+// Streams that are half writes want the opposite of the N-way reduction.  Measured on MI355X
+// with plain copy kernels over 512 MiB buffers: one 16-byte access per lane and workgroup
+// (2 KiB per workgroup, 262 144 workgroups) copies at 84 % of the HBM peak, two per lane at
+// 80 %, four or eight at 74 % -- the vendor's own device-to-device copy reaches 66 %.  Short
+// workgroups keep everything the chip has in flight inside a window of a few MiB that sweeps
+// through the buffers in address order; long ones spread it over tens of MiB.
+//
+// So pack and unpack do not run one workgroup per tile: a tile of the plan's list is cut into
+// pieces of SV * kBlock float4 (512 elements for SV = 1), one workgroup each, `subs` pieces per
+// tile, consecutive workgroups taking consecutive pieces.  A piece that lies beyond the end of
+// a ragged tile exits at once.  Pieces of a tile whose two sides disagree on 16-byte alignment
+// are realigned through a piece-sized LDS buffer; a gather tile (many tiny layers) is handled
+// whole by its first piece with 32-bit accesses.
+//
+// Where a piece starts matters on the side that is written: a wave's 1 KiB store that begins
+// 16 or 32 bytes past a 64-byte boundary leaves a partly written 64-byte sector at both ends,
+// and the same copy kernel drops from 84 % to 76 % of peak (a pure fill from 75 % to 52 %);
+// misaligned reads cost 3 points.  The merged offset of a layer is whatever the layers before
+// it add up to, so the pieces of a tile are laid out from the first 128-byte boundary of the
+// written side: the tile's first `head` elements (under 32) ride with piece 0, and piece k
+// covers [head + k * kElems, head + (k + 1) * kElems).
+template <int SV>
+struct Piece {
+    static constexpr uint32_t kElems = SV * kBlock * 4;
+};
 
+// x / d for a workgroup-uniform x with the host's m = floor(2^32 / d) (2^32 - 1 for d = 1):
+// the estimate mulhi(x, m) is the quotient or one less, so one correction makes it exact for
+// every 32-bit x.  Multiply-high, multiply, compare: all on the scalar unit (a plain `/` goes
+// through the vector unit's reciprocal and back).
+struct Divisor {
+    uint32_t d, m;
+};
+__device__ __forceinline__ uint32_t div_uniform(uint32_t x, Divisor dv)
+{
+    uint32_t q = __umulhi(x, dv.m);
+    if (x - q * dv.d >= dv.d) ++q;
+    return q;
+}
+
+// Elements from the start of a tile to the first 128-byte boundary of `written` (a 16-byte
+// aligned address): 0, 4, .. 28.
+__device__ __forceinline__ uint32_t head_elems(const float *written)
+{
+    return (32u - (static_cast<uint32_t>(reinterpret_cast<uintptr_t>(written) >> 2) & 31u)) & 31u;
+}
+
+// Range [lo, hi) of piece `sub` in a tile of n elements whose pieces start `head` elements in.
+template <int SV>
+__device__ __forceinline__ bool piece_range(uint32_t sub, uint32_t head, uint32_t n, uint32_t &lo, uint32_t &hi)
+{
+    const uint32_t base = head + sub * Piece<SV>::kElems;
+    lo = sub == 0 ? 0 : base;
+    hi = base + Piece<SV>::kElems < n ? base + Piece<SV>::kElems : n;
+    return lo < n;
+}
+
+// Copy elements [lo, hi) of a tile whose two sides are 16-byte aligned at element 0 (lo, head
+// multiples of four).  Every lane moves up to SV float4 of the piece proper, loads first; the
+// first lanes of piece 0 also move the head, the last piece the 1-3 trailing elements.
+template <bool NT, int SV>
+__device__ __forceinline__ void copy_piece_aligned(const float *src, float *dst, uint32_t lo, uint32_t hi,
+                                                   uint32_t head)
+{
+    const uint32_t body = lo == 0 ? head : lo;  // where the 128-byte aligned part of the piece starts
+    const uint32_t i0 = (body >> 2) + threadIdx.x, n4 = hi >> 2;
+    v4f x[SV], h;
+    const bool has_head = lo == 0 && threadIdx.x < (head >> 2) && threadIdx.x < n4;
+    if (has_head) h = ld<NT>(reinterpret_cast<const v4f *>(src) + threadIdx.x);
+#pragma unroll
+    for (int k = 0; k < SV; ++k)
+        if (i0 + k * kBlock < n4) x[k] = ld<NT>(reinterpret_cast<const v4f *>(src) + i0 + k * kBlock);
+    if (has_head) st<NT>(reinterpret_cast<v4f *>(dst) + threadIdx.x, h);
+#pragma unroll
+    for (int k = 0; k < SV; ++k)
+        if (i0 + k * kBlock < n4) st<NT>(reinterpret_cast<v4f *>(dst) + i0 + k * kBlock, x[k]);
+    const uint32_t t = (n4 << 2) + threadIdx.x;
+    if (t >= lo && t < hi) st<NT>(dst + t, ld<NT>(src + t));
+}
+
+template <bool NT, int SV>
+__global__ void __launch_bounds__(kBlock)
+k_pack(DeviceTables dt, uint32_t tile_begin, Divisor subs, Divisor workers, float *ws, uint64_t epad,
+       uint64_t base_off, bool worker_fastest)
+{
+    __shared__ float s_buf[Piece<SV>::kElems];
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
+    // consecutive workgroups take the same piece of consecutive workers (measured against one
+    // worker's whole buffer after the other: 261 against 270-290 us on ResNet-50 sizes, 2890
+    // against 2900-3080 us on VGG-16 sizes); a grid too long for one dimension puts the worker
+    // into the second one
+    const int nw = static_cast<int>(workers.d);
+    uint32_t lin = blockIdx.x, g = blockIdx.y;
+    if (worker_fastest) {
+        lin = div_uniform(blockIdx.x, workers);
+        g = blockIdx.x - lin * workers.d;
+    }
+    const uint32_t t = div_uniform(lin, subs), sub = lin - t * subs.d;
+    const TileDev tl = load_tile(dt.tiles + tile_begin + t);
+    float *merged = ws + static_cast<uint64_t>(g) * epad;
+    if (tl.nseg == 1) {
+        const SegDev sg = load_seg(dt.segs + tl.seg);
+        const float *src = table_load(dt.src + static_cast<size_t>(tl.seg) * nw + g) + tl.start;
+        const uint64_t moff = sg.plan_off - base_off + tl.start;
+        float *dst = merged + moff;
+        const bool aligned = (sg.flags & SEG_SRC_ALIGNED) && !(moff & 3);
+        const uint32_t head = aligned ? head_elems(dst) : 0;
+        uint32_t lo, hi;
+        if (!piece_range<SV>(sub, head, tl.n, lo, hi)) return;
+        if (hi == tl.n && threadIdx.x < tl.pad) st<NT>(dst + tl.n + threadIdx.x, 0.0f);  // padding after the layer
+        if (aligned) {
+            copy_piece_aligned<NT, SV>(src, dst, lo, hi, head);
+        } else {
+            global_to_lds<NT>(src + lo, s_buf, hi - lo);
+            __syncthreads();
+            lds_to_global<NT>(s_buf, dst + lo, hi - lo);
+        }
+    } else {
+        if (sub != 0) return;
+        stage_gather_offsets(dt, tl, s_rel, s_len);
+        float *run = merged + (tl.start - base_off);
+        for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
+            const uint32_t s = find_segment(s_rel, tl.nseg, k);
+            const uint32_t i = k - s_rel[s];
+            const float *src = dt.src[static_cast<size_t>(tl.seg + s) * nw + g];
+            st<NT>(run + k, i < s_len[s] ? ld<NT>(src + i) : 0.0f);  // zero in the padding between layers
+        }
+    }
+}
+
+template <bool STEP, bool NT, int SV>
+__global__ void __launch_bounds__(kBlock)
+k_unpack(DeviceTables dt, uint32_t tile_begin, Divisor subs, const float *reduced,
+         uint64_t base_off, float lr, float mu)
+{
+    __shared__ float s_buf[Piece<SV>::kElems];
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
+    const uint32_t t = div_uniform(blockIdx.x, subs), sub = blockIdx.x - t * subs.d;
+    const TileDev tl = load_tile(dt.tiles + tile_begin + t);
     if (tl.nseg == 1) {
         const SegDev sg = load_seg(dt.segs + tl.seg);
         const uint64_t moff = sg.plan_off - base_off + tl.start;
@@ -619,49 +701,73 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, const float *reduced, uint64_t ba
         float *outp = dt.out ? table_load(dt.out + tl.seg) + tl.start : nullptr;
         float *wp = STEP ? table_load(dt.w + tl.seg) + tl.start : nullptr;
         float *vp = STEP ? table_load(dt.v + tl.seg) + tl.start : nullptr;
-        const uint32_t n = tl.n;
         const bool tensors_al = (sg.flags & (SEG_OUT_ALIGNED | SEG_WV_ALIGNED)) ==
                                 (SEG_OUT_ALIGNED | SEG_WV_ALIGNED);
-        if constexpr (U > 0) {
-            if (tensors_al && !(moff & 3) && n == U * kBlock * 4) {
-                fast_tile<1, U, STEP, D, false>([src](int) { return src; }, outp, wp, vp, 1.0f, lr,
-                                                mu, pace);
-                return;
+        const bool aligned = tensors_al && !(moff & 3);
+        // the pieces follow the 128-byte boundaries of the tensor that is written (the weights
+        // when there is an update; momentum and out[] usually share their alignment)
+        const uint32_t head = aligned ? head_elems(STEP ? wp : outp) : 0;
+        uint32_t lo, hi;
+        if (!piece_range<SV>(sub, head, tl.n, lo, hi)) return;
+        if (aligned) {
+            if constexpr (!STEP) {
+                copy_piece_aligned<NT, SV>(src, outp, lo, hi, head);
+            } else {
+                const uint32_t body = lo == 0 ? head : lo;
+                const uint32_t i0 = (body >> 2) + threadIdx.x, n4 = hi >> 2;
+                if (lo == 0 && threadIdx.x < (head >> 2) && threadIdx.x < n4)
+                    finish<STEP, NT, v4f>(ld<NT>(reinterpret_cast<const v4f *>(src) + threadIdx.x), outp, wp, vp,
+                                          threadIdx.x, lr, mu);
+                v4f g[SV], w[SV], v[SV];
+#pragma unroll
+                for (int k = 0; k < SV; ++k) {
+                    const uint32_t i = i0 + k * kBlock;
+                    if (i < n4) {
+                        g[k] = ld<NT>(reinterpret_cast<const v4f *>(src) + i);
+                        w[k] = ld<NT>(reinterpret_cast<const v4f *>(wp) + i);
+                        v[k] = ld<NT>(reinterpret_cast<const v4f *>(vp) + i);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < SV; ++k) {
+                    const uint32_t i = i0 + k * kBlock;
+                    if (i < n4) {
+                        sgd_momentum(g[k], w[k], v[k], lr, mu);
+                        st<NT>(reinterpret_cast<v4f *>(vp) + i, v[k]);
+                        st<NT>(reinterpret_cast<v4f *>(wp) + i, w[k]);
+                        if (outp) st<NT>(reinterpret_cast<v4f *>(outp) + i, g[k]);
+                    }
+                }
+                const uint32_t tt = (n4 << 2) + threadIdx.x;
+                if (tt >= lo && tt < hi) finish<STEP, NT, float>(ld<NT>(src + tt), outp, wp, vp, tt, lr, mu);
             }
-        }
-        if (tensors_al && !(moff & 3)) {
-            const uint32_t n4 = n >> 2;
-            for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
-                const v4f avg = ld<NT>(reinterpret_cast<const v4f *>(src) + i);
-                finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
-            }
-            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock)
-                finish<STEP, NT, float>(ld<NT>(src + i), outp, wp, vp, i, lr, mu);
         } else {
-            global_to_lds<NT>(src, lds, n);
+            const uint32_t cnt = hi - lo;
+            global_to_lds<NT>(src + lo, s_buf, cnt);
             __syncthreads();
             uint32_t done = 0;
-            if (tensors_al) {
-                const uint32_t n4 = n >> 2;
+            if (tensors_al) {  // head = 0 here, so lo is a multiple of four: the tensor side is aligned
+                const uint32_t n4 = cnt >> 2;
                 for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
-                    const v4f avg = *reinterpret_cast<const v4f *>(lds + 4 * i);
-                    finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
+                    const v4f avg = *reinterpret_cast<const v4f *>(s_buf + 4 * i);
+                    finish<STEP, NT, v4f>(avg, outp ? outp + lo : nullptr, STEP ? wp + lo : nullptr,
+                                          STEP ? vp + lo : nullptr, i, lr, mu);
                 }
                 done = n4 << 2;
             }
-            for (uint32_t i = done + threadIdx.x; i < n; i += kBlock)
-                finish<STEP, NT, float>(lds[i], outp, wp, vp, i, lr, mu);
+            for (uint32_t i = done + threadIdx.x; i < cnt; i += kBlock)
+                finish<STEP, NT, float>(s_buf[i], outp, wp, vp, lo + i, lr, mu);
         }
     } else {
+        if (sub != 0) return;
         stage_gather_offsets(dt, tl, s_rel, s_len);
-        global_to_lds<NT>(reduced + (tl.start - base_off), lds, tl.n);
-        __syncthreads();
+        const float *run = reduced + (tl.start - base_off);
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
             const uint32_t s = find_segment(s_rel, tl.nseg, k);
             const uint32_t si = tl.seg + s;
             const uint32_t i = k - s_rel[s];
             if (i >= s_len[s]) continue;  // padding between two layers
-            finish<STEP, NT, float>(lds[k], dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
+            finish<STEP, NT, float>(ld<NT>(run + k), dt.out ? dt.out[si] : nullptr, STEP ? dt.w[si] : nullptr,
                                     STEP ? dt.v[si] : nullptr, i, lr, mu);
         }
     }
@@ -814,8 +920,8 @@ namespace {
 // request stream gains (N = 8: +3 to +5 % at 12 near 8 k workgroups, +2.5 % AlexNet sized;
 // N = 16: +1.5 % at 8 near 7 k, +4 % VGG-16 sized; more than that loses again).  The update
 // kernel pauses only in its gradient phase: N = 8 gains 1-2 % at 8 on long launches, N = 16
-// peaks at 4.  Copies (pack, unpack) keep the small values they were tuned with.
-enum class Stream { reduce, update, copy };
+// peaks at 4.
+enum class Stream { reduce, update };
 int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
 {
     if (pl.opt.pace >= 0) return pl.opt.pace;
@@ -824,9 +930,26 @@ int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
         if (workgroups < 6656) return 2;
         if (pl.N >= 16) return 8;
         return workgroups < 7680 ? 8 : 12;
-    case Stream::update: return workgroups < 8192 ? 2 : pl.N >= 16 ? 4 : 8;
-    default: return pl.N >= 16 ? 4 : 1;
+    default: return workgroups < 8192 ? 2 : pl.N >= 16 ? 4 : 8;
     }
+}
+}  // namespace
+
+namespace {
+constexpr int kCopyFloat4 = 1;  // float4 per lane and workgroup in pack / unpack (512-element pieces)
+
+// Pieces that cover the longest direct tile of the scope's list.  Full tiles have tile_elems
+// elements; a lone layer just under the gather threshold is a direct tile of its own and can be
+// longer than the shortened tiles of a group's list.
+uint32_t pieces_per_tile(const mgwfbp_plan_t &pl, const LaunchScope &sc, uint32_t piece_elems)
+{
+    const uint32_t longest = std::max(sc.tile_elems, std::min(pl.opt.small_elems, pl.opt.tile_elems));
+    return (longest + piece_elems - 1) / piece_elems;
+}
+
+Divisor divisor(uint32_t d)
+{
+    return Divisor{d, d <= 1 ? 0xffffffffu : static_cast<uint32_t>((uint64_t(1) << 32) / d)};
 }
 }  // namespace
 
@@ -867,23 +990,20 @@ int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint6
 {
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(sc.n_tiles, static_cast<uint32_t>(pl.N));
-    // N independent copies, half of the traffic writes: fastest at 9-10 workgroups per compute unit
-    // (measured: ResNet-50 sized 302 -> 275 us, VGG-16 sized 3202 -> 3045 us), which is what the
-    // staging buffer of a launch with gather tiles happens to give; ask for as much LDS without
-    const size_t staging = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    const size_t lds = std::max<size_t>(staging, 14000);
-    const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));
-    const bool deep = static_cast<uint64_t>(sc.n_tiles) * pl.N < 2048;
-    const int pace = pace_for(pl, Stream::copy, sc.n_tiles);
-    if (!pl.opt.nontemporal) {
-        k_pack<false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off, pace);
-    } else {
-        with_shape(true, u, deep, [&](auto uc, auto dc) {
-            k_pack<true, decltype(uc)::value, decltype(dc)::value>
-                <<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, pl.N, ws, epad, sc.base_off, pace);
-        });
+    const uint32_t subs = pieces_per_tile(pl, sc, Piece<kCopyFloat4>::kElems);
+    const uint64_t per_worker = static_cast<uint64_t>(sc.n_tiles) * subs;
+    const uint64_t all = per_worker * static_cast<uint64_t>(pl.N);
+    if (per_worker > 0x7fffffffull) {
+        set_error("pack: too many pieces for one launch");
+        return MGWFBP_EINVAL;
     }
+    const bool flat = all <= 0x7fffffffull;
+    const dim3 grid = flat ? dim3(static_cast<uint32_t>(all))
+                           : dim3(static_cast<uint32_t>(per_worker), static_cast<uint32_t>(pl.N));
+    if (pl.opt.nontemporal)
+        k_pack<true, kCopyFloat4><<<grid, kBlock, 0, s>>>(pl.dt, sc.tile_begin, divisor(subs), divisor(pl.N), ws, epad, sc.base_off, flat);
+    else
+        k_pack<false, kCopyFloat4><<<grid, kBlock, 0, s>>>(pl.dt, sc.tile_begin, divisor(subs), divisor(pl.N), ws, epad, sc.base_off, flat);
     return check_launch("pack kernel launch");
 }
 
@@ -922,23 +1042,22 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
 {
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(sc.n_tiles);
-    const size_t lds = sc.needs_lds ? static_cast<size_t>(pl.opt.tile_elems) * sizeof(float) : 0;
-    const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));
-    // a single read stream: eight loads in flight per wave beat one at any launch size
-    // (measured: scatter +6 %, with the update +1.5 %); with N streams it is the other way round
-    const bool deep = true;
-    const int pace = pace_for(pl, Stream::copy, sc.n_tiles);
-    if (!pl.opt.nontemporal) {
-        if (step) k_unpack<true, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
-        else k_unpack<false, false, 0, 1><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
-    } else {
-        with_shape(true, u, deep, [&](auto uc, auto dc) {
-            constexpr int U = decltype(uc)::value, D = decltype(dc)::value;
-            if (step) k_unpack<true, true, U, D><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
-            else k_unpack<false, true, U, D><<<grid, kBlock, lds, s>>>(pl.dt, sc.tile_begin, reduced, sc.base_off, lr, mu, pace);
-        });
+    const uint32_t subs = pieces_per_tile(pl, sc, Piece<kCopyFloat4>::kElems);
+    const uint64_t all = static_cast<uint64_t>(sc.n_tiles) * subs;
+    if (all > 0x7fffffffull) {
+        set_error("unpack: too many pieces for one launch");
+        return MGWFBP_EINVAL;
     }
+    const dim3 grid(static_cast<uint32_t>(all));
+    const bool nt = pl.opt.nontemporal != 0;
+#define MGWFBP_UNPACK(STEP, NT) \
+    k_unpack<STEP, NT, kCopyFloat4><<<grid, kBlock, 0, s>>>(pl.dt, sc.tile_begin, divisor(subs), reduced, sc.base_off, lr, mu)
+    if (step) {
+        if (nt) MGWFBP_UNPACK(true, true); else MGWFBP_UNPACK(true, false);
+    } else {
+        if (nt) MGWFBP_UNPACK(false, true); else MGWFBP_UNPACK(false, false);
+    }
+#undef MGWFBP_UNPACK
     return check_launch("unpack kernel launch");
 }
 

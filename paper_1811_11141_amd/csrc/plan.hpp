@@ -74,7 +74,6 @@ struct GroupInfo {
     uint32_t seg_begin = 0, seg_end = 0;
     uint32_t tile_begin = 0, tile_end = 0;
     uint32_t tile_elems = 0;  // tile length of the group's own list (<= the plan's tile_elems)
-    bool needs_lds = false;  // a gather tile or a misaligned copy exists in this group
     double start_ms = 0, finish_ms = 0;
 };
 
@@ -98,7 +97,6 @@ struct mgwfbp_plan_s {
     // binding
     bool bound = false, has_out = false, has_wv = false;
     int device = -1;
-    bool all_needs_lds = false;
     uint32_t all_tile_begin = 0, all_tile_count = 0;  // whole-plan ordering of the tiles
     // third list: the whole plan cut into longer tiles, for the fused reduce pass when that fills
     // the chip's batches of workgroups better (0 tiles = not built)
@@ -190,7 +188,6 @@ struct LaunchScope {
     uint64_t elems;       // elements in scope (one group or the whole plan)
     uint64_t base_off;    // plan_off of the scope's first element
     uint32_t tile_elems;  // length of the full tiles in this scope's list
-    bool needs_lds;
     int pace;                // >= 0: use this pause instead of the rule
     uint32_t occupancy_lds;  // unused dynamic LDS bytes, to cap the workgroups per CU (0 = no cap)
 };

@@ -126,7 +126,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     const uint32_t tile = pl.opt.tile_elems;
     const uint32_t small = std::min(pl.opt.small_elems, tile);
     // elements one gather tile may hold: a few per lane, since each costs a table search;
-    // small <= tile, so no tile of any kind exceeds tile_elems (the LDS staging size)
+    // small <= tile, so no tile of any kind exceeds tile_elems
     const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
     std::vector<TileDev> all_slow, all_full;
     // the longer tile lengths the fused reduce pass may use instead (only next to 4096)
@@ -139,12 +139,10 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     out_tbl.clear();
     w_tbl.clear();
     v_tbl.clear();
-    pl.all_needs_lds = false;
 
     for (size_t k = 0; k < pl.groups.size(); ++k) {
         GroupInfo &g = pl.groups[k];
         g.seg_begin = static_cast<uint32_t>(pl.segs.size());
-        g.needs_lds = false;
         for (int32_t l : g.layers) {
             SegDev s{};
             s.n = pl.p[l];
@@ -172,12 +170,6 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             } else {
                 s.flags |= SEG_WV_ALIGNED;
             }
-            // A copy between the tensor and a merged buffer is a plain 128-bit copy only when
-            // both sides agree on 16-byte alignment, for the group-relative and the
-            // plan-relative merged layout alike.
-            const uint32_t all = SEG_SRC_ALIGNED | SEG_OUT_ALIGNED | SEG_WV_ALIGNED;
-            if ((s.flags & all) != all || (s.group_off & 3) || (s.plan_off & 3))
-                g.needs_lds = true;
             pl.segs.push_back(s);
         }
         g.seg_end = static_cast<uint32_t>(pl.segs.size());
@@ -224,8 +216,6 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                     t.start = 0;
                     t.n = static_cast<uint32_t>(sd.n);
                     t.pad = static_cast<uint32_t>(padded_len(sd.n) - sd.n);
-                } else {
-                    g.needs_lds = true;
                 }
                 // (a lone layer of exactly one tile length runs the fast code like any full tile)
                 (t.nseg == 1 && t.n == tile_len ? full : slow).push_back(t);
@@ -248,7 +238,6 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         cut(tile, all_slow, all_full);
         if (longer_ok)
             for (int c = 1; c < kTileChoices; ++c) cut(kTileChoice[c], alt_slow[c], alt_full[c]);
-        pl.all_needs_lds = pl.all_needs_lds || g.needs_lds;
     }
     // A second copy of the tile list for whole-plan launches: every slow tile of every group
     // first, then the full tiles.
