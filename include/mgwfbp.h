@@ -232,6 +232,26 @@ int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspac
 int mgwfbp_step(mgwfbp_plan_t *plan, int32_t group, float lr, float momentum, void *workspace,
                 size_t workspace_bytes, void *hip_stream);
 
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): mgwfbp_pack_reduce_unpack through pack, reduce and
+ * unpack kernels with the workspace in a device array that is part of the library's own code
+ * object, MGWFBP_STATIC_WORKSPACE_BYTES long.  The call allocates nothing and frees nothing,
+ * on the host's heap or on the device, and makes no runtime query on a device the plan was
+ * bound on (mgwfbp_bind looks the array's address up; on any other device the first call does).
+ *   group        as for mgwfbp_pack_reduce_unpack (-1 = all groups at once)
+ *   hip_stream   a hipStream_t (NULL = the default stream)
+ * Results are those of mgwfbp_pack_reduce_unpack with a workspace, bit for bit.
+ * MGWFBP_EINVAL when mgwfbp_workspace_bytes(plan, group) exceeds the array; the other errors of
+ * mgwfbp_pack_reduce_unpack apply.  Every device the library runs on holds one copy of the
+ * array until the process ends, and all calls on a device share it: calls that overlap in time
+ * on one device (two streams, two threads, two plans) race on it; calls on one stream are safe.
+ * Nothing in it needs clearing between calls: every element that is read is written earlier by
+ * the same call.
+ */
+#define MGWFBP_STATIC_WORKSPACE_BYTES (64u * 1024u * 1024u)
+int mgwfbp_pack_reduce_unpack_static(mgwfbp_plan_t *plan, int32_t group, void *hip_stream);
+
 /* The three materialised steps on their own (workspace layout as above, required). */
 int mgwfbp_pack(mgwfbp_plan_t *plan, int32_t group, void *workspace, size_t workspace_bytes,
                 void *hip_stream);

@@ -21,12 +21,13 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
 OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES, OPT_PAD_ELEMS = 1, 2, 3, 4, 5, 6
 OPT_UPDATE_WGS_PER_CU = 7
+STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 
 EXPORTS = [
     "mgwfbp_plan", "mgwfbp_plan_explicit", "mgwfbp_plan_info", "mgwfbp_plan_timeline",
     "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_tune", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
-    "mgwfbp_pack_reduce", "mgwfbp_unpack_update",
+    "mgwfbp_pack_reduce", "mgwfbp_unpack_update", "mgwfbp_pack_reduce_unpack_static",
     "mgwfbp_run_iteration", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
     "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
@@ -62,6 +63,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_workspace_bytes.argtypes = [vp, i32, P(sz)]
     lib.mgwfbp_tune.argtypes = [vp, vp, P(i32), P(f64)]
     lib.mgwfbp_pack_reduce_unpack.argtypes = [vp, i32, vp, sz, vp]
+    lib.mgwfbp_pack_reduce_unpack_static.argtypes = [vp, i32, vp]
     lib.mgwfbp_step.argtypes = [vp, i32, f32, f32, vp, sz, vp]
     for name in ("mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack"):
         getattr(lib, name).argtypes = [vp, i32, vp, sz, vp]
@@ -228,6 +230,10 @@ class Plan:
     def pack_reduce_unpack(self, group: int = -1, workspace=None, stream=None) -> None:
         ws, nb = self._ws(workspace)
         _check(_lib.mgwfbp_pack_reduce_unpack(self._h, group, ws, nb, C.c_void_p(_stream(stream))))
+
+    def pack_reduce_unpack_static(self, group: int = -1, stream=None) -> None:
+        """The materialised path with the library's own static workspace (no allocation)."""
+        _check(_lib.mgwfbp_pack_reduce_unpack_static(self._h, group, C.c_void_p(_stream(stream))))
 
     def step(self, lr: float, momentum: float, group: int = -1, workspace=None, stream=None) -> None:
         ws, nb = self._ws(workspace)

@@ -267,6 +267,12 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     pl->has_out = out != nullptr;
     pl->has_wv = w != nullptr;
     pl->bound = true;
+    // set-up is the place for runtime queries: find this device's copy of the static workspace
+    // now, so that mgwfbp_pack_reduce_unpack_static never has to ask
+    if (int rc = prepare_static_workspace()) {
+        release_device(pl);
+        return rc;
+    }
     return MGWFBP_OK;
 }
 }  // namespace

@@ -158,6 +158,10 @@ void finish_plan(mgwfbp_plan_t &pl);
 int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws,
               size_t bytes, void *stream);
 
+// noalloc.hip: resolves the device address of the library's static workspace on the current
+// device (once per device; mgwfbp_bind calls it so that later calls need no runtime query)
+int prepare_static_workspace();
+
 // tables.cpp
 void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *out,
                   float *const *w, float *const *v, std::vector<const float *> &src_tbl,
