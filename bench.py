@@ -1,30 +1,38 @@
 #!/usr/bin/env python3
 """Throughput of the merged pack+reduce+unpack pass on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--variant fused]
 
 A step is one pass of the whole hot path over one synthetic gradient set: all N workers'
 per-layer gradients are packed, summed in worker order, scaled by 1/N and written back to
 per-layer tensors, for every group of the merge plan, in one fused launch
 (mgwfbp_pack_reduce_unpack with group = -1).  Inputs are resident in HBM before the timed
-region.  Consecutive steps rotate over several independently allocated gradient sets so that
-no step finds its inputs in the 256 MB Infinity Cache.
-
-The timed plans launch by the library's built-in rules.  `extra.fused_tuned` is the same pass
-after mgwfbp_tune has timed a few launch shapes at set-up and kept the fastest (its choices are
-listed; 0 = the rules won); --tune 1 applies that to the timed plans themselves.
+region.  Consecutive steps rotate over several independently allocated gradient sets (and
+merged buffers, where a variant reads one) so that no step finds its inputs in the 256 MB
+Infinity Cache.
 
 Prints one JSON line.  `value` = algorithmic bytes 4*(N+1)*P per step / wall time per step.
 `roofline.achieved` = the same bytes / average duration per launch from HIP events recorded on
 the launch stream: every timed step lies inside one bracket of 8 back-to-back steps, and a
-bracket's duration / 8 is the time per launch (an event pair costs ~5 us of stream time, so a
-pair around every single launch would tax both this figure and the whole-job one by 3 %).
+bracket's duration / 8 is the time per launch (an event pair costs 2-5 us of stream time, which a
+pair around every single launch would add to what it measures; all figures under `extra` are
+taken the same way).  `roofline.traffic` = HBM bytes per launch from the rocprofv3 counter runs
+summarised under profiles/ (profiles/traffic.json; null for a workload or variant that has none).
+
+With --extras 1 (default) the same gradient sets also go through the other forms of the path
+(update, materialised chain, launch per group, the two halves a transport calls, the three
+materialised kernels one by one) and through plain streaming probes.  With --others 1 (default
+for the default workload) the other gradient sets the paper's evaluation names -- VGG-16 at
+N = 16 and N = 8 and at three start-up costs, GoogLeNet, AlexNet -- are measured too, each in a
+child process of its own that is started before this process touches the GPU, and reported under
+`extra.<set>`.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -33,16 +41,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+EVERY = 8              # consecutive steps bracketed by one HIP-event pair
 
-# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by what the same counters read for the library's plain copy probe.  Filled from the
-# summaries under profiles/; None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    ("resnet50", "fused"): 920_979_000,      # profiles/k_fused_resnet50_n8_hbm_traffic.md
-    ("resnet50", "step"): 1_330_446_000,
-    ("vgg16", "fused"): 9_411_698_000,       # profiles/k_fused_vgg16_n16_hbm_traffic.md
-    ("vgg16", "step"): 11_627_816_000,
-}
+VARIANTS = ("fused", "step", "step_without_out", "materialised", "per_group", "per_group_2streams", "pack",
+            "reduce", "unpack", "pack_reduce", "unpack_only", "unpack_update", "unpack_update_without_out")
+
+
+def units(variant: str, N: int) -> int:
+    """Algorithmic (for the materialised forms: actual) traffic in units of 4P bytes."""
+    return {"fused": N + 1, "per_group": N + 1, "per_group_2streams": N + 1, "materialised": N + 1,
+            "step": N + 5, "step_without_out": N + 4, "pack": 2 * N, "reduce": N + 1, "unpack": 2,
+            "pack_reduce": N + 1, "unpack_only": 2, "unpack_update": 6, "unpack_update_without_out": 5}[variant]
+
+
+KERNEL_OF = {"fused": "k_fused", "per_group": "k_fused", "per_group_2streams": "k_fused", "step": "k_fused (update)",
+             "step_without_out": "k_fused (update)", "materialised": "k_pack+k_reduce+k_unpack", "pack": "k_pack",
+             "reduce": "k_reduce", "unpack": "k_unpack", "pack_reduce": "k_fused (merged out)",
+             "unpack_only": "k_unpack", "unpack_update": "k_unpack (update)",
+             "unpack_update_without_out": "k_unpack (update)"}
 
 
 def parse():
@@ -58,14 +74,62 @@ def parse():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--small", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
-    ap.add_argument("--variant", default="fused", choices=["fused", "step", "materialised", "per_group"],
-                    help="what one step runs (the headline is 'fused')")
+    ap.add_argument("--variant", default="fused", choices=VARIANTS, help="what one step runs (the headline is 'fused')")
     ap.add_argument("--tune", type=int, default=0,
                     help="1: let mgwfbp_tune pick the launch shape of the timed plans at set-up (untimed)")
     ap.add_argument("--extras", type=int, default=1, help="also time the other variants and the probes")
+    ap.add_argument("--others", type=int, default=-1,
+                    help="also measure the other gradient sets in child processes (-1: only for the default workload)")
+    ap.add_argument("--also", default="", help="comma-separated variants to time besides --variant (child runs use it)")
     ap.add_argument("--cpu-baseline", type=int, default=1)
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--cpu-seconds", type=float, default=14.0)
     return ap.parse_args()
+
+
+# the other gradient sets of the paper's evaluation, each measured in a child process
+OTHER_SETS = (
+    ("vgg16_n16", ["--workload", "vgg16", "--also", "step"], 40),
+    ("vgg16_n8", ["--workload", "vgg16", "--n-workers", "8", "--also", "step"], 60),
+    ("vgg16_n16_a0.1", ["--workload", "vgg16", "--a-ms", "0.1"], 30),
+    ("vgg16_n16_a2", ["--workload", "vgg16", "--a-ms", "2.0"], 30),
+    ("googlenet_n8", ["--workload", "googlenet", "--also",
+                      "step,per_group,per_group_2streams,pack,unpack,unpack_update,unpack_update_without_out"], 200),
+    ("alexnet_n8", ["--workload", "alexnet", "--also", "step"], 100),
+)
+
+
+def run_others():
+    """Each set in a fresh process (a set allocated after another set's large blocks were freed
+    measured ~3 % slower than in a run of its own).  Returns {name: result or error}."""
+    res = {}
+    for name, argv, steps in OTHER_SETS:
+        cmd = [sys.executable, os.path.abspath(__file__), *argv, "--steps", str(steps), "--warmup", str(max(5, steps // 8)),
+               "--extras", "0", "--others", "0", "--cpu-baseline", "0"]
+        try:
+            out = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+            line = [l for l in out.stdout.splitlines() if l.startswith("{")]
+            if out.returncode != 0 or not line:
+                res[name] = {"error": f"rc {out.returncode}: {(out.stderr or out.stdout)[-300:]}"}
+                continue
+            r = json.loads(line[-1])
+            keep = {"P": r["config"]["P"], "n_workers": r["config"]["n_workers"], "a_ms": r["config"]["a_ms"],
+                    "groups": r["config"]["groups"], "rotating_sets": r["config"]["rotating_sets"],
+                    "fused": {"us_per_launch": r["roofline"]["kernel_avg_us"], "GBps_algorithmic": r["roofline"]["achieved"],
+                              "frac_of_peak": r["roofline"]["frac"], "value_GBps": r["value"],
+                              "traffic": r["roofline"]["traffic"]}}
+            keep.update(r.get("extra", {}))
+            res[name] = keep
+        except Exception as e:  # a failing side measurement is reported, not fatal
+            res[name] = {"error": f"{type(e).__name__}: {e}"}
+    return res
+
+
+def load_traffic():
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {}
 
 
 def main():
@@ -75,6 +139,9 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (the other workers are "
               "replicas in the same HBM); run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    do_others = args.others == 1 or (args.others < 0 and args.workload == "resnet50" and args.variant == "fused"
+                                     and not args.n_workers and args.extras)
+    others = run_others() if do_others else None    # before this process initialises the GPU
 
     import numpy as np
     import torch
@@ -89,13 +156,12 @@ def main():
     N, P, L = w.n_workers, w.P, w.L
     mode = {"optimal": mg.MODE_OPTIMAL, "greedy": mg.MODE_PAPER_GREEDY, "wfbp": mg.MODE_WFBP,
             "single": mg.MODE_SINGLE}[args.mode]
+    traffic = load_traffic().get(f"{args.workload}_n{N}", {})
 
-    alg_bytes = {"fused": 4 * (N + 1) * P, "per_group": 4 * (N + 1) * P,
-                 "materialised": 4 * (N + 1) * P, "step": 4 * (N + 5) * P}
     set_bytes = 4 * (N + 1) * P
     n_sets = args.sets if args.sets > 0 else max(3, min(4, int(np.ceil(768e6 / set_bytes)) + 1))
-    if args.workload == "vgg16":
-        n_sets = args.sets if args.sets > 0 else 1  # 9.4 GB per pass evicts itself
+    if args.workload == "vgg16" and args.sets <= 0:
+        n_sets = 1 if N >= 16 else 2  # 9.4 GB (N = 8: 5 GB) per pass evicts itself
 
     def new_plan(mode=mode):
         pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, N, mode)
@@ -107,6 +173,14 @@ def main():
             pl.set_option(mg.OPT_NONTEMPORAL, args.nontemporal)
         return pl
 
+    also = [v for v in args.also.split(",") if v]
+    wanted = {args.variant, *also}
+    if args.extras:
+        wanted |= set(VARIANTS)
+    need_ws = wanted & {"materialised", "pack", "reduce", "unpack"}
+    need_mb = wanted & {"pack_reduce", "unpack_only", "unpack_update", "unpack_update_without_out"}
+    need_alt = wanted & {"step_without_out", "unpack_update_without_out"}
+
     sets = []
     for s in range(n_sets):
         grads = wl.make_gradients(w, wl.BASE_SEED + 1000 * 2 + s, dev)
@@ -114,65 +188,113 @@ def main():
         wt, vt = wl.make_weights(w, wl.BASE_SEED + s, dev)
         pl = new_plan()
         pl.bind(grads, out, wt, vt)
-        sets.append({"plan": pl, "grads": grads, "out": out, "w": wt, "v": vt})
+        st = {"plan": pl, "grads": grads, "out": out, "w": wt, "v": vt}
+        if need_mb:     # one merged buffer per set, so that a reader never finds it in the cache
+            st["mb"] = torch.empty((P + 63) // 64 * 64, dtype=torch.float32, device=dev).normal_(0, 1e-3)
+        if need_ws:     # reduce and unpack read what pack / reduce left there (filled at set-up)
+            st["ws"] = torch.empty(pl.workspace_bytes() // 4, dtype=torch.float32, device=dev)
+        if need_alt:    # the same tensors bound without out[]: the update alone
+            st["plan_no_out"] = new_plan()
+            st["plan_no_out"].bind(grads, None, wt, vt)
+        sets.append(st)
     tuned = [s_["plan"].tune()["candidate"] for s_ in sets] if args.tune else None
     info = sets[0]["plan"].info()
     n_groups = info["n_groups"]
-    ws = None
-    if args.variant == "materialised" or args.extras:
-        ws = torch.empty(sets[0]["plan"].workspace_bytes() // 4, dtype=torch.float32, device=dev)
 
     stream = torch.cuda.Stream(device=dev)
+    side = torch.cuda.Stream(device=dev)
 
     def run_step(variant, i):
-        pl = sets[i % n_sets]["plan"]
+        st = sets[i % n_sets]
+        pl = st["plan"]
         if variant == "fused":
             pl.pack_reduce_unpack(stream=stream)
         elif variant == "step":
             pl.step(0.1, 0.9, stream=stream)
+        elif variant == "step_without_out":
+            st["plan_no_out"].step(0.1, 0.9, stream=stream)
         elif variant == "materialised":
-            pl.pack_reduce_unpack(workspace=ws, stream=stream)
+            pl.pack_reduce_unpack(workspace=st["ws"], stream=stream)
         elif variant == "per_group":
             for k in range(n_groups):
                 pl.pack_reduce_unpack(group=k, stream=stream)
+        elif variant == "per_group_2streams":
+            # consecutive groups alternate between two streams of equal priority: one group's
+            # ramp-up overlaps the previous group's drain (they touch disjoint tensors)
+            fork = torch.cuda.Event()
+            fork.record(stream)
+            side.wait_event(fork)
+            for k in range(n_groups):
+                pl.pack_reduce_unpack(group=k, stream=stream if k % 2 == 0 else side)
+            join = torch.cuda.Event()
+            join.record(side)
+            stream.wait_event(join)
+        elif variant == "pack":
+            pl.pack(st["ws"], stream=stream)
+        elif variant == "reduce":
+            pl.reduce(st["ws"], stream=stream)
+        elif variant == "unpack":
+            pl.unpack(st["ws"], stream=stream)
+        elif variant == "pack_reduce":
+            pl.pack_reduce(st["mb"], stream=stream)
+        elif variant == "unpack_only":
+            pl.unpack_update(st["mb"], stream=stream)
+        elif variant == "unpack_update":
+            pl.unpack_update(st["mb"], update=True, lr=0.1, momentum=0.9, stream=stream)
+        elif variant == "unpack_update_without_out":
+            st["plan_no_out"].unpack_update(st["mb"], update=True, lr=0.1, momentum=0.9, stream=stream)
+        else:
+            raise ValueError(variant)
 
-    EVERY = 8  # consecutive steps bracketed by one HIP-event pair
-
-    def timed(variant, steps, warmup, launch_events):
+    def timed(step_fn, steps, warmup):
+        """Wall time per step and, from HIP-event brackets of up to EVERY back-to-back steps that
+        together cover every timed step, the average / median / minimum time per step."""
         for i in range(warmup):
-            run_step(variant, i)
+            step_fn(i)
         torch.cuda.synchronize()
-        # every step lies inside exactly one bracket of up to EVERY back-to-back steps; a bracket's
-        # duration / its steps is the time per launch without the cost of the event records
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-                min(EVERY, steps - i)) for i in range(0, steps, EVERY)] if launch_events else []
+                min(EVERY, steps - i)) for i in range(0, steps, EVERY)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            if evs and i % EVERY == 0:
+            if i % EVERY == 0:
                 evs[i // EVERY][0].record(stream)
-            run_step(variant, warmup + i)
-            if evs and (i % EVERY == EVERY - 1 or i == steps - 1):
+            step_fn(warmup + i)
+            if i % EVERY == EVERY - 1 or i == steps - 1:
                 evs[i // EVERY][1].record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        ms = (t1 - t0) * 1e3 / steps
-        kern = None
-        if evs:
-            tot = np.array([a.elapsed_time(b) for a, b, _ in evs])
-            cnt = np.array([c for _, _, c in evs], dtype=np.float64)
-            per = tot / cnt
-            kern = {"avg_ms": float(tot.sum() / cnt.sum()), "median_ms": float(np.median(per)),
-                    "min_ms": float(per.min()), "samples": int(cnt.sum())}
-        return ms, kern
+        tot = np.array([a.elapsed_time(b) for a, b, _ in evs])
+        cnt = np.array([c for _, _, c in evs], dtype=np.float64)
+        per = tot / cnt
+        return (t1 - t0) * 1e3 / steps, {"avg_ms": float(tot.sum() / cnt.sum()), "median_ms": float(np.median(per)),
+                                         "min_ms": float(per.min()), "samples": int(cnt.sum())}
 
-    # set-up, before the W warm-up steps: one pass over every rotating set, so that no set meets
-    # the kernel (code load, address translation of freshly allocated tensors) inside the timed steps
+    def side_figure(variant, steps, warmup):
+        for i in range(n_sets):
+            run_step(variant, i)
+        _, kk = timed(lambda i: run_step(variant, i), steps, warmup)
+        nbytes = 4 * units(variant, N) * P
+        gbps = nbytes / (kk["avg_ms"] * 1e-3) / 1e9
+        fig = {"us_per_step": round(kk["avg_ms"] * 1e3, 2), "min_us": round(kk["min_ms"] * 1e3, 2),
+               "bytes_per_step": nbytes, "GBps": round(gbps, 1), "frac_of_peak": round(gbps / HBM_PEAK_GBS, 4),
+               "kernel": KERNEL_OF[variant], "traffic": traffic.get(variant)}
+        if variant == "materialised":   # the chain really moves 3N + 3 units
+            fig["GBps_actual_traffic"] = round(4 * (3 * N + 3) * P / (kk["avg_ms"] * 1e-3) / 1e9, 1)
+        return fig
+
+    # set-up, before the W warm-up steps: the materialised kernels need a filled workspace, and
+    # one pass over every rotating set keeps code load and address translation of freshly
+    # allocated tensors out of the timed steps
+    for st in sets:
+        if "ws" in st:
+            st["plan"].pack(st["ws"], stream=stream)
+            st["plan"].reduce(st["ws"], stream=stream)
     for i in range(n_sets):
         run_step(args.variant, i)
     torch.cuda.synchronize()
-    ms_per_step, kern = timed(args.variant, args.steps, args.warmup, launch_events=True)
-    bytes_step = alg_bytes[args.variant]
+    ms_per_step, kern = timed(lambda i: run_step(args.variant, i), args.steps, args.warmup)
+    bytes_step = 4 * units(args.variant, N) * P
     value = bytes_step / (ms_per_step * 1e-3) / 1e9
     achieved = bytes_step / (kern["avg_ms"] * 1e-3) / 1e9
 
@@ -197,26 +319,29 @@ def main():
                    "percent_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant)),
-                     "kernel": "k_fused" if args.variant in ("fused", "per_group", "step") else "k_pack+k_reduce+k_unpack",
+                     "traffic": traffic.get(args.variant),
+                     "kernel": KERNEL_OF[args.variant],
                      "kernel_avg_us": round(kern["avg_ms"] * 1e3, 2),
                      "kernel_median_us": round(kern["median_ms"] * 1e3, 2),
                      "kernel_min_us": round(kern["min_ms"] * 1e3, 2),
                      "event_samples": kern["samples"]},
     }
 
+    extra = {}
+    k2, w2 = max(24, args.steps // 4), max(5, args.warmup // 4)
+    try:
+        for variant in also:
+            if variant != args.variant:
+                extra[variant] = side_figure(variant, k2, w2)
+    except Exception as e:
+        torch.cuda.synchronize()
+        extra["error"] = f"{type(e).__name__}: {e}"
     if args.extras:
-        extra = {}
         # the headline line is complete without these: a failing extra is reported, not fatal
         try:
-            k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 4)
-            for variant in ("fused", "step", "materialised", "per_group"):
-                if variant == args.variant:
-                    continue
-                ms, kk = timed(variant, k2, w2, launch_events=True)
-                extra[variant] = {"ms_per_step": round(ms, 5),
-                                  "GBps_algorithmic": round(alg_bytes[variant] / (ms * 1e-3) / 1e9, 1),
-                                  "event_avg_us": round(kk["avg_ms"] * 1e3, 2)}
+            for variant in VARIANTS:
+                if variant != args.variant and variant not in extra:
+                    extra[variant] = side_figure(variant, k2, w2)
             # the launch-per-group sequence captured once per gradient set into a HIP graph
             graphs = []
             torch.cuda.synchronize()
@@ -229,60 +354,22 @@ def main():
                 graphs.append(gph)
             torch.cuda.synchronize()
             with torch.cuda.stream(stream):
-                for i in range(w2):
-                    graphs[i % n_sets].replay()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for i in range(k2):
-                    graphs[i % n_sets].replay()
-                e1.record(stream)
-                torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / k2
-            extra["per_group_graph"] = {"groups": n_groups, "us_per_step": round(us, 2),
-                                        "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
+                _, kk = timed(lambda i: graphs[i % n_sets].replay(), k2, w2)
+            extra["per_group_graph"] = {"groups": n_groups, "us_per_step": round(kk["avg_ms"] * 1e3, 2),
+                                        "GBps": round(set_bytes / (kk["avg_ms"] * 1e-3) / 1e9, 1)}
             del graphs
-            # the update without writing the averaged gradients out (out[] not bound): N + 4 units
-            alt = []
-            for st in sets:
-                pa = new_plan()
-                pa.bind(st["grads"], None, st["w"], st["v"])
-                alt.append(pa)
-            for i in range(w2):
-                alt[i % n_sets].step(0.1, 0.9, stream=stream)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for i in range(k2):
-                alt[i % n_sets].step(0.1, 0.9, stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / k2
-            extra["step_without_out"] = {"us_per_step": round(us, 2),
-                                         "GBps_algorithmic": round(4 * (N + 4) * P / (us * 1e-6) / 1e9, 1)}
-            for pa in alt:
-                pa.destroy()
             # the same pass after mgwfbp_tune (set-up, untimed) has picked the launch shape
-            if not args.tune and args.variant == "fused":
+            if not args.tune:
                 alt, picks = [], []
                 for st in sets:
                     pa = new_plan()
                     pa.bind(st["grads"], st["out"], st["w"], st["v"])
                     picks.append(pa.tune(stream)["candidate"])
                     alt.append(pa)
-                for i in range(w2):
-                    alt[i % n_sets].pack_reduce_unpack(stream=stream)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for i in range(k2):
-                    alt[i % n_sets].pack_reduce_unpack(stream=stream)
-                e1.record(stream)
-                torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / k2
-                extra["fused_tuned"] = {"us_per_step": round(us, 2), "choices": picks,
-                                        "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1),
-                                        "frac_of_peak": round(alg_bytes["fused"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+                _, kk = timed(lambda i: alt[i % n_sets].pack_reduce_unpack(stream=stream), k2, w2)
+                gb = set_bytes / (kk["avg_ms"] * 1e-3) / 1e9
+                extra["fused_tuned"] = {"us_per_step": round(kk["avg_ms"] * 1e3, 2), "choices": picks,
+                                        "GBps": round(gb, 1), "frac_of_peak": round(gb / HBM_PEAK_GBS, 4)}
                 for pa in alt:
                     pa.destroy()
             # the two extreme plans (every tensor its own group / one group) through the same fused
@@ -293,80 +380,35 @@ def main():
                     pa = new_plan(md)
                     pa.bind(st["grads"], st["out"], st["w"], st["v"])
                     alt.append(pa)
-                for i in range(w2):
-                    alt[i % n_sets].pack_reduce_unpack(stream=stream)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for i in range(k2):
-                    alt[i % n_sets].pack_reduce_unpack(stream=stream)
-                e1.record(stream)
-                torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / k2
-                extra[nm] = {"groups": alt[0].info()["n_groups"], "us_per_step": round(us, 2),
-                             "GBps_algorithmic": round(alg_bytes["fused"] / (us * 1e-6) / 1e9, 1)}
+                _, kk = timed(lambda i: alt[i % n_sets].pack_reduce_unpack(stream=stream), k2, w2)
+                extra[nm] = {"groups": alt[0].info()["n_groups"], "us_per_step": round(kk["avg_ms"] * 1e3, 2),
+                             "GBps": round(set_bytes / (kk["avg_ms"] * 1e-3) / 1e9, 1)}
                 for pa in alt:
                     pa.destroy()
-            # the three materialised kernels one by one (actual bytes: pack 8NP, reduce 4(N+1)P, unpack 8P)
-            pl0 = sets[0]["plan"]
-            for nm, fn, nbytes in (("k_pack", lambda: pl0.pack(ws, stream=stream), 8 * N * P),
-                                   ("k_reduce", lambda: pl0.reduce(ws, stream=stream), 4 * (N + 1) * P),
-                                   ("k_unpack", lambda: pl0.unpack(ws, stream=stream), 8 * P)):
-                for _ in range(w2):
-                    fn()
-                torch.cuda.synchronize()
-                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
-                for a, b in evs:
-                    a.record(stream)
-                    fn()
-                    b.record(stream)
-                torch.cuda.synchronize()
-                d = np.array([a.elapsed_time(b) for a, b in evs])
-                extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
-                             "GBps_actual": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1),
-                             "frac_of_peak": round(nbytes / (float(d.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-            # the two halves a transport calls: sources -> merged buffer (N+1 units), merged buffer ->
-            # out (2 units) or -> w, v, out (6 units); rotating over the gradient sets
-            mb = torch.empty((P + 63) // 64 * 64, dtype=torch.float32, device=dev)
-            for nm, fn, nbytes in (
-                    ("pack_reduce", lambda i: sets[i % n_sets]["plan"].pack_reduce(mb, stream=stream), 4 * (N + 1) * P),
-                    ("unpack_only", lambda i: sets[i % n_sets]["plan"].unpack_update(mb, stream=stream), 8 * P),
-                    ("unpack_update", lambda i: sets[i % n_sets]["plan"].unpack_update(mb, update=True, lr=0.1, momentum=0.9, stream=stream), 24 * P)):
-                for i in range(w2):
-                    fn(i)
-                torch.cuda.synchronize()
-                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
-                for i in range(k2):
-                    evs[i][0].record(stream)
-                    fn(i)
-                    evs[i][1].record(stream)
-                torch.cuda.synchronize()
-                d = np.array([a.elapsed_time(b) for a, b in evs])
-                extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
-                             "GBps_actual": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1),
-                             "frac_of_peak": round(nbytes / (float(d.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-            del mb
-            # plain streaming ceilings: N reads + 1 write over contiguous buffers, and a copy
-            n_probe = (P + 3) // 4 * 4
-            src = torch.empty(N * n_probe, dtype=torch.float32, device=dev).normal_()
-            dst = torch.empty(n_probe, dtype=torch.float32, device=dev)
-            srcs = [src] + [torch.empty_like(src).normal_() for _ in range(n_sets - 1)]
-            for nm, fn, nbytes in (
-                    ("probe_streams", lambda i: mg.mgwfbp_probe_streams(srcs[i % n_sets], N, n_probe, n_probe, dst, stream), 4 * (N + 1) * n_probe),
-                    ("probe_copy", lambda i: mg.mgwfbp_probe_copy(srcs[i % n_sets], srcs[(i + 1) % n_sets], N * n_probe, stream), 8 * N * n_probe)):
-                for i in range(w2):
-                    fn(i)
-                torch.cuda.synchronize()
-                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k2)]
-                for i in range(k2):
-                    evs[i][0].record(stream)
-                    fn(i)
-                    evs[i][1].record(stream)
-                torch.cuda.synchronize()
-                d = np.array([a.elapsed_time(b) for a, b in evs])
-                extra[nm] = {"event_avg_us": round(float(d.mean()) * 1e3, 2),
-                             "GBps": round(nbytes / (float(d.mean()) * 1e-3) / 1e9, 1)}
-            del src, dst, srcs
+            # plain streaming kernels on buffers of the same size, rotated like the gradient sets:
+            # what one read stream, one write stream, a copy and the vendor's copy reach on this machine
+            n_probe = (N * P + 3) // 4 * 4
+            bufs = [torch.empty(n_probe, dtype=torch.float32, device=dev).normal_() for _ in range(max(3, n_sets))]
+            sink = torch.zeros(64, dtype=torch.float32, device=dev)
+            nb = len(bufs)
+            probes = (
+                ("probe_read", lambda i: mg.mgwfbp_probe_read(bufs[i % nb], n_probe, sink, stream), 4 * n_probe),
+                ("probe_fill", lambda i: mg.mgwfbp_probe_fill(bufs[i % nb], 1.0, n_probe, stream), 4 * n_probe),
+                ("probe_copy", lambda i: mg.mgwfbp_probe_copy(bufs[i % nb], bufs[(i + 1) % nb], n_probe, stream), 8 * n_probe),
+                ("probe_streams", lambda i: mg.mgwfbp_probe_streams(bufs[i % nb], N, n_probe // N // 4 * 4,
+                                                                   n_probe // N // 4 * 4, bufs[(i + 1) % nb], stream),
+                 4 * (N + 1) * (n_probe // N // 4 * 4)),
+            )
+            for nm, fn, nbytes in probes:
+                _, kk = timed(fn, k2, w2)
+                gb = nbytes / (kk["avg_ms"] * 1e-3) / 1e9
+                extra[nm] = {"us": round(kk["avg_ms"] * 1e3, 2), "GBps": round(gb, 1), "frac_of_peak": round(gb / HBM_PEAK_GBS, 4)}
+            with torch.cuda.stream(stream):
+                _, kk = timed(lambda i: bufs[(i + 1) % nb].copy_(bufs[i % nb], non_blocking=True), k2, w2)
+            gb = 8 * n_probe / (kk["avg_ms"] * 1e-3) / 1e9
+            extra["vendor_copy"] = {"what": "torch Tensor.copy_ device to device", "us": round(kk["avg_ms"] * 1e3, 2),
+                                    "GBps": round(gb, 1), "frac_of_peak": round(gb / HBM_PEAK_GBS, 4)}
+            del bufs
             # host side, once per training job: planning and binding time
             host = {}
             for nm, md in (("optimal", mg.MODE_OPTIMAL), ("theorem1", mg.MODE_PAPER_GREEDY)):
@@ -387,28 +429,17 @@ def main():
                 tg = wl.make_gradients(tw, seed, dev)
                 tp = mg.mgwfbp_plan(tw.p, tw.tb_ms, 0.0, tw.a_ms, tw.b_ms_per_byte, tw.n_workers, mg.MODE_OPTIMAL)
                 tp.bind(tg, [torch.empty_like(t) for t in tg[0]])
-                for _ in range(5):
-                    tp.pack_reduce_unpack(stream=stream)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for _ in range(50):
-                    tp.pack_reduce_unpack(stream=stream)
-                e1.record(stream)
-                torch.cuda.synchronize()
-                lat.append(e0.elapsed_time(e1) * 1e3 / 50)
+                _, kk = timed(lambda i: tp.pack_reduce_unpack(stream=stream), 48, 5)
+                lat.append(kk["avg_ms"] * 1e3)
                 tp.destroy()
             extra["tiny_config_us_per_launch"] = {"median": round(float(np.median(lat)), 2),
                                                   "min": round(float(np.min(lat)), 2), "seeds": len(lat)}
-            # the other gradient set the target names (VGG-16-shaped, N = 16), so that one default
-            # run carries both: fused pass and update, rules only, one set (9.4 GB per pass evicts
-            # itself).  Only this one: sets allocated after large blocks were freed measured 3 % slower
-            # than in a run of their own (AlexNet 340 against 333 us), so the others keep their own runs
-            if args.workload == "resnet50" and torch.cuda.mem_get_info()[0] > 24e9:
-                extra["vgg16_n16"] = other_workload(mg, wl, torch, "vgg16", stream, dev)
         except Exception as e:
             torch.cuda.synchronize()
             extra["error"] = f"{type(e).__name__}: {e}"
+    if others is not None:
+        extra.update(others)
+    if extra:
         result["extra"] = extra
     props = torch.cuda.get_device_properties(0)
     result["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
@@ -416,7 +447,7 @@ def main():
 
     if args.cpu_baseline:
         try:
-            result["cpu_baseline"] = cpu_baseline(w, sets[0], info, args.cpu_seconds)
+            result["cpu_baseline"] = cpu_baseline(w, sets[0], args.cpu_seconds)
             result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)
         except Exception as e:  # e.g. the oracle's C library is not built: say so in the line
             result["cpu_baseline"] = {"value": None, "unit": "GB/s", "cores": 0, "kind": "oracle",
@@ -425,73 +456,43 @@ def main():
     print(json.dumps(result))
 
 
-def other_workload(mg, wl, torch, name, stream, dev, launches=20, sets=1):
-    """Fused pass and update on another workload, rules only, timed with events on `stream`;
-    `sets` independently allocated gradient sets are rotated (one is enough when a pass moves
-    far more than the 256 MB Infinity Cache holds)."""
-    w = wl.cnn_workload(name)
-    plans, keep = [], []
-    for s in range(sets):
-        grads = wl.make_gradients(w, wl.BASE_SEED + 7000 + s, dev)
-        out = [torch.empty_like(t) for t in grads[0]]
-        wt, vt = wl.make_weights(w, wl.BASE_SEED + 7 + s, dev)
-        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
-        pl.bind(grads, out, wt, vt)
-        plans.append(pl)
-        keep.append((grads, out, wt, vt))
-    res = {"P": int(w.P), "n_workers": int(w.n_workers), "groups": plans[0].info()["n_groups"], "rotating_sets": sets}
-    for key, units, call in (("fused", w.n_workers + 1, lambda pl: pl.pack_reduce_unpack(stream=stream)),
-                             ("step", w.n_workers + 5, lambda pl: pl.step(0.1, 0.9, stream=stream))):
-        for i in range(2 * sets + 1):
-            call(plans[i % sets])
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record(stream)
-        for i in range(launches):
-            call(plans[i % sets])
-        e1.record(stream)
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / launches
-        gbps = 4 * units * w.P / (us * 1e-6) / 1e9
-        res[key] = {"us_per_step": round(us, 2), "GBps_algorithmic": round(gbps, 1),
-                    "frac_of_peak": round(gbps / 8000.0, 4)}
-    for pl in plans:
-        pl.destroy()
-    del keep
-    torch.cuda.empty_cache()
-    return res
-
-
-def cpu_baseline(w, s, info, budget_s):
-    """The CPU oracle, as it stands, on the same gradient set: whole passes of
-    pack -> reduce -> unpack over host copies of set 0, single thread (the oracle's default)."""
-    import numpy as np
-
+def cpu_baseline(w, s, budget_s):
+    """The CPU oracle, as it stands, on the same gradient set: whole passes of pack -> reduce ->
+    unpack per group over host copies of set 0, first on one thread, then with its element loops
+    split over all host cores the process may use; the faster leg is the reported value."""
     from oracle import datapath as od
 
     N, P = w.n_workers, w.P
     groups = s["plan"].groups()
     g_np = [[t.cpu().numpy() for t in rep] for rep in s["grads"]]
     od.merged_gradient_path([[a[:16].copy() for a in rep] for rep in g_np], groups)  # load + warm
-    passes, t0 = 0, time.perf_counter()
-    while True:
-        od.merged_gradient_path(g_np, groups, threads=1)
-        passes += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s or passes >= 1000:
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    nthreads = max(1, min(od.max_threads(), usable))
+    legs = {}
+    for threads, share in ((1, 0.5), (nthreads, 0.5)):
+        passes, t0 = 0, time.perf_counter()
+        while True:
+            od.merged_gradient_path(g_np, groups, threads=threads)
+            passes += 1
+            el = time.perf_counter() - t0
+            if (el >= budget_s * share and passes >= 3) or passes >= 1000:
+                break
+        legs[threads] = {"threads": threads, "passes": passes, "seconds": round(el, 2),
+                         "seconds_per_pass": round(el / passes, 4),
+                         "value": round(4 * (N + 1) * P / (el / passes) / 1e9, 3)}
+        if nthreads == 1:
             break
-    sec = el / passes
-    nthreads = min(od.max_threads(), os.cpu_count() or 1)
-    t1 = time.perf_counter()
-    od.merged_gradient_path(g_np, groups, threads=nthreads)
-    sec_mt = time.perf_counter() - t1
-    return {"value": round(4 * (N + 1) * P / sec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{passes} whole passes of the oracle (pack, reduce, unpack per group) over "
-                      f"gradient set 0 of the same workload, {el:.1f} s",
-            "seconds_per_pass": round(sec, 4), "ns_per_element": round(sec / P * 1e9, 3),
-            "all_threads": {"threads": nthreads, "value": round(4 * (N + 1) * P / sec_mt / 1e9, 3),
-                            "seconds_per_pass": round(sec_mt, 4),
-                            "note": "reduce loop split statically over threads; pack/unpack stay serial"}}
+    best = max(legs.values(), key=lambda x: x["value"])
+    total_s = sum(x["seconds"] for x in legs.values())
+    return {"value": best["value"], "unit": "GB/s", "cores": best["threads"], "kind": "oracle",
+            "sample": f"whole passes of the oracle (pack, reduce, unpack per group) over gradient set 0 of the same "
+                      f"workload: {', '.join(str(x['passes']) + ' on ' + str(x['threads']) + ' thread(s)' for x in legs.values())}, "
+                      f"{total_s:.1f} s in all",
+            "seconds_per_pass": best["seconds_per_pass"], "ns_per_element": round(best["seconds_per_pass"] / P * 1e9, 3),
+            "legs": list(legs.values())}
 
 
 if __name__ == "__main__":

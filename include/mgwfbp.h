@@ -125,7 +125,9 @@ int mgwfbp_plan_explicit(int32_t L, const uint64_t *p_elems, const double *tb_ms
                          mgwfbp_plan_t **out);
 
 /*
- * Read a plan back.  Every out-pointer is a host pointer and may be NULL.
+ * Read a plan back: the merged-gradient set M of Eq. 22 as groups, and where each layer sits in
+ * its group's merged message (Condition 3 / Eq. 16: a merged layer's parameters are appended to
+ * those of the layer below it).  Every out-pointer is a host pointer and may be NULL.
  *   n_groups         number of groups
  *   group_of_layer   [L]  group id of each layer
  *   offset_in_group  [L]  element offset of the layer inside its group's merged buffer
@@ -179,7 +181,9 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *plan, uint64_t *n_segments, uint64_t
                        size_t segments_cap, uint64_t *n_tiles, uint64_t *tiles, size_t tiles_cap);
 
 /*
- * Attach tensors and upload the segment, tile and pointer tables (once; the pointers are
+ * Attach the per-layer tensors Algorithm 2 works on -- every worker's gradients (the layers it
+ * pushes into the queue), the averaged gradient and the weights of its update line, plus the
+ * momentum buffers -- and upload the segment, tile and pointer tables (once; the pointers are
  * not re-read from host memory afterwards).  A second call replaces the binding.
  *   grads  host array [N*L] of device pointers, worker-major: grads[g*L + l] is worker g's
  *          gradient of layer l, p_elems[l] floats, 4-byte aligned (16-byte alignment of
@@ -215,6 +219,9 @@ int mgwfbp_tune(mgwfbp_plan_t *plan, void *hip_stream, int32_t *chosen, double *
 int mgwfbp_workspace_bytes(const mgwfbp_plan_t *plan, int32_t group, size_t *bytes);
 
 /*
+ * What Algorithm 2's communication thread does with one merged group: the layer buffer `lb` of
+ * the group's gradients, the all-reduce of it -- whose arithmetic is Eq. 2's average over the N
+ * workers -- and the averaged gradients back in per-layer form.
  * Pack + N-way reduce + unpack of one group (or all groups when group = -1) into out[].
  *   workspace == NULL : one fused pass that never materialises the merged buffers.
  *   workspace != NULL : device pointer, 256-byte aligned, at least mgwfbp_workspace_bytes;
@@ -226,8 +233,10 @@ int mgwfbp_pack_reduce_unpack(mgwfbp_plan_t *plan, int32_t group, void *workspac
                               size_t workspace_bytes, void *hip_stream);
 
 /*
- * Same reduction fused with the update v = momentum*v + avg; w = w - lr*v on the bound
- * w[], v[].  The averaged gradient is also written to out[] when out[] is bound.
+ * Same reduction fused with Algorithm 2's update line W = W - eta * grad (Eq. 1 with the
+ * averaged gradient of Eq. 2), extended by a momentum buffer: v = momentum*v + avg;
+ * w = w - lr*v on the bound w[], v[]; momentum = 0 is the paper's update exactly.  The averaged
+ * gradient is also written to out[] when out[] is bound.
  */
 int mgwfbp_step(mgwfbp_plan_t *plan, int32_t group, float lr, float momentum, void *workspace,
                 size_t workspace_bytes, void *hip_stream);
@@ -345,6 +354,22 @@ int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t updat
                          double *group_finish_ms, double *t_iter_ms);
 
 /*
+ * mgwfbp_run_iteration with several communication streams: group k is enqueued on
+ * comm_streams[k mod n_comm_streams], so consecutive groups may overlap (one group's ramp-up
+ * hides the previous group's drain; they touch disjoint tensors).  Each group still waits for
+ * its own gradients (Condition 2); what is given up is the serial channel of Eq. 7, which is a
+ * property of a network, not of one GPU's memory.  n_comm_streams = 1 is mgwfbp_run_iteration.
+ *   comm_streams    host array [n_comm_streams] of different hipStream_t handles, 1 .. 8 of
+ *                   them, default priority.  Results do not depend on their number.
+ * With more than one stream group_start_ms[k] >= group_finish_ms[k-1] no longer holds;
+ * t_iter_ms is the end of the last group to finish.
+ */
+int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
+                                 float momentum, void *compute_stream, void *const *comm_streams,
+                                 int32_t n_comm_streams, double *group_ready_ms,
+                                 double *group_start_ms, double *group_finish_ms, double *t_iter_ms);
+
+/*
  * The same iteration captured once into a HIP graph and replayed: one graph launch per
  * iteration instead of several runtime calls per group, for loops in which the schedule
  * (plan, backward times, update parameters, bound tensors) does not change.
@@ -356,9 +381,9 @@ int mgwfbp_run_iteration(mgwfbp_plan_t *plan, const double *tb_ms, int32_t updat
  *   mgwfbp_iteration_replay   launches the graph on `hip_stream`.  t_iter_ms == NULL: returns
  *       at once (asynchronous).  Otherwise waits for the stream and reports the time from the
  *       start of the backward pass to the end of the last group, read from the device clock.
- *   mgwfbp_iteration_destroy  frees the graph.  Destroy it before destroying the plan.  After
- *       a new mgwfbp_bind the graph is stale: replay then returns MGWFBP_ESTATE.  Replays of
- *       one plan must not overlap.
+ *   mgwfbp_iteration_destroy  frees the graph.  After a new mgwfbp_bind, or once the plan has
+ *       been destroyed, the graph is stale: replay then returns MGWFBP_ESTATE (the handle itself
+ *       stays valid until it is destroyed).  Replays of one plan must not overlap.
  */
 typedef struct mgwfbp_iteration_s mgwfbp_iteration_t; /* opaque */
 int mgwfbp_iteration_capture(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
@@ -366,16 +391,6 @@ int mgwfbp_iteration_capture(mgwfbp_plan_t *plan, const double *tb_ms, int32_t u
                              mgwfbp_iteration_t **out);
 int mgwfbp_iteration_replay(mgwfbp_iteration_t *iteration, void *hip_stream, double *t_iter_ms);
 void mgwfbp_iteration_destroy(mgwfbp_iteration_t *iteration);
-
-/*
- * Bandwidth probes used to calibrate measurements; they are not part of the method.
- *   mgwfbp_probe_copy    dst[i] = src[i]                              (1 read + 1 write stream)
- *   mgwfbp_probe_streams dst[i] = sum_g src[g*stride_elems + i] / n   (n read + 1 write streams)
- * All pointers are device pointers, 16-byte aligned; n_elems a multiple of 4.
- */
-int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream);
-int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_elems,
-                         uint64_t n_elems, float *dst, void *hip_stream);
 
 void mgwfbp_plan_destroy(mgwfbp_plan_t *plan);
 

@@ -28,10 +28,12 @@ EXPORTS = [
     "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_tune", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update", "mgwfbp_pack_reduce_unpack_static",
-    "mgwfbp_run_iteration", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
-    "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_probe_copy", "mgwfbp_probe_streams", "mgwfbp_plan_destroy",
+    "mgwfbp_run_iteration", "mgwfbp_run_iteration_streams", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
+    "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
+# include/mgwfbp_probe.h: bandwidth probes for the benchmark, not part of the method
+PROBE_EXPORTS = ["mgwfbp_probe_copy", "mgwfbp_probe_read", "mgwfbp_probe_fill", "mgwfbp_probe_streams"]
 
 
 class MgwfbpError(RuntimeError):
@@ -78,13 +80,16 @@ def _load() -> C.CDLL:
     lib.mgwfbp_table2_cost.argtypes = [i32, i32, f64, f64, f64, P(f64), P(f64)]
     lib.mgwfbp_scaling_curve.argtypes = [i32, P(u64), P(f64), f64, i32, f64, f64, f64, i32, P(i32), i32,
                                          P(f64), P(f64)]
+    lib.mgwfbp_run_iteration_streams.argtypes = [vp, P(f64), i32, f32, f32, vp, P(vp), i32, P(f64), P(f64), P(f64), P(f64)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
+    lib.mgwfbp_probe_read.argtypes = [vp, u64, vp, vp]
+    lib.mgwfbp_probe_fill.argtypes = [vp, f32, u64, vp]
     lib.mgwfbp_probe_streams.argtypes = [vp, i32, u64, u64, vp, vp]
     lib.mgwfbp_plan_destroy.argtypes = [vp]
     lib.mgwfbp_plan_destroy.restype = None
     lib.mgwfbp_last_error.argtypes = []
     lib.mgwfbp_last_error.restype = C.c_char_p
-    for name in EXPORTS:
+    for name in EXPORTS + PROBE_EXPORTS:
         if name not in ("mgwfbp_plan_destroy", "mgwfbp_iteration_destroy", "mgwfbp_last_error"):
             getattr(lib, name).restype = i32
     return lib
@@ -264,7 +269,8 @@ class Plan:
     def run_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
                       lr: float = 0.0, momentum: float = 0.0, timeline: bool = True) -> dict:
         """One event-driven iteration (see mgwfbp_run_iteration); returns the measured timeline,
-        or only t_iter_ms with timeline=False (no per-group timestamps are taken then)."""
+        or only t_iter_ms with timeline=False (no per-group timestamps are taken then).
+        comm_stream may be a list of streams (see mgwfbp_run_iteration_streams)."""
         ng = self.info()["n_groups"]
         ready, gs, gf = np.zeros(ng), np.zeros(ng), np.zeros(ng)
         t_iter = C.c_double()
@@ -272,10 +278,17 @@ class Plan:
         tb = None if tb_ms is None else np.ascontiguousarray(tb_ms, dtype=np.float64)
         if tb is not None and tb.shape != (self.L,):
             raise ValueError("tb_ms must have L entries")
-        _check(_lib.mgwfbp_run_iteration(self._h, None if tb is None else dp(tb), int(update), lr, momentum,
-                                         C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)),
-                                         dp(ready) if timeline else None, dp(gs) if timeline else None,
-                                         dp(gf) if timeline else None, C.byref(t_iter)))
+        outs = (dp(ready) if timeline else None, dp(gs) if timeline else None,
+                dp(gf) if timeline else None, C.byref(t_iter))
+        if isinstance(comm_stream, (list, tuple)):
+            arr = (C.c_void_p * len(comm_stream))(*[_stream(s) for s in comm_stream])
+            _check(_lib.mgwfbp_run_iteration_streams(self._h, None if tb is None else dp(tb), int(update), lr,
+                                                     momentum, C.c_void_p(_stream(compute_stream)), arr,
+                                                     len(comm_stream), *outs))
+        else:
+            _check(_lib.mgwfbp_run_iteration(self._h, None if tb is None else dp(tb), int(update), lr, momentum,
+                                             C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)),
+                                             *outs))
         if not timeline:
             return {"t_iter_ms": t_iter.value}
         return {"group_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
@@ -418,6 +431,15 @@ def mgwfbp_scaling_curve(p, tb_ms, tf_ms: float, algorithm: str, alpha_ms: float
 def mgwfbp_probe_copy(src, dst, n_elems: int, stream=None) -> None:
     _check(_lib.mgwfbp_probe_copy(C.c_void_p(_ptr(src)), C.c_void_p(_ptr(dst)), n_elems,
                                   C.c_void_p(_stream(stream))))
+
+
+def mgwfbp_probe_read(src, n_elems: int, sink, stream=None) -> None:
+    _check(_lib.mgwfbp_probe_read(C.c_void_p(_ptr(src)), n_elems, C.c_void_p(_ptr(sink)),
+                                  C.c_void_p(_stream(stream))))
+
+
+def mgwfbp_probe_fill(dst, value: float, n_elems: int, stream=None) -> None:
+    _check(_lib.mgwfbp_probe_fill(C.c_void_p(_ptr(dst)), value, n_elems, C.c_void_p(_stream(stream))))
 
 
 def mgwfbp_probe_streams(src, n_streams: int, stride_elems: int, n_elems: int, dst,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmgwfbp.so")
-SOURCES = ["api.cpp", "planner.cpp", "tables.cpp", "executor.cpp", "kernels.hip", "noalloc.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "tables.cpp", "executor.cpp", "kernels.hip", "noalloc.hip", "probes.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -98,6 +98,7 @@ int scope_of(const mgwfbp_plan_t *pl, int32_t group, LaunchScope &sc, bool long_
         return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
     sc.pace = -1;
     sc.occupancy_lds = 0;
+    sc.resolve_only = false;
     if (group < 0) {
         sc.tile_begin = pl->all_tile_begin;
         sc.n_tiles = pl->all_tile_count;
@@ -173,6 +174,16 @@ int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, v
     if ((rc = launch_pack(*pl, sc, w, epad, stream))) return rc;
     if ((rc = launch_reduce(*pl, sc, w, epad, stream))) return rc;
     return launch_unpack(*pl, sc, w + static_cast<uint64_t>(pl->N) * epad, step, lr, mu, stream);
+}
+
+int resolve_scope_kernel(mgwfbp_plan_t *pl, int32_t group, bool step)
+{
+    int rc = check_bound(pl, !step, step);
+    if (rc) return rc;
+    LaunchScope sc{};
+    if ((rc = scope_of(pl, group, sc, !step))) return rc;
+    sc.resolve_only = true;
+    return launch_fused(*pl, sc, step, 0.0f, 0.0f, nullptr);
 }
 
 }  // namespace mgwfbp
@@ -698,29 +709,6 @@ int mgwfbp_unpack_update(mgwfbp_plan_t *pl, int32_t group, const void *merged, s
     });
 }
 
-int mgwfbp_probe_copy(const float *src, float *dst, uint64_t n_elems, void *hip_stream)
-{
-    return guarded([&]() -> int {
-        if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
-        if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) || (n_elems & 3u))
-            return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned and n_elems a multiple of 4");
-        return launch_probe_copy(src, dst, n_elems, hip_stream);
-    });
-}
-
-int mgwfbp_probe_streams(const float *src, int32_t n_streams, uint64_t stride_elems,
-                         uint64_t n_elems, float *dst, void *hip_stream)
-{
-    return guarded([&]() -> int {
-        if (!src || !dst) return fail(MGWFBP_EINVAL, "src or dst is NULL");
-        if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) ||
-            (n_elems & 3u) || (stride_elems & 3u) || stride_elems < n_elems)
-            return fail(MGWFBP_EINVAL, "probe buffers must be 16-byte aligned, n_elems and stride multiples "
-                                       "of 4, stride >= n_elems");
-        return launch_probe_streams(src, n_streams, stride_elems, n_elems, dst, hip_stream);
-    });
-}
-
 int mgwfbp_fit_cost(int32_t n, const double *bytes, const double *ms, double *a_ms,
                     double *b_ms_per_byte)
 {
@@ -790,6 +778,7 @@ int mgwfbp_scaling_curve(int32_t L, const uint64_t *p_elems, const double *tb_ms
 void mgwfbp_plan_destroy(mgwfbp_plan_t *pl)
 {
     if (!pl) return;
+    detach_iterations(pl);
     release_device(pl);
     delete pl;
 }

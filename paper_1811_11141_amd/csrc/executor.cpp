@@ -74,21 +74,26 @@ int check_iteration_args(mgwfbp_plan_t *pl, const double *tb, int32_t update)
     return MGWFBP_OK;
 }
 
-// Enqueue one iteration on the two streams: gate (publishes time zero in the plan's clock word 0),
-// then per group a backward stand-in on `cs`, an event, and the group's reduction on `ms` behind
-// that event; finally word 1 of the clock gets the device time at which the last group ended.
-// g_start / g_finish may be NULL (no per-group timestamps).
+// Enqueue one iteration: gate (publishes time zero in the plan's clock word 0) on `cs`, then per
+// group a backward stand-in on `cs`, an event, and the group's reduction behind that event on
+// communication stream k mod n; finally word 1 of the clock gets the device time at which the
+// last group ended.  With one communication stream the groups follow each other as on the
+// serial channel of Eq. 7; with more, consecutive groups go to different streams and may overlap
+// (they touch disjoint tensors), each still waiting for its own gradients (Condition 2).
+// g_start / g_finish may be NULL (no per-group timestamps).  `joins` holds one untimed event per
+// communication stream beyond the first.
 int enqueue_iteration(mgwfbp_plan_t *pl, const double *tb, bool update, float lr, float momentum,
-                      hipStream_t cs, hipStream_t ms, double gate_ms, hipEvent_t base,
+                      hipStream_t cs, const std::vector<hipStream_t> &ms, double gate_ms, hipEvent_t base,
                       const std::vector<hipEvent_t> &g_ready, const std::vector<hipEvent_t> *g_start,
-                      const std::vector<hipEvent_t> *g_finish)
+                      const std::vector<hipEvent_t> *g_finish, const std::vector<hipEvent_t> &joins)
 {
     int rc;
     if ((rc = launch_spin(gate_ms, cs, pl->d_clock))) return rc;
-    // the communication stream must not start before the backward pass does
+    // no communication stream may start before the backward pass does
     hipError_t e = hipEventRecord(base, cs);
     if (e != hipSuccess) return hip_fail("hipEventRecord", e);
-    if ((e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+    for (hipStream_t m : ms)
+        if ((e = hipStreamWaitEvent(m, base, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
 
     // Backward pass, highest layer first.  Only the moment a group's lowest layer finishes
     // matters to the communication side, so the layers of a group share one stand-in kernel
@@ -99,18 +104,44 @@ int enqueue_iteration(mgwfbp_plan_t *pl, const double *tb, bool update, float lr
         if (pl->merged[l]) continue;  // layer l rides with layer l-1: nothing is sent yet
         // layer l is the lowest layer of its group: the group's gradients are complete
         const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
+        hipStream_t m = ms[k % ms.size()];
         if ((rc = launch_spin_until(elapsed_ms, pl->d_clock, cs))) return rc;
         if ((e = hipEventRecord(g_ready[k], cs)) != hipSuccess) return hip_fail("hipEventRecord", e);
-        if ((e = hipStreamWaitEvent(ms, g_ready[k], 0)) != hipSuccess)
+        if ((e = hipStreamWaitEvent(m, g_ready[k], 0)) != hipSuccess)
             return hip_fail("hipStreamWaitEvent", e);
-        if (g_start && (e = hipEventRecord((*g_start)[k], ms)) != hipSuccess)
+        if (g_start && (e = hipEventRecord((*g_start)[k], m)) != hipSuccess)
             return hip_fail("hipEventRecord", e);
-        if ((rc = run_scope(pl, static_cast<int32_t>(k), update, lr, momentum, nullptr, 0, ms))) return rc;
-        if (g_finish && (e = hipEventRecord((*g_finish)[k], ms)) != hipSuccess)
+        if ((rc = run_scope(pl, static_cast<int32_t>(k), update, lr, momentum, nullptr, 0, m))) return rc;
+        if (g_finish && (e = hipEventRecord((*g_finish)[k], m)) != hipSuccess)
             return hip_fail("hipEventRecord", e);
     }
-    // groups run in order on the communication stream: its end is the end of the iteration (Eq. 8)
-    return launch_spin(0.0, ms, pl->d_clock + 1);
+    // the first communication stream collects the others: its end is the end of the iteration (Eq. 8)
+    for (size_t i = 1; i < ms.size(); ++i) {
+        if ((e = hipEventRecord(joins[i - 1], ms[i])) != hipSuccess) return hip_fail("hipEventRecord", e);
+        if ((e = hipStreamWaitEvent(ms[0], joins[i - 1], 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+    }
+    return launch_spin(0.0, ms[0], pl->d_clock + 1);
+}
+
+// The communication streams of a call: distinct handles, at least one, at most kMaxCommStreams.
+constexpr int32_t kMaxCommStreams = 8;
+int collect_streams(void *const *comm_streams, int32_t n, std::vector<hipStream_t> &out)
+{
+    if (!comm_streams || n < 1 || n > kMaxCommStreams) {
+        set_error("need 1 to " + std::to_string(kMaxCommStreams) + " communication streams");
+        return MGWFBP_EINVAL;
+    }
+    out.clear();
+    for (int32_t i = 0; i < n; ++i) {
+        hipStream_t s = static_cast<hipStream_t>(comm_streams[i]);
+        for (hipStream_t t : out)
+            if (t == s) {
+                set_error("the communication streams must be different streams");
+                return MGWFBP_EINVAL;
+            }
+        out.push_back(s);
+    }
+    return MGWFBP_OK;
 }
 
 // (clock word 1 - clock word 0) in milliseconds, after the streams have drained.
@@ -127,16 +158,17 @@ int read_t_iter(const mgwfbp_plan_t *pl, double *t_iter_ms)
 
 namespace {
 int run_iteration_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
-                                    float momentum, void *compute_stream, void *comm_stream,
-                                    double *group_ready_ms, double *group_start_ms,
-                                    double *group_finish_ms, double *t_iter_ms)
+                       float momentum, void *compute_stream, void *const *comm_streams,
+                       int32_t n_comm_streams, double *group_ready_ms, double *group_start_ms,
+                       double *group_finish_ms, double *t_iter_ms)
 {
     const double *tb = tb_ms ? tb_ms : (pl ? pl->tb.data() : nullptr);
     int rc = check_iteration_args(pl, tb, update);
     if (rc) return rc;
     const size_t G = pl->groups.size();
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-    hipStream_t ms = static_cast<hipStream_t>(comm_stream);
+    std::vector<hipStream_t> ms;
+    if ((rc = collect_streams(comm_streams, n_comm_streams, ms))) return rc;
 
     // Per-group timestamps are taken only when the caller asks for them: a timed event record
     // costs a few microseconds of stream time, which is a large part of a short group's cost.
@@ -145,12 +177,14 @@ int run_iteration_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, f
     Events pool;
     hipEvent_t base;
     std::vector<hipEvent_t> g_ready(G), g_start(time_comm ? G : 0), g_finish(time_comm ? G : 0);
+    std::vector<hipEvent_t> joins(ms.size() - 1);
     rc = pool.make(&base);
     for (size_t k = 0; k < G && !rc; ++k) {
         rc = pool.make(&g_ready[k], time_ready);
         if (!rc && time_comm) rc = pool.make(&g_start[k]);
         if (!rc && time_comm) rc = pool.make(&g_finish[k]);
     }
+    for (size_t i = 0; i < joins.size() && !rc; ++i) rc = pool.make(&joins[i], false);
     if (rc) return rc;
 
     // A zero-length stand-in first: the first launch of a kernel loads its code.  Then a gate:
@@ -163,10 +197,14 @@ int run_iteration_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, f
     // not stretch the backward pass.
     if ((rc = launch_spin(0.0, cs))) return rc;
     rc = enqueue_iteration(pl, tb, update != 0, lr, momentum, cs, ms, 1.0 + 0.06 * static_cast<double>(G),
-                           base, g_ready, time_comm ? &g_start : nullptr, time_comm ? &g_finish : nullptr);
+                           base, g_ready, time_comm ? &g_start : nullptr, time_comm ? &g_finish : nullptr, joins);
     // whatever was enqueued must drain before the events are destroyed or read
     const hipError_t e1 = hipStreamSynchronize(cs);
-    const hipError_t e2 = hipStreamSynchronize(ms);
+    hipError_t e2 = hipSuccess;
+    for (hipStream_t m : ms) {
+        const hipError_t em = hipStreamSynchronize(m);
+        if (e2 == hipSuccess) e2 = em;
+    }
     if (rc) return rc;
     if (e1 != hipSuccess) return hip_fail("hipStreamSynchronize(compute)", e1);
     if (e2 != hipSuccess) return hip_fail("hipStreamSynchronize(comm)", e2);
@@ -202,7 +240,19 @@ extern "C" int mgwfbp_run_iteration(mgwfbp_plan_t *pl, const double *tb_ms, int3
                                     double *group_finish_ms, double *t_iter_ms)
 {
     return guarded([&]() -> int {
-        return run_iteration_impl(pl, tb_ms, update, lr, momentum, compute_stream, comm_stream,
+        void *const one[1] = {comm_stream};
+        return run_iteration_impl(pl, tb_ms, update, lr, momentum, compute_stream, one, 1,
+                                  group_ready_ms, group_start_ms, group_finish_ms, t_iter_ms);
+    });
+}
+
+extern "C" int mgwfbp_run_iteration_streams(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                            float momentum, void *compute_stream, void *const *comm_streams,
+                                            int32_t n_comm_streams, double *group_ready_ms,
+                                            double *group_start_ms, double *group_finish_ms, double *t_iter_ms)
+{
+    return guarded([&]() -> int {
+        return run_iteration_impl(pl, tb_ms, update, lr, momentum, compute_stream, comm_streams, n_comm_streams,
                                   group_ready_ms, group_start_ms, group_finish_ms, t_iter_ms);
     });
 }
@@ -215,6 +265,8 @@ struct mgwfbp_iteration_s {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
+
+extern "C" void mgwfbp_iteration_destroy(mgwfbp_iteration_t *it);
 
 namespace {
 int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
@@ -247,11 +299,15 @@ int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t updat
     if (!rc) rc = pool.make(&done, false);
     for (size_t k = 0; k < G && !rc; ++k) rc = pool.make(&g_ready[k], false);
     if (rc) return rc;
-    // load the code of every kernel the graph will hold before capturing (a first launch may
-    // allocate, which capture forbids): one eager pass of the stand-in and of each group
+    // A kernel's first use makes the runtime load and look up its code, which may allocate, and
+    // capture forbids that.  So before capturing: one eager launch of the stand-in (it touches
+    // no memory of the caller's), and for every group a look-up of the very kernel its launch
+    // will pick, without launching it -- running a group here would write out[], w[] and v[].
     if ((rc = launch_spin(0.0, cs))) return rc;
     hipError_t e = hipStreamSynchronize(cs);
     if (e != hipSuccess) return hip_fail("hipStreamSynchronize", e);
+    for (size_t k = 0; k < pl->groups.size(); ++k)
+        if ((rc = resolve_scope_kernel(pl, static_cast<int32_t>(k), update != 0))) return rc;
 
     mgwfbp_iteration_t *it = new (std::nothrow) mgwfbp_iteration_t();
     if (!it) {
@@ -260,13 +316,15 @@ int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t updat
     }
     it->plan = pl;
     it->binding_generation = pl->binding_generation;
+    pl->iterations.push_back(it);  // so that destroying the plan first can be told apart
     if ((e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal)) != hipSuccess) {
-        delete it;
+        mgwfbp_iteration_destroy(it);
         return hip_fail("hipStreamBeginCapture", e);
     }
     // A short gate only: replaying a graph needs no head start for the host, but time zero still
     // has to be published by a kernel that precedes every stand-in.
-    rc = enqueue_iteration(pl, tb, update != 0, lr, momentum, cs, ms, 0.05, base, g_ready, nullptr, nullptr);
+    rc = enqueue_iteration(pl, tb, update != 0, lr, momentum, cs, std::vector<hipStream_t>{ms}, 0.05, base, g_ready,
+                           nullptr, nullptr, std::vector<hipEvent_t>());
     // join the communication stream back into the capturing stream (also on failure, so that
     // the capture can end and both streams stay usable)
     hipError_t ej = hipEventRecord(done, ms);
@@ -277,8 +335,7 @@ int iteration_capture_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t updat
     if (rc == MGWFBP_OK && (e = hipGraphInstantiate(&it->exec, it->graph, nullptr, nullptr, 0)) != hipSuccess)
         rc = hip_fail("hipGraphInstantiate", e);
     if (rc) {
-        if (it->graph) (void)hipGraphDestroy(it->graph);
-        delete it;
+        mgwfbp_iteration_destroy(it);
         return rc;
     }
     *out = it;
@@ -302,6 +359,10 @@ extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream,
             set_error("iteration handle is NULL");
             return MGWFBP_EINVAL;
         }
+        if (!it->plan) {
+            set_error("the plan of this iteration has been destroyed");
+            return MGWFBP_ESTATE;
+        }
         if (!it->plan->bound || it->plan->binding_generation != it->binding_generation) {
             set_error("the plan was re-bound after the capture: capture the iteration again");
             return MGWFBP_ESTATE;
@@ -315,9 +376,26 @@ extern "C" int mgwfbp_iteration_replay(mgwfbp_iteration_t *it, void *hip_stream,
     });
 }
 
+namespace mgwfbp {
+// The plan is going away: its iteration handles stay valid objects but can no longer replay.
+void detach_iterations(mgwfbp_plan_t *pl)
+{
+    for (mgwfbp_iteration_s *it : pl->iterations) it->plan = nullptr;
+    pl->iterations.clear();
+}
+}  // namespace mgwfbp
+
 extern "C" void mgwfbp_iteration_destroy(mgwfbp_iteration_t *it)
 {
     if (!it) return;
+    if (it->plan) {
+        std::vector<mgwfbp_iteration_s *> &v = it->plan->iterations;
+        for (size_t i = 0; i < v.size(); ++i)
+            if (v[i] == it) {
+                v.erase(v.begin() + static_cast<std::ptrdiff_t>(i));
+                break;
+            }
+    }
     if (it->exec) (void)hipGraphExecDestroy(it->exec);
     if (it->graph) (void)hipGraphDestroy(it->graph);
     delete it;

@@ -792,35 +792,6 @@ __global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls,
         __builtin_nontemporal_store(static_cast<uint64_t>(__builtin_amdgcn_s_memrealtime()), clock);
 }
 
-// ------------------------------------------------------------------------------------------
-// Bandwidth probes
-// ------------------------------------------------------------------------------------------
-constexpr uint32_t kProbeTile = 8192;
-
-__global__ void __launch_bounds__(kBlock) k_probe_copy(const float *src, float *dst, uint64_t n)
-{
-    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * kProbeTile;
-    const uint32_t cnt = static_cast<uint32_t>(n - t0 < kProbeTile ? n - t0 : kProbeTile) >> 2;
-    const v4f *s4 = reinterpret_cast<const v4f *>(src + t0);
-    v4f *d4 = reinterpret_cast<v4f *>(dst + t0);
-    for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) st<true>(d4 + i, ld<true>(s4 + i));
-}
-
-template <int NW>
-__global__ void __launch_bounds__(kBlock)
-k_probe_streams(const float *src, uint64_t stride, uint64_t n, float *dst, float inv_n)
-{
-    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * kProbeTile;
-    const uint32_t cnt = static_cast<uint32_t>(n - t0 < kProbeTile ? n - t0 : kProbeTile) >> 2;
-    const float *sp[NW];
-#pragma unroll
-    for (int g = 0; g < NW; ++g) sp[g] = src + static_cast<uint64_t>(g) * stride + t0;
-    for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) {
-        const v4f avg = nway_mean_fixed<NW, true, v4f>(sp, i, inv_n);
-        st<true>(reinterpret_cast<v4f *>(dst + t0) + i, avg);
-    }
-}
-
 int check_launch(const char *what)
 {
     const hipError_t e = hipGetLastError();
@@ -838,8 +809,16 @@ void fused_launch_u(int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s, 
                     uint32_t tb, int nw, float inv_n, float lr, float mu, int pace, float *merged_out,
                     uint64_t base_off)
 {
+    // grid.x == 0 asks for the kernel to be looked up in the runtime, not launched
 #define MGWFBP_LAUNCH(UU, DD)                                                                  \
-    k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, cap_lds, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off)
+    do {                                                                                       \
+        if (grid.x == 0) {                                                                     \
+            hipFuncAttributes fa;                                                              \
+            (void)hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&k_fused<NW, UU, STEP, NT, DD>)); \
+        } else {                                                                               \
+            k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, cap_lds, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); \
+        }                                                                                      \
+    } while (0)
     if constexpr (NW > 0 && NT) {
         if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
@@ -959,7 +938,7 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const uint64_t base_off = sc.base_off;
     if (sc.n_tiles == 0) return MGWFBP_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(sc.n_tiles);
+    const dim3 grid(sc.resolve_only ? 0u : sc.n_tiles);
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const bool nt = pl.opt.nontemporal != 0;
     const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));  // float4 per lane per worker
@@ -1093,34 +1072,6 @@ int launch_spin(double ms, void *stream, uint64_t *publish_clock) { return spin(
 int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream)
 {
     return spin(deadline_ms, clock, 1, stream);
-}
-
-int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream)
-{
-    if (n == 0) return MGWFBP_OK;
-    const dim3 grid(static_cast<uint32_t>((n + kProbeTile - 1) / kProbeTile));
-    k_probe_copy<<<grid, kBlock, 0, static_cast<hipStream_t>(stream)>>>(src, dst, n);
-    return check_launch("probe copy launch");
-}
-
-int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
-                         float *dst, void *stream)
-{
-    if (n == 0) return MGWFBP_OK;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(static_cast<uint32_t>((n + kProbeTile - 1) / kProbeTile));
-    const float inv_n = 1.0f / static_cast<float>(n_streams);
-    switch (n_streams) {
-    case 1: k_probe_streams<1><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
-    case 2: k_probe_streams<2><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
-    case 4: k_probe_streams<4><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
-    case 8: k_probe_streams<8><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
-    case 16: k_probe_streams<16><<<grid, kBlock, 0, s>>>(src, stride, n, dst, inv_n); break;
-    default:
-        set_error("probe_streams: n_streams must be 1, 2, 4, 8 or 16");
-        return MGWFBP_EINVAL;
-    }
-    return check_launch("probe streams launch");
 }
 
 }  // namespace mgwfbp

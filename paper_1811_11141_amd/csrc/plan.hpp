@@ -117,6 +117,7 @@ struct mgwfbp_plan_s {
     int n_cus = 256;  // compute units of the device the plan is bound on (MI355X until bound)
     uint32_t lds_per_cu = 160u * 1024u;  // LDS bytes per compute unit of that device
     uint64_t binding_generation = 0;  // bumped whenever the device tables are released or replaced
+    std::vector<struct mgwfbp_iteration_s *> iterations;  // graphs captured from this plan and still alive
     // two words at the end of d_blob: device clock at the start and at the end of an iteration
     uint64_t *d_clock = nullptr;
     mgwfbp::DeviceTables dt;
@@ -157,6 +158,12 @@ void finish_plan(mgwfbp_plan_t &pl);
 // api.cpp
 int run_scope(mgwfbp_plan_t *pl, int32_t group, bool step, float lr, float mu, void *ws,
               size_t bytes, void *stream);
+// Makes the runtime look up the kernel run_scope would launch for the fused form of `group`,
+// without launching it.
+int resolve_scope_kernel(mgwfbp_plan_t *pl, int32_t group, bool step);
+
+// executor.cpp
+void detach_iterations(mgwfbp_plan_t *pl);
 
 // noalloc.hip: resolves the device address of the library's static workspace on the current
 // device (once per device; mgwfbp_bind calls it so that later calls need no runtime query)
@@ -194,6 +201,7 @@ struct LaunchScope {
     uint32_t tile_elems;  // length of the full tiles in this scope's list
     int pace;                // >= 0: use this pause instead of the rule
     uint32_t occupancy_lds;  // unused dynamic LDS bytes, to cap the workgroups per CU (0 = no cap)
+    bool resolve_only;       // look the kernel up in the runtime instead of launching it
 };
 int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, float lr, float mu,
                  void *stream, float *merged_out = nullptr);
@@ -208,8 +216,5 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
 int launch_spin(double ms, void *stream, uint64_t *publish_clock = nullptr);
 int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream);
 int wall_clock_khz();  // ticks per millisecond of the device clock the stand-ins read
-int launch_probe_copy(const float *src, float *dst, uint64_t n, void *stream);
-int launch_probe_streams(const float *src, int32_t n_streams, uint64_t stride, uint64_t n,
-                         float *dst, void *stream);
 
 }  // namespace mgwfbp

@@ -11,6 +11,5 @@ int launch_unpack(const mgwfbp_plan_t &, const LaunchScope &, const float *, boo
 int launch_spin(double, void *, uint64_t *) { return MGWFBP_EHIP; }
 int launch_spin_until(double, uint64_t *, void *) { return MGWFBP_EHIP; }
 int wall_clock_khz() { return 100000; }
-int launch_probe_copy(const float *, float *, uint64_t, void *) { return MGWFBP_EHIP; }
-int launch_probe_streams(const float *, int32_t, uint64_t, uint64_t, float *, void *) { return MGWFBP_EHIP; }
+int prepare_static_workspace() { return MGWFBP_EHIP; }
 }  // namespace mgwfbp

@@ -850,6 +850,35 @@ def test_tune_argument_errors(mg):
         assert_same(out[l].cpu().numpy(), exp[l], f"layer {l}")
 
 
+# ---- the benchmark's probes ------------------------------------------------------------------
+
+def test_bandwidth_probes_do_what_their_header_says(mg):
+    """mgwfbp_probe.h: copy, fill, read (writes nothing) and the N-stream mean, on a size with a
+    ragged last workgroup."""
+    n = 4 * (128 * 37 + 5)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    src = torch.empty(8 * n, device="cuda").normal_(0, 1e-2, generator=gen)
+    dst = torch.full((n + 64,), float("nan"), device="cuda")
+    mg.mgwfbp_probe_copy(src, dst, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(dst[:n].cpu().numpy()), bits(src[:n].cpu().numpy())) and bool(torch.isnan(dst[n:]).all())
+    mg.mgwfbp_probe_fill(dst, 2.5, n)
+    torch.cuda.synchronize()
+    assert bool((dst[:n] == 2.5).all()) and bool(torch.isnan(dst[n:]).all())
+    sink = torch.full((64,), 7.0, device="cuda")
+    mg.mgwfbp_probe_read(src, 8 * n, sink)
+    torch.cuda.synchronize()
+    assert bool((sink == 7.0).all())
+    mg.mgwfbp_probe_streams(src, 8, n, n, dst)
+    torch.cuda.synchronize()
+    host = src.cpu().numpy()
+    assert_same(dst[:n].cpu().numpy(), od.reduce([host[g * n:(g + 1) * n].copy() for g in range(8)]), "probe_streams")
+    with pytest.raises(mg.MgwfbpError):
+        mg.mgwfbp_probe_copy(src[1:], dst, 4)                # not 16-byte aligned
+    with pytest.raises(mg.MgwfbpError):
+        mg.mgwfbp_probe_streams(src, 3, n, n, dst)           # 3 streams: not offered
+
+
 # ---- capture into a HIP graph ----------------------------------------------------------------
 
 @pytest.mark.parametrize("update", [False, True])

@@ -75,6 +75,49 @@ def test_iteration_results_and_timeline(mg, seed, update):
             assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32))
 
 
+@pytest.mark.parametrize("n_streams,update", [(2, False), (3, True), (8, False)])
+def test_iteration_over_several_communication_streams(mg, n_streams, update):
+    """Groups enqueued round-robin over several communication streams: the values are the
+    oracle's whatever the number of streams, every group still waits for its own gradients
+    (Condition 2), and the iteration ends when the last group has (Eq. 8).  The serial channel of
+    Eq. 7 is what this mode gives up, so group k is not required to wait for group k-1."""
+    seed = 3
+    w = wl.tiny_workload(seed, L=12)
+    tb = w.tb_ms * 0.2
+    pl = mg.mgwfbp_plan(w.p, tb, 0.0, 0.05, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    groups = pl.groups()
+    assert len(groups) >= 3
+    grads = wl.make_gradients(w, seed, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    wt, vt = wl.make_weights(w, seed, "cuda")
+    g_np, w_np, v_np = [to_np(r) for r in grads], to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    s_comp = torch.cuda.Stream()
+    comm = [torch.cuda.Stream() for _ in range(n_streams)]
+    torch.cuda.synchronize()
+    tl = pl.run_iteration(s_comp, comm, update=update, lr=0.1, momentum=0.9)
+    exp = od.merged_gradient_path(g_np, groups, w_np if update else None, v_np if update else None, lr=0.1, mu=0.9)
+    for l in range(w.L):
+        assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), l
+        if update:
+            assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32))
+            assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32))
+    ready, gs, gf = tl["group_ready_ms"], tl["group_start_ms"], tl["group_finish_ms"]
+    for k in range(len(groups)):
+        assert gs[k] >= ready[k] - 0.02 and gf[k] >= gs[k]
+        if k >= n_streams:                                    # same stream: still in order
+            assert gs[k] >= gf[k - n_streams] - 0.02
+    assert tl["t_iter_ms"] >= gf.max() - 1e-6
+    # argument errors: no stream, the same stream twice, too many
+    with pytest.raises(mg.MgwfbpError) as ei:
+        pl.run_iteration(s_comp, [])
+    assert ei.value.code == mg.EINVAL
+    with pytest.raises(mg.MgwfbpError):
+        pl.run_iteration(s_comp, [comm[0], comm[0]])
+    with pytest.raises(mg.MgwfbpError):
+        pl.run_iteration(s_comp, [torch.cuda.Stream() for _ in range(9)])
+
+
 def test_iteration_needs_binding(mg):
     w = wl.custom_workload([100, 200], 2)
     pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, 0.5, 1e-6, 2, mg.MODE_WFBP)
@@ -172,3 +215,16 @@ def test_iteration_graph_argument_errors(mg):
     assert it2.replay(s1) >= 0.095
     pl.destroy()                      # takes its graphs with it
     assert not it2._h
+    # through the C ABI alone, destroying the plan first leaves the iteration handle valid but stale
+    raw = mg.raw()
+    import ctypes as C
+    pl2 = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, 0.5, 1e-6, 2, mg.MODE_WFBP)
+    pl2.bind(grads, [torch.empty_like(t) for t in grads[0]])
+    it3 = pl2.capture_iteration(s1, s2, tb_ms=[0.05, 0.05])
+    handle, it3._h = it3._h, C.c_void_p(0)            # take the handle away from the wrapper
+    pl2._graphs = []
+    pl2.destroy()
+    t = C.c_double()
+    assert raw.mgwfbp_iteration_replay(handle, C.c_void_p(int(s1.cuda_stream)), C.byref(t)) == mg.ESTATE
+    assert "destroyed" in mg.last_error()
+    raw.mgwfbp_iteration_destroy(handle)

@@ -25,12 +25,22 @@ def oracle_args(w, a=None, b=None, tf=0.0):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "mgwfbp.h")).read()
-    declared = set(re.findall(r"\b(mgwfbp_[a-z0-9_]+)\s*\(", hdr))
-    assert declared == set(mg.EXPORTS)
+    """Every function any header under include/ declares is exported by the built library, and
+    the binding lists exactly those names (the method's in mgwfbp.h, the benchmark's probes in
+    mgwfbp_probe.h)."""
+    import glob
     lib = C.CDLL(mg.LIB_PATH)
-    for name in declared:
-        assert hasattr(lib, name), name
+    seen = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        hdr = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)      # declarations, not prose
+        declared = set(re.findall(r"\b(mgwfbp_[a-z0-9_]+)\s*\(", hdr))
+        assert declared, path
+        want = mg.PROBE_EXPORTS if path.endswith("mgwfbp_probe.h") else mg.EXPORTS
+        assert declared == set(want), (path, declared ^ set(want))
+        for name in declared:
+            assert hasattr(lib, name), name
+        seen |= declared
+    assert seen == set(mg.EXPORTS) | set(mg.PROBE_EXPORTS)
 
 
 def test_optimal_equals_brute_force_tiny_nets():
