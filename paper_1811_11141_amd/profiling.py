@@ -181,9 +181,9 @@ def _traffic_summary(wl_tag: str, steps: int) -> dict:
     _, desc, n, p = WORKLOADS[wl_tag]
     fetch, write = _counter_table(wl_tag, "FETCH_SIZE"), _counter_table(wl_tag, "WRITE_SIZE")
 
-    def pick(pattern):          # the launch with the largest grid among the kernels that match
-        keys = [k for k in fetch if re.search(pattern, k[0]) and k in write]
-        return max(keys, key=lambda k: k[1]) if keys else None
+    def pick(pattern):          # whole-plan launches: the most frequent of the large grids that match
+        keys = [k for k in fetch if re.search(pattern, k[0]) and k in write and k[1] >= 128 * 2048]
+        return max(keys, key=lambda k: (int(fetch[k]["Dispatches"]), k[1])) if keys else None
 
     cal = pick(r"k_probe_copy")
     if cal is None:
