@@ -25,7 +25,8 @@ materialised kernels one by one) and through plain streaming probes.  With --oth
 for the default workload) the other gradient sets the paper's evaluation names -- VGG-16 at
 N = 16 and N = 8 and at three start-up costs, GoogLeNet, AlexNet -- are measured too, each in a
 child process of its own that is started before this process touches the GPU, and reported under
-`extra.<set>`.
+`extra.<set>` (`resnet50_n12` is the default set with 12 workers, a count the kernels have no
+unrolled worker loop for).
 """
 from __future__ import annotations
 
@@ -95,6 +96,8 @@ OTHER_SETS = (
     ("googlenet_n8", ["--workload", "googlenet", "--also",
                       "step,per_group,per_group_2streams,pack,unpack,unpack_update,unpack_update_without_out"], 200),
     ("alexnet_n8", ["--workload", "alexnet", "--also", "step"], 100),
+    # a worker count that is not a power of two: the worker loop of the kernels is a run-time loop
+    ("resnet50_n12", ["--workload", "resnet50", "--n-workers", "12", "--also", "step"], 100),
 )
 
 

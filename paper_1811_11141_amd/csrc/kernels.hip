@@ -12,7 +12,7 @@
 // cores to do.  One workgroup of 128 lanes (2 wave64) owns one tile.  Full aligned tiles, the
 // bulk of the bytes, run fast_tile(): 128-bit streaming loads and stores written out as
 // instructions, one load in flight per wave at full occupancy, stores after all loads.  The
-// rest (ragged tails, misaligned tensors, gather tiles of many tiny layers, run-time N) runs
+// rest (ragged tails, misaligned tensors, gather tiles of many tiny layers) runs
 // compiler-scheduled loops that issue the N loads of an element before the first add.
 // Arithmetic order is fixed (worker 0 first, one rounding per operation; the file is compiled
 // with -ffp-contract=off) so results are reproducible bit for bit.
@@ -323,9 +323,14 @@ __device__ __forceinline__ void pace_wave(int pace)
 #define MGWFBP_STEP_BATCH 4
 #endif
 
+//
+// NW = 0: the number of workers `nw` is only known at run time.  The walk is the same with a
+// loop over the workers that is not unrolled (worker 0 is peeled off: it initialises the
+// accumulators); short launches keep the U pieces of one worker in flight instead of a ring
+// across workers.
 template <int NW, int U, bool STEP, int D, bool SCALE, class SrcFn>
 __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, float *vp,
-                                          float inv_n, float lr, float mu, int pace)
+                                          float inv_n, float lr, float mu, int pace, int nw = NW)
 {
     // Lane offset of piece 0 (+BIAS); piece u sits u KiB further on, which the load and store
     // instructions add as their immediate offset (13 bits, signed: -4096 .. 4095), so one
@@ -337,7 +342,60 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
 #define MGWFBP_OFF(u) (((u) % 8) * 1024 - BIAS)
 #define MGWFBP_HI(u) (((u) / 8) * 8192)
     v4f res[U];
-    if constexpr (D == 1) {
+    if constexpr (NW == 0 && D == 1) {
+        {
+            const char *sb = scalar_ptr(src(0));
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                v4f x;
+                if constexpr (u == 0) x = ld_stream<MGWFBP_OFF(u)>(sb, vo);
+                else x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u - 1]);
+                wait_all_loads(x);
+                res[u] = x;
+                pace_wave(pace);
+            });
+        }
+#pragma unroll 1
+        for (int g = 1; g < nw; ++g) {
+            const char *sb = scalar_ptr(src(g));
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                v4f x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
+                wait_all_loads(x);
+                res[u] = res[u] + x;
+                pace_wave(pace);
+            });
+        }
+    } else if constexpr (NW == 0) {
+        // latency-bound launches: the U pieces of a worker go out together
+        {
+            const char *sb = scalar_ptr(src(0));
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                res[u] = ld_stream<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo);
+            });
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                wait_loads<U - 1 - u>(res[u]);
+            });
+        }
+#pragma unroll 1
+        for (int g = 1; g < nw; ++g) {
+            const char *sb = scalar_ptr(src(g));
+            v4f x[U];
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                // ordered after the previous worker's last add, so that no more than U loaded
+                // values are live
+                x[u] = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[U - 1]);
+            });
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                wait_loads<U - 1 - u>(x[u]);
+                res[u] = res[u] + x[u];
+            });
+        }
+    } else if constexpr (D == 1) {
         static_for<NW>([&](auto gc) {
             constexpr int g = decltype(gc)::value;
             const char *sb = scalar_ptr(src(g));
@@ -420,7 +478,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
 }
 
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
-// misaligned tensors, gather tiles, run-time N) takes the general path below.
+// misaligned tensors, gather tiles) takes the general path below.
 template <int NW, int U, bool STEP, bool NT, int D>
 __global__ void __launch_bounds__(kBlock)
 k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace,
@@ -449,12 +507,12 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
         float *vp = STEP ? table_load(dt.v + tl.seg) + tl.start : nullptr;
         const uint32_t n = tl.n;
         const bool vec = (flags & need) == need && merged_al;
-        if constexpr (NW > 0 && U > 0) {
+        if constexpr (U > 0) {
             if (vec && n == U * kBlock * 4) {
                 const uint64_t start = tl.start;
                 fast_tile<NW, U, STEP, D, true>(
                     [sp_tbl, start](int g) { return table_load(sp_tbl + g) + start; }, outp, wp, vp,
-                    inv_n, lr, mu, pace);
+                    inv_n, lr, mu, pace, nw);
                 return;
             }
         }
@@ -524,11 +582,11 @@ k_reduce(float *ws, uint64_t epad, uint64_t elems, uint32_t tile, int nw, float 
     const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * tile;
     const uint32_t n = static_cast<uint32_t>(elems - t0 < tile ? elems - t0 : tile);
     float *outp = ws + static_cast<uint64_t>(nw) * epad + t0;
-    if constexpr (NW > 0 && U > 0) {
+    if constexpr (U > 0) {
         if (n == U * kBlock * 4) {
             fast_tile<NW, U, false, D, true>(
                 [ws, epad, t0](int g) { return ws + static_cast<uint64_t>(g) * epad + t0; }, outp,
-                nullptr, nullptr, inv_n, 0.0f, 0.0f, pace);
+                nullptr, nullptr, inv_n, 0.0f, 0.0f, pace, nw);
             return;
         }
     }
@@ -802,7 +860,9 @@ int check_launch(const char *what)
     return MGWFBP_OK;
 }
 
-// The fast path exists for tiles of U*kBlock float4, U = 2, 4 or 8 (1024, 2048, 4096 elements).
+// The fast path exists for tiles of U*kBlock float4, U = 2, 4 or 8 (1024, 2048, 4096 elements),
+// for the worker counts 1, 2, 4, 8, 16 with the worker loop unrolled and for any other count with
+// a run-time loop (NW = 0).
 // deep = launch too small to fill the chip (latency-bound): 8 loads in flight per wave.
 template <int NW, bool STEP, bool NT>
 void fused_launch_u(int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s, const DeviceTables &dt,
@@ -819,7 +879,7 @@ void fused_launch_u(int u, bool deep, dim3 grid, size_t cap_lds, hipStream_t s, 
             k_fused<NW, UU, STEP, NT, DD><<<grid, kBlock, cap_lds, s>>>(dt, tb, nw, inv_n, lr, mu, pace, merged_out, base_off); \
         }                                                                                      \
     } while (0)
-    if constexpr (NW > 0 && NT) {
+    if constexpr (NT) {
         if (u == 2) { if (deep) MGWFBP_LAUNCH(2, 8); else MGWFBP_LAUNCH(2, 1); return; }
         if (u == 4) { if (deep) MGWFBP_LAUNCH(4, 8); else MGWFBP_LAUNCH(4, 1); return; }
         if (u == 8) { if (deep) MGWFBP_LAUNCH(8, 8); else MGWFBP_LAUNCH(8, 1); return; }
@@ -870,7 +930,7 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
         k_reduce<NW, false, 0, 1><<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
         return;
     }
-    if constexpr (NW > 0) {
+    {
         // longer tiles, chosen by launch_reduce
 #define MGWFBP_REDUCE_LONG(UU)                                                                  \
     if (u == UU && !deep) {                                                                      \
@@ -883,7 +943,7 @@ void reduce_launch(bool nt, int u, bool deep, dim3 grid, hipStream_t s, float *w
         MGWFBP_REDUCE_LONG(16)
 #undef MGWFBP_REDUCE_LONG
     }
-    with_shape(NW > 0, u, deep, [&](auto uc, auto dc) {
+    with_shape(true, u, deep, [&](auto uc, auto dc) {
         k_reduce<NW, true, decltype(uc)::value, decltype(dc)::value>
             <<<grid, kBlock, 0, s>>>(ws, epad, elems, tile, nw, inv_n, pace);
     });
