@@ -1014,6 +1014,7 @@ def test_full_size_materialised(mg):
     ("alexnet", None, 0.5, None, False),
     ("vgg16", None, 0.1, None, False), ("vgg16", None, 0.5, None, False), ("vgg16", None, 2.0, None, False),
     ("vgg16", 8, 0.5, None, False),
+    ("resnet50", 12, 0.5, None, False),        # a worker count with a run-time worker loop
     ("resnet50", None, 0.5, None, True),       # one launch per group, as Algorithm 2 would issue them
     ("googlenet", None, 0.5, None, True),
     ("googlenet", None, 0.5, 1024, False), ("googlenet", None, 0.5, 2048, False),
