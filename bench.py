@@ -402,6 +402,11 @@ def main():
                                                                    n_probe // N // 4 * 4, bufs[(i + 1) % nb], stream),
                  4 * (N + 1) * (n_probe // N // 4 * 4)),
             )
+            # the same copy at the size of one worker's set (what unpack moves): short launches pay
+            # their ramp-up and drain
+            n_small = (P + 3) // 4 * 4
+            probes += (("probe_copy_one_set", lambda i: mg.mgwfbp_probe_copy(bufs[i % nb], bufs[(i + 1) % nb], n_small, stream),
+                        8 * n_small),)
             for nm, fn, nbytes in probes:
                 _, kk = timed(fn, k2, w2)
                 gb = nbytes / (kk["avg_ms"] * 1e-3) / 1e9
