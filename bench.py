@@ -89,7 +89,7 @@ def parse():
 
 # the other gradient sets of the paper's evaluation, each measured in a child process
 OTHER_SETS = (
-    ("vgg16_n16", ["--workload", "vgg16", "--also", "step"], 40),
+    ("vgg16_n16", ["--workload", "vgg16", "--also", "step,pack,unpack,unpack_update,unpack_update_without_out"], 40),
     ("vgg16_n8", ["--workload", "vgg16", "--n-workers", "8", "--also", "step"], 60),
     ("vgg16_n16_a0.1", ["--workload", "vgg16", "--a-ms", "0.1"], 30),
     ("vgg16_n16_a2", ["--workload", "vgg16", "--a-ms", "2.0"], 30),

@@ -79,9 +79,12 @@ enum {
                                    that length                                                     */
     MGWFBP_OPT_PAD_ELEMS = 6,   /* layout of the merged buffers.  0 (default): the layers of a group
                                    follow each other without padding, as the cost model counts them
-                                   (Condition 3).  4: every layer starts on a 16-byte boundary; the
-                                   1-3 padding elements after a layer are written as zeros by pack and
-                                   mgwfbp_pack_reduce and skipped by unpack.  offset_in_group,
+                                   (Condition 3).  4, 8, 16 or 32: every layer starts on a multiple of
+                                   that many elements (4: a 16-byte boundary, so that every copy is
+                                   128 bits wide whatever the layer lengths; 32: a 128-byte boundary,
+                                   so that both sides of every copy are aligned to whole memory
+                                   lines); the padding elements after a layer are written as zeros by
+                                   pack and mgwfbp_pack_reduce and skipped by unpack.  offset_in_group,
                                    group_elems, workspace and merged-buffer sizes follow the layout;
                                    the predicted times do not change                               */
     MGWFBP_OPT_UPDATE_WGS_PER_CU = 7 /* workgroups of the update kernel (mgwfbp_step without

@@ -519,7 +519,8 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
             pl->opt.pace = static_cast<int>(value);
             return MGWFBP_OK;
         case MGWFBP_OPT_PAD_ELEMS:
-            if (value != 0 && value != 4) return fail(MGWFBP_EINVAL, "pad_elems must be 0 or 4");
+            if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32)
+                return fail(MGWFBP_EINVAL, "pad_elems must be 0, 4, 8, 16 or 32");
             pl->opt.pad_elems = static_cast<uint32_t>(value);
             finish_plan(*pl);  // offsets and group sizes follow the layout
             return MGWFBP_OK;

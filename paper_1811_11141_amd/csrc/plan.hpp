@@ -61,7 +61,7 @@ struct Options {
     uint32_t small_elems = 64;
     int nontemporal = 1;
     int pace = -1;  // -1: chosen per launch from its size and N
-    uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4: every layer starts 16-byte aligned
+    uint32_t pad_elems = 0;  // 0: merged buffers hold exactly sum p; 4 .. 32: every layer starts on a multiple
     int long_tiles = -1;  // tile length of the whole-plan fused reduce pass: -1 by rule, 0 = tile_elems,
                           // 1 = 8192, or 5120 / 6144 / 7168 / 8192 elements
     int update_wgs_per_cu = -1;  // update kernel: -1 by rule, 0 uncapped, 8..11 forced

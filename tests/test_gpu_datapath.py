@@ -717,9 +717,10 @@ def padded_pack(rep, p, layers, pad=4):
     return buf
 
 
-@pytest.mark.parametrize("seed,tile,small,n_workers", [
-    (0, 1024, 512, 4), (1, 2048, 0, 3), (2, 4096, 512, 8), (3, 4096, 1026, 2), (4, 8192, 2048, 16)])
-def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
+@pytest.mark.parametrize("seed,tile,small,n_workers,pad", [
+    (0, 1024, 512, 4, 4), (1, 2048, 0, 3, 4), (2, 4096, 512, 8, 4), (3, 4096, 1026, 2, 4), (4, 8192, 2048, 16, 4),
+    (5, 1024, 512, 4, 32), (6, 4096, 64, 8, 32), (7, 2048, 2048, 3, 16), (8, 4096, 0, 2, 8)])
+def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers, pad):
     rng = np.random.default_rng(300 + seed)
     L = int(rng.integers(3, 30))
     sizes = [int(rng.integers(1, 3000)) if rng.random() < 0.7 else int(rng.integers(3000, 60000)) for _ in range(L)]
@@ -727,7 +728,7 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
     merged = random_merged(rng, L)
     groups = groups0(L, merged)
     pl = make_plan(mg, w, merged, tile=tile, small=small)
-    pl.set_option(mg.OPT_PAD_ELEMS, 4)
+    pl.set_option(mg.OPT_PAD_ELEMS, pad)
     inf = pl.info()
     grads = wl.make_gradients(w, seed, "cuda")
     g_np = [to_np(r) for r in grads]
@@ -738,7 +739,7 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
     exp = od.merged_gradient_path(g_np, groups)
     scopes = [(-1, [l for g in groups for l in g])] + [(k, g) for k, g in enumerate(groups)]
     for scope, layers in scopes:
-        pos, E = padded_positions(w.p, layers)
+        pos, E = padded_positions(w.p, layers, pad)
         assert E == (int(inf["group_elems"].sum()) if scope < 0 else int(inf["group_elems"][scope]))
         # pack: N padded buffers, zeros in the padding
         ws = alloc_ws(pl, scope)
@@ -748,7 +749,7 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
         torch.cuda.synchronize()
         host = ws.cpu().numpy()
         for g in range(n_workers):
-            assert np.array_equal(bits(host[g * epad:g * epad + E]), bits(padded_pack(g_np[g], w.p, layers))), (scope, g)
+            assert np.array_equal(bits(host[g * epad:g * epad + E]), bits(padded_pack(g_np[g], w.p, layers, pad))), (scope, g)
         # reduce + unpack through the workspace
         for t in out:
             t.fill_(float("nan"))
@@ -756,7 +757,7 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
         pl.unpack(ws, group=scope)
         torch.cuda.synchronize()
         red = ws[n_workers * epad:n_workers * epad + E].cpu().numpy()
-        assert_same(red, padded_pack(exp, w.p, layers), f"reduced buffer scope {scope}")
+        assert_same(red, padded_pack(exp, w.p, layers, pad), f"reduced buffer scope {scope}")
         for l in layers:
             assert_same(out[l].cpu().numpy(), exp[l], f"unpack scope {scope} layer {l}")
         # the two halves
@@ -764,7 +765,7 @@ def test_padded_layout_all_entry_points(mg, seed, tile, small, n_workers):
         pl.pack_reduce(mb, group=scope)
         torch.cuda.synchronize()
         hb = mb.cpu().numpy()
-        assert_same(hb[:E], padded_pack(exp, w.p, layers), f"pack_reduce scope {scope}")
+        assert_same(hb[:E], padded_pack(exp, w.p, layers, pad), f"pack_reduce scope {scope}")
         assert np.isnan(hb[E:]).all()
         for t in out:
             t.fill_(float("nan"))

@@ -75,6 +75,7 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
                 assert n == tlen or start + n == sn, "only the last piece of a segment is ragged"
                 assert tpad == (plen(sn) - sn if start + n == sn else 0), "the last piece owns the layer's padding"
                 lo = soff + start
+                is_full = n == tlen              # before the padding it owns is counted in
                 n += tpad
             else:
                 members = exp[first:first + nseg]
@@ -84,13 +85,14 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
                 assert n <= max(min(tile, 1024), small_eff)
                 grp = members[0][3]
                 lo = start
+                is_full = False
             cover[lo:lo + n] += 1
             if which == 0:
                 # group after group; inside a group the slow tiles (gather, ragged) come first
                 assert grp >= last_group
                 if grp != last_group:
                     last_group, seen_full_in_group = grp, False
-                full = nseg == 1 and n == tlen
+                full = is_full
                 assert not (seen_full_in_group and not full), "slow tile after a full tile"
                 seen_full_in_group = seen_full_in_group or full
         assert cover.min() == 1 and cover.max() == 1, "every element in exactly one tile"
@@ -168,8 +170,8 @@ def test_longer_tile_list_is_chosen_by_launch_size():
 
 @pytest.mark.parametrize("tile,small", [(1024, 0), (1024, 512), (4096, 512), (4096, 1026), (2048, 2048)])
 def test_layout_padded(tile, small):
-    """MGWFBP_OPT_PAD_ELEMS = 4: every layer starts on a multiple of four elements, the tiles
-    cover the padded merged order exactly once, the predicted times do not move."""
+    """MGWFBP_OPT_PAD_ELEMS = 4, 8, 16, 32: every layer starts on a multiple of that many
+    elements, the tiles cover the padded merged order exactly once, the predicted times do not move."""
     for seed in range(6):
         rng = np.random.default_rng(50 + seed)
         L = int(rng.integers(1, 30))
@@ -178,6 +180,7 @@ def test_layout_padded(tile, small):
         merged = [l for l in range(2, L + 1) if rng.random() < 0.6]
         check_layout(p, merged, tile, small, pad=4)
         check_layout(p, merged, tile, small, long_tiles=1, pad=4)
+        check_layout(p, merged, tile, small, pad=(8, 16, 32)[seed % 3])
 
 
 def test_layout_many_tiny_layers_split_gather_tiles():
