@@ -112,6 +112,37 @@ def test_fused_tiny_config(mg, seed):
             assert_same(vt[l].cpu().numpy(), v_np[l], f"v layer {l} step {step}")
 
 
+def test_fused_tiny_config_hundred_seeds(mg):
+    """Config 1 over 100 more seeds at the library's default options: the optimal plan's
+    predicted time equals brute force over all 128 partitions, and the fused pass and one
+    SGD-momentum step (lr 0.1, momentum 0.9) equal the oracle bit for bit."""
+    for seed in range(100, 200):
+        w = wl.tiny_workload(seed)
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+        t_best, _ = op.brute_force(w.p.tolist(), w.tb_ms.tolist(), 0.0, w.a_ms, w.b_ms_per_byte)
+        assert pl.info()["t_iter_ms"] == t_best, seed
+        groups = pl.groups()
+        grads = wl.make_gradients(w, seed, "cuda")
+        out = [torch.full_like(t, float("nan")) for t in grads[0]]
+        wt, vt = wl.make_weights(w, seed, "cuda")
+        for t in vt:
+            t.normal_(0, 1e-3)
+        w_np, v_np = to_np(wt), to_np(vt)
+        pl.bind(grads, out, wt, vt)
+        pl.pack_reduce_unpack()
+        torch.cuda.synchronize()
+        g_np = [to_np(r) for r in grads]
+        exp = od.merged_gradient_path(g_np, groups, w_np, v_np, lr=0.1, mu=0.9)
+        for l in range(w.L):
+            assert_same(out[l].cpu().numpy(), exp[l], f"seed {seed} avg layer {l}")
+        pl.step(0.1, 0.9)
+        torch.cuda.synchronize()
+        for l in range(w.L):
+            assert_same(wt[l].cpu().numpy(), w_np[l], f"seed {seed} w layer {l}")
+            assert_same(vt[l].cpu().numpy(), v_np[l], f"seed {seed} v layer {l}")
+        pl.destroy()
+
+
 @pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 7, 8, 16, 19])
 def test_fused_worker_counts(mg, n_workers):
     """Fixed-N kernels (1, 2, 4, 8, 16) and the run-time-N path; N = 3, 5, 7 have inexact 1/N."""
