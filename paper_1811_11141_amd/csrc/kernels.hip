@@ -9,11 +9,13 @@
 //   k_unpack  merged buffer back to per-layer tensors (+ update of Eq. 1-2 with momentum).
 //
 // The path is bound by HBM bandwidth (0.2-0.3 flop per byte); there is nothing for the matrix
-// cores to do.  One workgroup of 128 lanes (2 wave64) owns one tile.  Full aligned tiles, the
-// bulk of the bytes, run fast_tile(): 128-bit streaming loads and stores written out as
-// instructions, one load in flight per wave at full occupancy, stores after all loads.  The
-// rest (ragged tails, misaligned tensors, gather tiles of many tiny layers) runs
-// compiler-scheduled loops that issue the N loads of an element before the first add.
+// cores to do.  In the reductions (k_fused, k_reduce) one workgroup of 128 lanes (2 wave64) owns
+// one tile.  Full aligned tiles, the bulk of the bytes, run fast_tile(): 128-bit streaming loads
+// and stores written out as instructions, one load in flight per wave at full occupancy,
+// stores after all loads.  The rest (ragged tails, misaligned tensors, gather tiles of many
+// tiny layers) runs compiler-scheduled loops that issue the N loads of an element before the
+// first add.  The copy-like steps (k_pack, k_unpack) want the opposite shape: one workgroup per
+// 512-element piece of a tile, one 16-byte access per lane (see "Copy-like steps").
 // Arithmetic order is fixed (worker 0 first, one rounding per operation; the file is compiled
 // with -ffp-contract=off) so results are reproducible bit for bit.
 #include <hip/hip_runtime.h>
