@@ -44,18 +44,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 EVERY = 8              # consecutive steps bracketed by one HIP-event pair
 
-VARIANTS = ("fused", "step", "step_without_out", "materialised", "per_group", "per_group_2streams", "pack",
+VARIANTS = ("fused", "step", "step_without_out", "materialised", "per_group", "per_group_2streams",
+            "per_group_gated", "gated_all_arrived", "pack",
             "reduce", "unpack", "pack_reduce", "unpack_only", "unpack_update", "unpack_update_without_out")
 
 
 def units(variant: str, N: int) -> int:
     """Algorithmic (for the materialised forms: actual) traffic in units of 4P bytes."""
     return {"fused": N + 1, "per_group": N + 1, "per_group_2streams": N + 1, "materialised": N + 1,
+            "per_group_gated": N + 1, "gated_all_arrived": N + 1,
             "step": N + 5, "step_without_out": N + 4, "pack": 2 * N, "reduce": N + 1, "unpack": 2,
             "pack_reduce": N + 1, "unpack_only": 2, "unpack_update": 6, "unpack_update_without_out": 5}[variant]
 
 
 KERNEL_OF = {"fused": "k_fused", "per_group": "k_fused", "per_group_2streams": "k_fused", "step": "k_fused (update)",
+             "per_group_gated": "k_fused_gated", "gated_all_arrived": "k_fused_gated",
              "step_without_out": "k_fused (update)", "materialised": "k_pack+k_reduce+k_unpack", "pack": "k_pack",
              "reduce": "k_reduce", "unpack": "k_unpack", "pack_reduce": "k_fused (merged out)",
              "unpack_only": "k_unpack", "unpack_update": "k_unpack (update)",
@@ -94,7 +97,7 @@ OTHER_SETS = (
     ("vgg16_n16_a0.1", ["--workload", "vgg16", "--a-ms", "0.1"], 30),
     ("vgg16_n16_a2", ["--workload", "vgg16", "--a-ms", "2.0"], 30),
     ("googlenet_n8", ["--workload", "googlenet", "--also",
-                      "step,per_group,per_group_2streams,pack,unpack,unpack_update,unpack_update_without_out"], 200),
+                      "step,per_group,per_group_2streams,per_group_gated,pack,unpack,unpack_update,unpack_update_without_out"], 200),
     ("alexnet_n8", ["--workload", "alexnet", "--also", "step"], 100),
     # a worker count that is not a power of two: the worker loop of the kernels is a run-time loop
     ("resnet50_n12", ["--workload", "resnet50", "--n-workers", "12", "--also", "step"], 100),
@@ -204,8 +207,17 @@ def main():
     info = sets[0]["plan"].info()
     n_groups = info["n_groups"]
 
-    stream = torch.cuda.Stream(device=dev)
-    side = torch.cuda.Stream(device=dev)
+    # `side` signals to the gated launch on `stream`: the device must run the two side by side
+    # (streams that share one of the runtime's hardware queues do not)
+    for _ in range(8):
+        stream = torch.cuda.Stream(device=dev)
+        side = torch.cuda.Stream(device=dev)
+        if sets[0]["plan"].streams_side_by_side(side, stream):
+            break
+    else:
+        wanted -= {"per_group_gated", "gated_all_arrived"}
+    for st in sets:
+        st["arrival"] = 0
 
     def run_step(variant, i):
         st = sets[i % n_sets]
@@ -232,6 +244,23 @@ def main():
             join = torch.cuda.Event()
             join.record(side)
             stream.wait_event(join)
+        elif variant == "per_group_gated":
+            # the whole plan is ONE launch that waits, group by group, for arrival counters which
+            # a second stream bumps with one small kernel per group, back to back
+            st["arrival"] += 1
+            fork = torch.cuda.Event()
+            fork.record(stream)
+            side.wait_event(fork)
+            pl.gated_launch(st["arrival"], give_up_ms=2000.0, stream=stream)
+            for k in range(n_groups):
+                pl.gated_signal(k, st["arrival"], stream=side)
+            join = torch.cuda.Event()
+            join.record(side)
+            stream.wait_event(join)
+        elif variant == "gated_all_arrived":
+            # the same launch when every group has arrived before it starts: what the arrival-order
+            # tile list and the look at the counters cost against the plain fused launch
+            pl.gated_launch(st["arrival"], give_up_ms=2000.0, stream=stream)
         elif variant == "pack":
             pl.pack(st["ws"], stream=stream)
         elif variant == "reduce":
@@ -282,6 +311,9 @@ def main():
         fig = {"us_per_step": round(kk["avg_ms"] * 1e3, 2), "min_us": round(kk["min_ms"] * 1e3, 2),
                "bytes_per_step": nbytes, "GBps": round(gbps, 1), "frac_of_peak": round(gbps / HBM_PEAK_GBS, 4),
                "kernel": KERNEL_OF[variant], "traffic": traffic.get(variant)}
+        if variant in ("per_group_gated", "gated_all_arrived"):
+            fig["groups"] = n_groups
+            fig["gave_up"] = any(st["plan"].gated_gave_up() for st in sets)
         if variant == "materialised":   # the chain really moves 3N + 3 units
             fig["GBps_actual_traffic"] = round(4 * (3 * N + 3) * P / (kk["avg_ms"] * 1e-3) / 1e9, 1)
         return fig
@@ -334,7 +366,7 @@ def main():
     k2, w2 = max(24, args.steps // 4), max(5, args.warmup // 4)
     try:
         for variant in also:
-            if variant != args.variant:
+            if variant != args.variant and variant in wanted:
                 extra[variant] = side_figure(variant, k2, w2)
     except Exception as e:
         torch.cuda.synchronize()
@@ -343,7 +375,7 @@ def main():
         # the headline line is complete without these: a failing extra is reported, not fatal
         try:
             for variant in VARIANTS:
-                if variant != args.variant and variant not in extra:
+                if variant != args.variant and variant not in extra and (variant in wanted or "gated" not in variant):
                     extra[variant] = side_figure(variant, k2, w2)
             # the launch-per-group sequence captured once per gradient set into a HIP graph
             graphs = []

@@ -87,11 +87,15 @@ enum {
                                    pack and mgwfbp_pack_reduce and skipped by unpack.  offset_in_group,
                                    group_elems, workspace and merged-buffer sizes follow the layout;
                                    the predicted times do not change                               */
-    MGWFBP_OPT_UPDATE_WGS_PER_CU = 7 /* workgroups of the update kernel (mgwfbp_step without
+    MGWFBP_OPT_UPDATE_WGS_PER_CU = 7, /* workgroups of the update kernel (mgwfbp_step without
                                    workspace) one compute unit may hold.  -1 (default): chosen per
                                    launch so that its batches of resident workgroups fill well;
                                    0: whatever the kernel's registers allow (14; 12 for N = 16);
                                    8, 9, 10, 11: that many.  Results do not depend on it            */
+    MGWFBP_OPT_GATED_WGS_PER_CU = 8 /* workgroups per compute unit in mgwfbp_gated_launch, which
+                                   stay for the whole launch: -1 (default) two fewer than a unit
+                                   holds, or 1 .. 15 (never more than that default): the rest is
+                                   room for the kernels that signal                                 */
 };
 
 /*
@@ -170,7 +174,8 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             list 0: the per-group lists (group after group); list 1: the second copy used
  *             by whole-plan launches; list 2 or 3 (when built): the whole plan in longer
  *             tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses it by default,
- *             3 if only mgwfbp_tune may select it.
+ *             3 if only mgwfbp_tune may select it; list 4: the whole plan in tiles of tile_elems,
+ *             group after group in communication order (mgwfbp_gated_launch).
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too
  *             few workgroups).
@@ -371,6 +376,61 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
                                  float momentum, void *compute_stream, void *const *comm_streams,
                                  int32_t n_comm_streams, double *group_ready_ms,
                                  double *group_start_ms, double *group_finish_ms, double *t_iter_ms);
+
+/*
+ * Algorithm 2's communication thread as ONE launch.  A kernel launch per group costs a few
+ * microseconds however little the group holds, which is the start-up term a of this
+ * "transport"; here the whole plan is a single launch whose workgroups take the tiles in
+ * arrival order (group 0 first) and, before each tile, wait until the tile's group has arrived:
+ * the plan keeps one arrival counter per group in device memory, and a tile runs once its
+ * group's counter has reached the `arrival` number of the launch (counters only grow; use 1, 2,
+ * 3, ... for successive iterations; they start at 0 after mgwfbp_bind).
+ *   mgwfbp_gated_launch   enqueues the launch on `hip_stream` (reduction into out[], or with
+ *                         update != 0 the update of w[], v[]; fused form, results as
+ *                         mgwfbp_pack_reduce_unpack / mgwfbp_step with group = -1).  It starts
+ *                         at once and waits on the device.  Every wait is bounded: a workgroup
+ *                         that has waited give_up_ms (0 < give_up_ms <= 60000) for a group sets a
+ *                         give-up word and ends, the others end at their next look at it, so the
+ *                         launch always drains; tiles not yet run are then left undone.
+ *                         Needs tile_elems at its default (4096).
+ *   mgwfbp_gated_signal   enqueues, behind the work already in `hip_stream`, a release store of
+ *                         `arrival` to the group's counter: call it on the stream that produces
+ *                         the group's gradients, after the kernel that writes the lowest layer.
+ *                         That stream must not be the one the launch is on, nor wait for it.
+ *   mgwfbp_gated_gave_up  after the launch's stream has been waited for: *gave_up = 1 if the
+ *                         last launch gave up.
+ * The launch holds two workgroups per compute unit fewer than the unit can take of this kernel
+ * (16; 14 with update != 0), or fewer still with MGWFBP_OPT_GATED_WGS_PER_CU, so that the kernels
+ * that produce gradients and bump counters find room on the chip while it waits; each workgroup
+ * walks its share of the tiles.  One gated launch per plan at a time.
+ *
+ * The signalling kernels must be able to run WHILE the launch is running.  The runtime serves its
+ * streams from a few hardware queues (four by default), and two streams that share a queue run
+ * their kernels one after the other: the signals would then sit behind the launch that waits for
+ * them, and the launch would give up.
+ *   mgwfbp_streams_side_by_side  *side_by_side = 1 if a kernel on stream_a runs while a kernel on
+ *                         stream_b is still running, 0 if not (also for stream_a == stream_b).  It
+ *                         finds out with a handshake of two tiny kernels (the waiting one ends by
+ *                         itself after 2 ms), blocks until both streams are idle, and remembers in
+ *                         the plan the pairs that passed.  The plan must be bound.  Take another
+ *                         stream when a pair fails: most pairs pass.
+ *
+ * mgwfbp_run_iteration_gated is mgwfbp_run_iteration in this form: the stand-in backward pass on
+ * `compute_stream` signals each group's arrival, `comm_stream` (a different stream) holds the one
+ * launch.  It first checks the pair as mgwfbp_streams_side_by_side(compute, comm) does and returns
+ * MGWFBP_ESTATE, with nothing run, if the pair fails.  It blocks until both streams are idle,
+ * reports the time from the start of the backward pass to the end of the launch, and returns
+ * MGWFBP_ESTATE if the launch gave up.  Like several communication streams, this form does not
+ * serialise the groups (Eq. 7's channel); it keeps Condition 2.
+ */
+int mgwfbp_gated_launch(mgwfbp_plan_t *plan, int32_t update, float lr, float momentum, uint32_t arrival,
+                        double give_up_ms, void *hip_stream);
+int mgwfbp_gated_signal(mgwfbp_plan_t *plan, int32_t group, uint32_t arrival, void *hip_stream);
+int mgwfbp_gated_gave_up(mgwfbp_plan_t *plan, int32_t *gave_up);
+int mgwfbp_streams_side_by_side(mgwfbp_plan_t *plan, void *stream_a, void *stream_b, int32_t *side_by_side);
+int mgwfbp_run_iteration_gated(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
+                               float momentum, void *compute_stream, void *comm_stream,
+                               double give_up_ms, double *t_iter_ms);
 
 /*
  * The same iteration captured once into a HIP graph and replayed: one graph launch per

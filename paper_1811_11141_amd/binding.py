@@ -21,6 +21,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
 OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES, OPT_PAD_ELEMS = 1, 2, 3, 4, 5, 6
 OPT_UPDATE_WGS_PER_CU = 7
+OPT_GATED_WGS_PER_CU = 8
 STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 
 EXPORTS = [
@@ -28,7 +29,8 @@ EXPORTS = [
     "mgwfbp_plan_set_option", "mgwfbp_plan_layout", "mgwfbp_bind", "mgwfbp_tune", "mgwfbp_workspace_bytes",
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update", "mgwfbp_pack_reduce_unpack_static",
-    "mgwfbp_run_iteration", "mgwfbp_run_iteration_streams", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
+    "mgwfbp_run_iteration", "mgwfbp_run_iteration_streams", "mgwfbp_run_iteration_gated",
+    "mgwfbp_gated_launch", "mgwfbp_gated_signal", "mgwfbp_gated_gave_up", "mgwfbp_streams_side_by_side", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
     "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
@@ -81,6 +83,11 @@ def _load() -> C.CDLL:
     lib.mgwfbp_scaling_curve.argtypes = [i32, P(u64), P(f64), f64, i32, f64, f64, f64, i32, P(i32), i32,
                                          P(f64), P(f64)]
     lib.mgwfbp_run_iteration_streams.argtypes = [vp, P(f64), i32, f32, f32, vp, P(vp), i32, P(f64), P(f64), P(f64), P(f64)]
+    lib.mgwfbp_run_iteration_gated.argtypes = [vp, P(f64), i32, f32, f32, vp, vp, f64, P(f64)]
+    lib.mgwfbp_gated_launch.argtypes = [vp, i32, f32, f32, C.c_uint32, f64, vp]
+    lib.mgwfbp_gated_signal.argtypes = [vp, i32, C.c_uint32, vp]
+    lib.mgwfbp_gated_gave_up.argtypes = [vp, P(i32)]
+    lib.mgwfbp_streams_side_by_side.argtypes = [vp, vp, vp, P(i32)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.mgwfbp_probe_fill.argtypes = [vp, f32, u64, vp]
@@ -293,6 +300,38 @@ class Plan:
             return {"t_iter_ms": t_iter.value}
         return {"group_ready_ms": ready, "group_start_ms": gs, "group_finish_ms": gf,
                 "t_iter_ms": t_iter.value}
+
+    def run_iteration_gated(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
+                            lr: float = 0.0, momentum: float = 0.0, give_up_ms: float = 2000.0) -> float:
+        """One iteration with the communication side as a single gated launch; returns t_iter in ms."""
+        tb = None if tb_ms is None else np.ascontiguousarray(tb_ms, dtype=np.float64)
+        if tb is not None and tb.shape != (self.L,):
+            raise ValueError("tb_ms must have L entries")
+        t = C.c_double()
+        _check(_lib.mgwfbp_run_iteration_gated(
+            self._h, None if tb is None else tb.ctypes.data_as(C.POINTER(C.c_double)), int(update), lr, momentum,
+            C.c_void_p(_stream(compute_stream)), C.c_void_p(_stream(comm_stream)), give_up_ms, C.byref(t)))
+        return t.value
+
+    def streams_side_by_side(self, stream_a, stream_b) -> bool:
+        """Does the device run stream_a's kernels while one of stream_b's is still running?"""
+        y = C.c_int32()
+        _check(_lib.mgwfbp_streams_side_by_side(self._h, C.c_void_p(_stream(stream_a)),
+                                                C.c_void_p(_stream(stream_b)), C.byref(y)))
+        return bool(y.value)
+
+    def gated_launch(self, arrival: int, update: bool = False, lr: float = 0.0, momentum: float = 0.0,
+                     give_up_ms: float = 2000.0, stream=None) -> None:
+        _check(_lib.mgwfbp_gated_launch(self._h, int(update), lr, momentum, arrival, give_up_ms,
+                                        C.c_void_p(_stream(stream))))
+
+    def gated_signal(self, group: int, arrival: int, stream=None) -> None:
+        _check(_lib.mgwfbp_gated_signal(self._h, group, arrival, C.c_void_p(_stream(stream))))
+
+    def gated_gave_up(self) -> bool:
+        g = C.c_int32()
+        _check(_lib.mgwfbp_gated_gave_up(self._h, C.byref(g)))
+        return bool(g.value)
 
     def capture_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
                           lr: float = 0.0, momentum: float = 0.0) -> "IterationGraph":

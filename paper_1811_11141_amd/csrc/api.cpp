@@ -86,6 +86,8 @@ void release_device(mgwfbp_plan_t *pl)
     }
     pl->d_blob = nullptr;
     pl->d_clock = nullptr;
+    pl->d_ready = pl->d_gave_up = pl->d_handshake = nullptr;
+    pl->side_by_side.clear();
     pl->dt = DeviceTables();
     pl->bound = false;
     ++pl->binding_generation;  // graphs captured against the old tables must not run again
@@ -234,7 +236,8 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     const size_t b_tile = up(pl->tiles.size() * sizeof(TileDev));
     const size_t b_src = up(src_tbl.size() * sizeof(void *));
     const size_t b_ptr = up(pl->segs.size() * sizeof(void *));
-    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr + 256;
+    const size_t b_flags = up((pl->groups.size() + 3) * sizeof(uint32_t));
+    const size_t total = b_seg + b_tile + b_src + 3 * b_ptr + 256 + b_flags;
     std::vector<char> host(total, 0);
     size_t o = 0;
     std::memcpy(host.data() + o, pl->segs.data(), pl->segs.size() * sizeof(SegDev));
@@ -246,7 +249,9 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     const size_t o_out = o; o += b_ptr;
     const size_t o_w = o; o += b_ptr;
     const size_t o_v = o; o += b_ptr;
-    const size_t o_clock = o;
+    const size_t o_clock = o; o += 256;
+    const size_t o_flags = o;
+    // [arrival counters][give-up word][two handshake words]
     if (out) std::memcpy(host.data() + o_out, out_tbl.data(), out_tbl.size() * sizeof(void *));
     if (w) {
         std::memcpy(host.data() + o_w, w_tbl.data(), w_tbl.size() * sizeof(void *));
@@ -273,11 +278,22 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     pl->dt.w = w ? reinterpret_cast<float *const *>(d + o_w) : nullptr;
     pl->dt.v = w ? reinterpret_cast<float *const *>(d + o_v) : nullptr;
     pl->d_clock = reinterpret_cast<uint64_t *>(d + o_clock);
+    pl->d_ready = reinterpret_cast<uint32_t *>(d + o_flags);
+    pl->d_gave_up = pl->d_ready + pl->groups.size();
+    pl->d_handshake = pl->d_gave_up + 1;
+    pl->gated_epoch = 0;
+    pl->handshake_epoch = 0;
+    pl->side_by_side.clear();
     pl->host_src = src_tbl;
     pl->host_out = out_tbl;
     pl->has_out = out != nullptr;
     pl->has_wv = w != nullptr;
     pl->bound = true;
+    for (int step = 0; step < 2; ++step)
+        if (int rc = gated_resident_per_cu(step != 0, &pl->gated_resident_per_cu[step])) {
+            release_device(pl);
+            return rc;
+        }
     // set-up is the place for runtime queries: find this device's copy of the static workspace
     // now, so that mgwfbp_pack_reduce_unpack_static never has to ask
     if (int rc = prepare_static_workspace()) {
@@ -534,6 +550,11 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
                 return fail(MGWFBP_EINVAL, "update_wgs_per_cu must be -1, 0, 8, 9, 10 or 11");
             pl->opt.update_wgs_per_cu = static_cast<int>(value);
             return MGWFBP_OK;
+        case MGWFBP_OPT_GATED_WGS_PER_CU:
+            if (value != -1 && !(value >= 1 && value <= 15))
+                return fail(MGWFBP_EINVAL, "gated_wgs_per_cu must be -1 or 1 .. 15");
+            pl->opt.gated_wgs_per_cu = static_cast<int>(value);
+            return MGWFBP_OK;
         default: return fail(MGWFBP_EINVAL, "unknown option key");
         }
     });
@@ -578,6 +599,10 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
                 if (tmp.long_tile_count && i >= tmp.long_tile_begin) {
                     r[4] = tmp.long_by_default ? 2 : 3;
                     r[5] = tmp.long_tile_elems;
+                }
+                if (i >= tmp.ordered_tile_begin) {
+                    r[4] = 4;
+                    r[5] = tmp.opt.tile_elems;
                 }
             }
             // the per-group lists carry their own (possibly halved) tile length
@@ -707,6 +732,98 @@ int mgwfbp_unpack_update(mgwfbp_plan_t *pl, int32_t group, const void *merged, s
         if ((rc = scope_of(pl, group, sc))) return rc;
         if ((rc = check_merged(sc, const_cast<void *>(merged), merged_bytes))) return rc;
         return launch_unpack(*pl, sc, static_cast<const float *>(merged), update != 0, lr, momentum, hip_stream);
+    });
+}
+
+}  // extern "C"
+
+namespace mgwfbp {
+int streams_side_by_side(mgwfbp_plan_t *pl, void *stream_a, void *stream_b, bool &yes)
+{
+    yes = false;
+    if (stream_a == stream_b) return MGWFBP_OK;
+    for (const auto &pr : pl->side_by_side)
+        if (pr.first == stream_a && pr.second == stream_b) {
+            yes = true;
+            return MGWFBP_OK;
+        }
+    // a kernel on stream_b waits (for at most 2 ms) for a word that a kernel put into stream_a
+    // AFTER it writes; it sees the word only if the device runs the two streams' kernels at once
+    const uint32_t value = ++pl->handshake_epoch;
+    int rc = launch_signal(pl->d_handshake + 1, 0u, stream_b);
+    if (!rc) rc = launch_await(pl->d_handshake, value, pl->d_handshake + 1, 2000, stream_b);
+    if (!rc) rc = launch_signal(pl->d_handshake, value, stream_a);
+    const hipError_t e1 = hipStreamSynchronize(static_cast<hipStream_t>(stream_a));
+    const hipError_t e2 = hipStreamSynchronize(static_cast<hipStream_t>(stream_b));
+    if (rc) return rc;
+    if (e1 != hipSuccess || e2 != hipSuccess) {
+        set_error(std::string("hipStreamSynchronize in the stream handshake: ") +
+                  hipGetErrorString(e1 != hipSuccess ? e1 : e2));
+        return MGWFBP_EHIP;
+    }
+    uint32_t seen = 0;
+    const hipError_t e = hipMemcpy(&seen, pl->d_handshake + 1, sizeof(seen), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        set_error(std::string("hipMemcpy of the handshake word: ") + hipGetErrorString(e));
+        return MGWFBP_EHIP;
+    }
+    yes = seen == 1u;
+    if (yes) pl->side_by_side.emplace_back(stream_a, stream_b);
+    return MGWFBP_OK;
+}
+}  // namespace mgwfbp
+
+extern "C" {
+
+int mgwfbp_gated_launch(mgwfbp_plan_t *pl, int32_t update, float lr, float momentum, uint32_t arrival,
+                        double give_up_ms, void *hip_stream)
+{
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, !update, update != 0);
+        if (rc) return rc;
+        if (update && (!std::isfinite(lr) || !std::isfinite(momentum)))
+            return fail(MGWFBP_EINVAL, "lr and momentum must be finite");
+        if (!(give_up_ms > 0.0) || give_up_ms > 6.0e4) return fail(MGWFBP_EINVAL, "give_up_ms must be in (0, 60000]");
+        return launch_fused_gated(*pl, update != 0, lr, momentum, pl->d_ready, arrival, pl->d_gave_up,
+                                  1 + static_cast<uint64_t>(give_up_ms * 1000.0), hip_stream);
+    });
+}
+
+int mgwfbp_streams_side_by_side(mgwfbp_plan_t *pl, void *stream_a, void *stream_b, int32_t *side_by_side)
+{
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        if (!side_by_side) return fail(MGWFBP_EINVAL, "side_by_side is NULL");
+        bool yes = false;
+        if ((rc = streams_side_by_side(pl, stream_a, stream_b, yes))) return rc;
+        *side_by_side = yes ? 1 : 0;
+        return MGWFBP_OK;
+    });
+}
+
+int mgwfbp_gated_signal(mgwfbp_plan_t *pl, int32_t group, uint32_t arrival, void *hip_stream)
+{
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        if (group < 0 || group >= static_cast<int32_t>(pl->groups.size()))
+            return fail(MGWFBP_EINVAL, "group " + std::to_string(group) + " out of range");
+        return launch_signal(pl->d_ready + group, arrival, hip_stream);
+    });
+}
+
+int mgwfbp_gated_gave_up(mgwfbp_plan_t *pl, int32_t *gave_up)
+{
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        if (!gave_up) return fail(MGWFBP_EINVAL, "gave_up is NULL");
+        uint32_t word = 0;
+        const hipError_t e = hipMemcpy(&word, pl->d_gave_up, sizeof(word), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipMemcpy of the give-up word: ") + hipGetErrorString(e));
+        *gave_up = word != 0;
+        return MGWFBP_OK;
     });
 }
 

@@ -257,6 +257,86 @@ extern "C" int mgwfbp_run_iteration_streams(mgwfbp_plan_t *pl, const double *tb_
     });
 }
 
+// ---- the iteration with the communication side as ONE gated launch ------------------------------
+
+namespace {
+int run_iteration_gated_impl(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr, float momentum,
+                             void *compute_stream, void *comm_stream, double give_up_ms, double *t_iter_ms)
+{
+    const double *tb = tb_ms ? tb_ms : (pl ? pl->tb.data() : nullptr);
+    int rc = check_iteration_args(pl, tb, update);
+    if (rc) return rc;
+    if (!(give_up_ms > 0.0) || give_up_ms > 6.0e4) {
+        set_error("give_up_ms must be in (0, 60000]");
+        return MGWFBP_EINVAL;
+    }
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    hipStream_t ms = static_cast<hipStream_t>(comm_stream);
+    if (cs == ms) {
+        // one stream would put the launch that waits in front of the kernels it waits for
+        set_error("the gated iteration needs two different streams");
+        return MGWFBP_EINVAL;
+    }
+    // the launch that waits must not sit in front of the kernels it waits for: two streams that the
+    // runtime serves from one hardware queue would do just that, and the launch would give up
+    bool apart = false;
+    if ((rc = streams_side_by_side(pl, compute_stream, comm_stream, apart))) return rc;
+    if (!apart) {
+        set_error("the device does not run these two streams' kernels at the same time (they share a "
+                  "hardware queue): the gated iteration needs a pair that mgwfbp_streams_side_by_side accepts");
+        return MGWFBP_ESTATE;
+    }
+    Events pool;
+    hipEvent_t base;
+    if ((rc = pool.make(&base, false))) return rc;
+    const uint32_t epoch = ++pl->gated_epoch;
+    const uint64_t max_polls = 1 + static_cast<uint64_t>(give_up_ms * 1000.0);  // a poll sleeps about a microsecond
+
+    // same shape as enqueue_iteration: a gate publishes time zero, the stand-ins wait for absolute
+    // deadlines; but instead of an event per group the compute stream bumps the group's arrival
+    // counter, and the communication stream holds a single launch that is already running
+    hipError_t e = hipSuccess;
+    if ((rc = launch_spin(0.0, cs))) return rc;
+    rc = launch_spin(0.3, cs, pl->d_clock);
+    if (!rc && (e = hipEventRecord(base, cs)) != hipSuccess) rc = hip_fail("hipEventRecord", e);
+    if (!rc && (e = hipStreamWaitEvent(ms, base, 0)) != hipSuccess) rc = hip_fail("hipStreamWaitEvent", e);
+    if (!rc) rc = launch_fused_gated(*pl, update != 0, lr, momentum, pl->d_ready, epoch, pl->d_gave_up, max_polls, ms);
+    if (!rc) rc = launch_spin(0.0, ms, pl->d_clock + 1);
+    double elapsed_ms = 0.0;
+    for (int32_t l = pl->L - 1; l >= 0 && !rc; --l) {
+        elapsed_ms += tb[l];
+        if (pl->merged[l]) continue;
+        const size_t k = static_cast<size_t>(pl->group_of_layer[l]);
+        // the stand-in for the group's lowest layer bumps the counter itself, at its end
+        rc = launch_spin_until(elapsed_ms, pl->d_clock, cs, pl->d_ready + k, epoch);
+    }
+    const hipError_t e1 = hipStreamSynchronize(cs);
+    const hipError_t e2 = hipStreamSynchronize(ms);
+    if (rc) return rc;
+    if (e1 != hipSuccess) return hip_fail("hipStreamSynchronize(compute)", e1);
+    if (e2 != hipSuccess) return hip_fail("hipStreamSynchronize(comm)", e2);
+    uint32_t gave_up = 0;
+    if ((e = hipMemcpy(&gave_up, pl->d_gave_up, sizeof(gave_up), hipMemcpyDeviceToHost)) != hipSuccess)
+        return hip_fail("hipMemcpy of the give-up word", e);
+    if (gave_up) {
+        set_error("the gated launch gave up waiting for a group's gradients (give_up_ms too short?)");
+        return MGWFBP_ESTATE;
+    }
+    if (t_iter_ms) return read_t_iter(pl, t_iter_ms);
+    return MGWFBP_OK;
+}
+}  // namespace
+
+extern "C" int mgwfbp_run_iteration_gated(mgwfbp_plan_t *pl, const double *tb_ms, int32_t update, float lr,
+                                          float momentum, void *compute_stream, void *comm_stream,
+                                          double give_up_ms, double *t_iter_ms)
+{
+    return guarded([&]() -> int {
+        return run_iteration_gated_impl(pl, tb_ms, update, lr, momentum, compute_stream, comm_stream, give_up_ms,
+                                        t_iter_ms);
+    });
+}
+
 // ---- the same iteration as a HIP graph -------------------------------------------------------
 
 struct mgwfbp_iteration_s {

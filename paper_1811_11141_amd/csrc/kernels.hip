@@ -229,22 +229,32 @@ __device__ __forceinline__ void lds_to_global(const float *lds, float *dst, uint
 // a tile to the top, ~270 registers, one wave per SIMD).  Such a load is invisible to the
 // compiler's own wait-count bookkeeping, so its result is passed through wait_all_loads()
 // before the first use.
-template <int OFF>
+// COH: the load also carries the device-scope bit, so it is served from where every compute
+// die's writes are visible instead of this die's L2 (for data another running kernel produced).
+template <int OFF, bool COH = false>
 __device__ __forceinline__ v4f ld_stream(const char *base, uint32_t voff)
 {
     v4f r;
-    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(r) : "v"(voff), "s"(base), "n"(OFF));
+    if constexpr (COH)
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 sc1 nt" : "=v"(r) : "v"(voff), "s"(base), "n"(OFF));
+    else
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(r) : "v"(voff), "s"(base), "n"(OFF));
     return r;
 }
 
 // Same load, ordered after the computation of `dep` (an in/out operand that is not touched).
-template <int OFF>
+template <int OFF, bool COH = false>
 __device__ __forceinline__ v4f ld_stream_after(const char *base, uint32_t voff, v4f &dep)
 {
     v4f r;
-    asm volatile("global_load_dwordx4 %0, %2, %3 offset:%4 nt"
-                 : "=v"(r), "+v"(dep)
-                 : "v"(voff), "s"(base), "n"(OFF));
+    if constexpr (COH)
+        asm volatile("global_load_dwordx4 %0, %2, %3 offset:%4 sc1 nt"
+                     : "=v"(r), "+v"(dep)
+                     : "v"(voff), "s"(base), "n"(OFF));
+    else
+        asm volatile("global_load_dwordx4 %0, %2, %3 offset:%4 nt"
+                     : "=v"(r), "+v"(dep)
+                     : "v"(voff), "s"(base), "n"(OFF));
     return r;
 }
 
@@ -330,7 +340,7 @@ __device__ __forceinline__ void pace_wave(int pace)
 // loop over the workers that is not unrolled (worker 0 is peeled off: it initialises the
 // accumulators); short launches keep the U pieces of one worker in flight instead of a ring
 // across workers.
-template <int NW, int U, bool STEP, int D, bool SCALE, class SrcFn>
+template <int NW, int U, bool STEP, int D, bool SCALE, bool COH = false, class SrcFn>
 __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, float *vp,
                                           float inv_n, float lr, float mu, int pace, int nw = NW)
 {
@@ -350,8 +360,8 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 v4f x;
-                if constexpr (u == 0) x = ld_stream<MGWFBP_OFF(u)>(sb, vo);
-                else x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u - 1]);
+                if constexpr (u == 0) x = ld_stream<MGWFBP_OFF(u), COH>(sb, vo);
+                else x = ld_stream_after<MGWFBP_OFF(u), COH>(sb + MGWFBP_HI(u), vo, res[u - 1]);
                 wait_all_loads(x);
                 res[u] = x;
                 pace_wave(pace);
@@ -362,7 +372,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             const char *sb = scalar_ptr(src(g));
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
-                v4f x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
+                v4f x = ld_stream_after<MGWFBP_OFF(u), COH>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
                 wait_all_loads(x);
                 res[u] = res[u] + x;
                 pace_wave(pace);
@@ -374,7 +384,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             const char *sb = scalar_ptr(src(0));
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
-                res[u] = ld_stream<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo);
+                res[u] = ld_stream<MGWFBP_OFF(u), COH>(sb + MGWFBP_HI(u), vo);
             });
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
@@ -389,7 +399,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
                 constexpr int u = decltype(uc)::value;
                 // ordered after the previous worker's last add, so that no more than U loaded
                 // values are live
-                x[u] = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[U - 1]);
+                x[u] = ld_stream_after<MGWFBP_OFF(u), COH>(sb + MGWFBP_HI(u), vo, res[U - 1]);
             });
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
@@ -405,8 +415,8 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
                 constexpr int u = decltype(uc)::value;
                 // the load is ordered after the previous add through its operand res[..]
                 v4f x;
-                if constexpr (g == 0 && u == 0) x = ld_stream<MGWFBP_OFF(u)>(sb, vo);
-                else x = ld_stream_after<MGWFBP_OFF(u)>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
+                if constexpr (g == 0 && u == 0) x = ld_stream<MGWFBP_OFF(u), COH>(sb, vo);
+                else x = ld_stream_after<MGWFBP_OFF(u), COH>(sb + MGWFBP_HI(u), vo, res[u == 0 ? U - 1 : u - 1]);
                 wait_all_loads(x);
                 if constexpr (g == 0) res[u] = x;
                 else res[u] = res[u] + x;
@@ -424,7 +434,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
         v4f x[DD];
         static_for<DD>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            x[j] = ld_stream<MGWFBP_OFF(j % U)>(sb[j / U] + MGWFBP_HI(j % U), vo);
+            x[j] = ld_stream<MGWFBP_OFF(j % U), COH>(sb[j / U] + MGWFBP_HI(j % U), vo);
         });
         static_for<T>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -436,7 +446,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             // the next load re-uses the slot just consumed; naming res[u] as an operand keeps
             // the add above ahead of it, so no more than DD loaded values are ever live
             if constexpr (j + DD < T)
-                x[j % DD] = ld_stream_after<MGWFBP_OFF((j + DD) % U)>(sb[(j + DD) / U] + MGWFBP_HI((j + DD) % U), vo, res[u]);
+                x[j % DD] = ld_stream_after<MGWFBP_OFF((j + DD) % U), COH>(sb[(j + DD) / U] + MGWFBP_HI((j + DD) % U), vo, res[u]);
         });
     }
     if constexpr (SCALE) {
@@ -453,9 +463,9 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
             v4f w[UB], v[UB];
             static_for<UB>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                w[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(wb + MGWFBP_HI(u0 + k), vo, res[u0 + k]);
+                w[k] = ld_stream_after<MGWFBP_OFF(u0 + k), COH>(wb + MGWFBP_HI(u0 + k), vo, res[u0 + k]);
                 wait_all_loads(w[k]);
-                v[k] = ld_stream_after<MGWFBP_OFF(u0 + k)>(vb + MGWFBP_HI(u0 + k), vo, w[k]);
+                v[k] = ld_stream_after<MGWFBP_OFF(u0 + k), COH>(vb + MGWFBP_HI(u0 + k), vo, w[k]);
                 wait_all_loads(v[k]);
             });
 #pragma unroll
@@ -481,15 +491,17 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
 
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
 // misaligned tensors, gather tiles) takes the general path below.
-template <int NW, int U, bool STEP, bool NT, int D>
-__global__ void __launch_bounds__(kBlock)
-k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace,
-        float *merged_out, uint64_t base_off)
+// COH: the gradients were written by a kernel that ran while this one was already running (the
+// gated launch): full tiles read them with device-scope loads, every other tile first drops what
+// this die's caches hold.
+template <int NW, int U, bool STEP, bool NT, int D, bool COH = false>
+__device__ __forceinline__ void fused_tile(const DeviceTables &dt, uint32_t tile_index, int nw, float inv_n,
+                                           float lr, float mu, int pace, float *merged_out, uint64_t base_off,
+                                           uint32_t *s_rel, uint32_t *s_len)
 {
     // merged_out != nullptr: the averaged values go to a merged buffer (the layer buffer of
     // Algorithm 2, already reduced) at their packed position instead of the per-layer out[].
-    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
-    const TileDev tl = load_tile(dt.tiles + tile_begin + blockIdx.x);
+    const TileDev tl = load_tile(dt.tiles + tile_index);
 
     if (tl.nseg == 1) {
         const uint32_t flags = table_load(&dt.segs[tl.seg].flags);
@@ -512,12 +524,13 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
         if constexpr (U > 0) {
             if (vec && n == U * kBlock * 4) {
                 const uint64_t start = tl.start;
-                fast_tile<NW, U, STEP, D, true>(
+                fast_tile<NW, U, STEP, D, true, COH>(
                     [sp_tbl, start](int g) { return table_load(sp_tbl + g) + start; }, outp, wp, vp,
                     inv_n, lr, mu, pace, nw);
                 return;
             }
         }
+        if constexpr (COH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         if (!STEP && merged_out && threadIdx.x < tl.pad) st<NT>(outp + n + threadIdx.x, 0.0f);
         const uint32_t n4 = vec ? (n >> 2) : 0;
         if constexpr (NW > 0) {
@@ -550,6 +563,7 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
             }
         }
     } else {
+        if constexpr (COH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         stage_gather_offsets(dt, tl, s_rel, s_len);
 #pragma unroll 1
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
@@ -569,6 +583,110 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
                                         STEP ? dt.v[si] : nullptr, i, lr, mu);
         }
     }
+}
+
+template <int NW, int U, bool STEP, bool NT, int D>
+__global__ void __launch_bounds__(kBlock)
+k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, float mu, int pace,
+        float *merged_out, uint64_t base_off)
+{
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
+    fused_tile<NW, U, STEP, NT, D>(dt, tile_begin + blockIdx.x, nw, inv_n, lr, mu, pace, merged_out, base_off,
+                                   s_rel, s_len);
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 2's communication thread as one launch
+// ------------------------------------------------------------------------------------------
+// Algorithm 2 sends a group when its lowest layer arrives from the backward pass.  Launching a
+// kernel per group costs 3.5 us each for groups that hold a few kilobytes (a dependent launch
+// cannot be shorter on this part), 90 of the 232 us of ResNet-50's 33 launches.  Here the whole
+// plan is ONE launch over a list of the tiles in arrival order.  Its workgroups stay: workgroup b
+// takes tiles b, b + gridDim.x, ... of the list and, before each, waits until the tile's group
+// has arrived, which is when the group's counter in device memory has reached this iteration's
+// number.  Whoever produces the gradients (here: the stand-ins of the backward pass) bumps the
+// group's counter with a release store behind its work.
+//   * Every wait is bounded: after max_polls polls of about a microsecond the workgroup sets
+//     the give-up word and ends, and every other workgroup ends at its next look at that word,
+//     so the launch always drains; the host then reports the failure.
+//   * The caller launches fewer workgroups than the chip holds at once, so the kernels that
+//     bump the counters (and the backward pass itself) find free slots.
+//   * The gradients were written while this kernel was already running, by a kernel that may
+//     have run on another compute die, and each die has its own L2.  The polls read the counter
+//     with device-scope loads that order nothing (an acquiring load drops the die's cached
+//     lines each time: 30 us more per ResNet-50 pass when every tile did it).  Full tiles then
+//     read the gradients with device-scope loads as well, which costs nothing measurable; the
+//     few ragged and gather tiles take one acquire fence instead.
+//   * The worker loop is the run-time one (any N), one load in flight per wave.
+__device__ __forceinline__ uint32_t load_agent(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t peek_agent(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kGatedReserve = 2;  // workgroup slots per compute unit the gated launch leaves free
+
+// *ctl: the give-up word, zero when the launch starts
+template <int U, bool STEP>
+__global__ void __launch_bounds__(kBlock)
+k_fused_gated(DeviceTables dt, uint32_t tile_begin, uint32_t n_tiles, int nw, float inv_n, float lr, float mu,
+              int pace, const uint32_t *ready, uint32_t epoch, uint32_t *ctl, uint64_t max_polls)
+{
+    __shared__ uint32_t s_rel[kMaxGatherSegs], s_len[kMaxGatherSegs];
+    __shared__ uint32_t s_go;
+#pragma unroll 1
+    for (uint32_t i = blockIdx.x; i < n_tiles; i += gridDim.x) {
+        // the tables are the host's and never change: the tile's descriptor is read before the wait
+        // (its second word holds the first segment, whose group is the tile's)
+        const uint32_t seg = static_cast<uint32_t>(
+            table_load(reinterpret_cast<const uint64_t *>(dt.tiles + tile_begin + i) + 1));
+        const uint32_t grp = table_load(&dt.segs[seg].group);
+        if (threadIdx.x == 0) {
+            uint32_t go = 0;
+            for (uint64_t k = 0; k < max_polls; ++k) {
+                const uint32_t stop = peek_agent(ctl), seen = peek_agent(ready + grp);  // both in flight
+                if (stop != 0) break;
+                // counters only grow; the difference is taken modulo 2^32
+                if (static_cast<int32_t>(seen - epoch) >= 0) {
+                    go = 1;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(16);
+            }
+            if (!go) __hip_atomic_store(ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_go = go;
+        }
+        __syncthreads();
+        const uint32_t go = s_go;
+        __syncthreads();  // s_go and the gather tables are rewritten in the next pass
+        if (!go) return;  // the same for every lane of the workgroup
+        fused_tile<0, U, STEP, true, 1, true>(dt, tile_begin + i, nw, inv_n, lr, mu, pace, nullptr, 0, s_rel, s_len);
+    }
+}
+
+// The kernels in front of this one in its stream have ended, which made what they wrote visible
+// to the whole device; the store itself needs to order nothing more.
+__global__ void __launch_bounds__(64) k_signal(uint32_t *counter, uint32_t epoch)
+{
+    if (threadIdx.x == 0) __hip_atomic_store(counter, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void __launch_bounds__(64)
+k_await(const uint32_t *word, uint32_t value, uint32_t *result, uint64_t max_polls)
+{
+    if (threadIdx.x != 0) return;
+    uint32_t seen = 2u;
+    for (uint64_t i = 0; i < max_polls; ++i) {
+        if (load_agent(word) == value) {
+            seen = 1u;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(32);
+    }
+    __hip_atomic_store(result, seen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -841,7 +959,11 @@ k_unpack(DeviceTables dt, uint32_t tile_begin, Divisor subs, const float *reduce
 // mode 0: wait `ticks` from now; then, if `clock` is given, publish the counter's value there.
 // mode 1: wait until `ticks` after the value published in `clock` (an absolute deadline, so the
 //         gaps between consecutive stand-ins do not add up).
-__global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls, uint64_t *clock, int mode)
+// arrive != nullptr: at its end the stand-in also bumps a group's arrival counter for the gated
+// launch, as the kernel that produces the group's last gradients would (a release store: what
+// the kernel wrote is visible to the device before the counter is).
+__global__ void __launch_bounds__(64)
+k_spin(uint64_t ticks, uint64_t max_polls, uint64_t *clock, int mode, uint32_t *arrive, uint32_t epoch)
 {
     const uint64_t t0 = mode == 1 ? __builtin_nontemporal_load(clock) : __builtin_amdgcn_s_memrealtime();
     for (uint64_t i = 0; i < max_polls; ++i) {
@@ -850,6 +972,8 @@ __global__ void __launch_bounds__(64) k_spin(uint64_t ticks, uint64_t max_polls,
     }
     if (mode == 0 && clock != nullptr && threadIdx.x == 0)
         __builtin_nontemporal_store(static_cast<uint64_t>(__builtin_amdgcn_s_memrealtime()), clock);
+    if (arrive != nullptr && threadIdx.x == 0)
+        __hip_atomic_store(arrive, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 int check_launch(const char *what)
@@ -1026,6 +1150,66 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     return check_launch("fused kernel launch");
 }
 
+int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
+                       uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream)
+{
+    if (pl.opt.tile_elems != 4096) {
+        set_error("the gated launch runs on 4096-element tiles (MGWFBP_OPT_TILE_ELEMS at its default)");
+        return MGWFBP_EINVAL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // cleared by a kernel, not a memset: the caller may be capturing a graph
+    k_signal<<<1, 64, 0, s>>>(ctl, 0u);
+    if (int rc = check_launch("launch that clears the give-up word")) return rc;
+    if (pl.ordered_tile_count == 0) return MGWFBP_OK;
+    // the launch takes kGatedReserve fewer workgroups per compute unit than the unit can hold of
+    // this kernel (16 by wave slots; the update form's registers allow 14) and so leaves room
+    // for the kernels that bump the counters: a chip filled with waiting workgroups would never
+    // see a counter move.  Every workgroup gets the same number of tiles (the last pass aside).
+    const int holds = pl.gated_resident_per_cu[step ? 1 : 0];
+    if (holds <= kGatedReserve) {
+        set_error("the gated launch needs a device that holds more than " + std::to_string(kGatedReserve) +
+                  " of its workgroups per compute unit");
+        return MGWFBP_ESTATE;
+    }
+    const int want = pl.opt.gated_wgs_per_cu > 0 ? pl.opt.gated_wgs_per_cu : holds;
+    const uint32_t cap = static_cast<uint32_t>(std::min(want, holds - kGatedReserve)) *
+                         static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
+    const uint32_t nt = pl.ordered_tile_count, passes = (nt + cap - 1) / cap;
+    const dim3 grid((nt + passes - 1) / passes);
+    const float inv_n = 1.0f / static_cast<float>(pl.N);
+    const int pace = pl.opt.pace >= 0 ? pl.opt.pace : 2;
+    const uint32_t tb = pl.ordered_tile_begin;
+    if (step) k_fused_gated<8, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+    else k_fused_gated<8, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+    return check_launch("gated launch");
+}
+
+int gated_resident_per_cu(bool step, int *per_cu)
+{
+    int n = 0;
+    const hipError_t e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, true>, kBlock, 0)
+                              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, false>, kBlock, 0);
+    if (e != hipSuccess) {
+        set_error(std::string("hipOccupancyMaxActiveBlocksPerMultiprocessor: ") + hipGetErrorString(e));
+        return MGWFBP_EHIP;
+    }
+    *per_cu = n;
+    return MGWFBP_OK;
+}
+
+int launch_signal(uint32_t *counter, uint32_t epoch, void *stream)
+{
+    k_signal<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(counter, epoch);
+    return check_launch("signal launch");
+}
+
+int launch_await(const uint32_t *word, uint32_t value, uint32_t *result, uint64_t max_polls, void *stream)
+{
+    k_await<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(word, value, result, max_polls);
+    return check_launch("handshake launch");
+}
+
 int launch_pack(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uint64_t epad,
                 void *stream)
 {
@@ -1118,22 +1302,22 @@ int wall_clock_khz()
 }
 
 namespace {
-int spin(double ms, uint64_t *clock, int mode, void *stream)
+int spin(double ms, uint64_t *clock, int mode, void *stream, uint32_t *arrive = nullptr, uint32_t epoch = 0)
 {
     if (!(ms > 0.0)) ms = 0.0;
     const uint64_t ticks = static_cast<uint64_t>(ms * wall_clock_khz());
     // one poll takes at least ~2048 clocks of sleep (~1 us); cap generously at 50x the target
     const uint64_t max_polls = 1000 + static_cast<uint64_t>(ms * 1000.0 * 50.0);
-    k_spin<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(ticks, max_polls, clock, mode);
+    k_spin<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(ticks, max_polls, clock, mode, arrive, epoch);
     return check_launch("backward stand-in launch");
 }
 }  // namespace
 
 int launch_spin(double ms, void *stream, uint64_t *publish_clock) { return spin(ms, publish_clock, 0, stream); }
 
-int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream)
+int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream, uint32_t *arrive, uint32_t epoch)
 {
-    return spin(deadline_ms, clock, 1, stream);
+    return spin(deadline_ms, clock, 1, stream, arrive, epoch);
 }
 
 }  // namespace mgwfbp

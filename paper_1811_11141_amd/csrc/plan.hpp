@@ -6,6 +6,7 @@
 #include <cstdint>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/mgwfbp.h"
@@ -65,6 +66,7 @@ struct Options {
     int long_tiles = -1;  // tile length of the whole-plan fused reduce pass: -1 by rule, 0 = tile_elems,
                           // 1 = 8192, or 5120 / 6144 / 7168 / 8192 elements
     int update_wgs_per_cu = -1;  // update kernel: -1 by rule, 0 uncapped, 8..11 forced
+    int gated_wgs_per_cu = -1;   // gated launch: -1 = all but the reserve, or 1..15
 };
 
 struct GroupInfo {
@@ -101,6 +103,10 @@ struct mgwfbp_plan_s {
     // third list: the whole plan cut into longer tiles, for the fused reduce pass when that fills
     // the chip's batches of workgroups better (0 tiles = not built)
     uint32_t long_tile_begin = 0, long_tile_count = 0, long_tile_elems = 0;
+    // fourth list: the whole plan in full-length tiles, group after group in communication order
+    // (inside a group slow tiles first), for the single gated launch that walks the groups in the
+    // order their gradients arrive
+    uint32_t ordered_tile_begin = 0, ordered_tile_count = 0;
     std::vector<const float *> host_src;  // host copies of the bound pointers (alias checks)
     std::vector<float *> host_out;
     bool long_by_default = false;  // the rule (or the option) says to use it
@@ -120,6 +126,14 @@ struct mgwfbp_plan_s {
     std::vector<struct mgwfbp_iteration_s *> iterations;  // graphs captured from this plan and still alive
     // two words at the end of d_blob: device clock at the start and at the end of an iteration
     uint64_t *d_clock = nullptr;
+    // behind them, for the gated launch: one arrival counter per group and the give-up word
+    uint32_t *d_ready = nullptr, *d_gave_up = nullptr;
+    int gated_resident_per_cu[2] = {0, 0};  // workgroups of the gated kernel (reduce, update) a compute unit holds
+    uint32_t gated_epoch = 0;  // arrival number the executor used last
+    // and two words for the handshake that shows whether two streams' kernels run at the same time
+    uint32_t *d_handshake = nullptr;
+    uint32_t handshake_epoch = 0;
+    std::vector<std::pair<void *, void *>> side_by_side;  // (signalling, waiting) stream pairs that passed it
     mgwfbp::DeviceTables dt;
 };
 
@@ -211,10 +225,27 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
                   void *stream);
 int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *reduced, bool step,
                   float lr, float mu, void *stream);
+// One launch over the whole plan in arrival order; a tile runs once its group's counter has
+// reached `epoch` (or the launch gives up after max_polls polls of ~1 us and says so in *ctl).
+// ctl: the plan's give-up word; a small kernel in front of the launch clears it.
+int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
+                       uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream);
+// How many workgroups of the gated kernel (update form or not) one compute unit of the current device holds.
+int gated_resident_per_cu(bool step, int *per_cu);
+// Sets *counter = epoch (device scope, release) behind the work already in the stream.
+int launch_signal(uint32_t *counter, uint32_t epoch, void *stream);
+// One wave polls *word until it equals `value` (then *result = 1) or max_polls polls of ~1 us have
+// passed (then *result = 2).
+int launch_await(const uint32_t *word, uint32_t value, uint32_t *result, uint64_t max_polls, void *stream);
+// Do kernels of stream_a run while a kernel of stream_b is still running?  Streams that the runtime
+// serves from one hardware queue do not.  Pairs that passed are remembered in the plan.
+int streams_side_by_side(mgwfbp_plan_t *pl, void *stream_a, void *stream_b, bool &yes);
 // Timed stand-ins for the backward pass: wait `ms`, optionally publishing the device clock at the
-// end; or wait until `deadline_ms` after the published clock value.
+// end; or wait until `deadline_ms` after the published clock value and then, if `arrive` is given,
+// set *arrive = epoch as the gated launch's signal.
 int launch_spin(double ms, void *stream, uint64_t *publish_clock = nullptr);
-int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream);
+int launch_spin_until(double deadline_ms, uint64_t *clock, void *stream, uint32_t *arrive = nullptr,
+                      uint32_t epoch = 0);
 int wall_clock_khz();  // ticks per millisecond of the device clock the stand-ins read
 
 }  // namespace mgwfbp

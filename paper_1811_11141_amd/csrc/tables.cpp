@@ -128,7 +128,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     // elements one gather tile may hold: a few per lane, since each costs a table search;
     // small <= tile, so no tile of any kind exceeds tile_elems
     const uint32_t gather_cap = std::max<uint32_t>(std::min<uint32_t>(tile, 1024), small);
-    std::vector<TileDev> all_slow, all_full;
+    std::vector<TileDev> all_slow, all_full, ordered;
     // the longer tile lengths the fused reduce pass may use instead (only next to 4096)
     const bool longer_ok = tile == 4096 && pl.opt.long_tiles != 0;
     std::vector<TileDev> alt_slow[kTileChoices], alt_full[kTileChoices];
@@ -236,6 +236,12 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         pl.tiles.insert(pl.tiles.end(), full.begin(), full.end());
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
         cut(tile, all_slow, all_full);
+        {
+            std::vector<TileDev> os, of;
+            cut(tile, os, of);
+            ordered.insert(ordered.end(), os.begin(), os.end());
+            ordered.insert(ordered.end(), of.begin(), of.end());
+        }
         if (longer_ok)
             for (int c = 1; c < kTileChoices; ++c) cut(kTileChoice[c], alt_slow[c], alt_full[c]);
     }
@@ -286,6 +292,10 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             pl.long_tile_elems = kTileChoice[pick];
         }
     }
+    // A fourth copy in arrival order, for the gated launch.
+    pl.ordered_tile_begin = static_cast<uint32_t>(pl.tiles.size());
+    pl.ordered_tile_count = static_cast<uint32_t>(ordered.size());
+    pl.tiles.insert(pl.tiles.end(), ordered.begin(), ordered.end());
 }
 
 }  // namespace mgwfbp

@@ -9,7 +9,11 @@ int launch_pack(const mgwfbp_plan_t &, const LaunchScope &, float *, uint64_t, v
 int launch_reduce(const mgwfbp_plan_t &, const LaunchScope &, float *, uint64_t, void *) { return MGWFBP_EHIP; }
 int launch_unpack(const mgwfbp_plan_t &, const LaunchScope &, const float *, bool, float, float, void *) { return MGWFBP_EHIP; }
 int launch_spin(double, void *, uint64_t *) { return MGWFBP_EHIP; }
-int launch_spin_until(double, uint64_t *, void *) { return MGWFBP_EHIP; }
+int launch_spin_until(double, uint64_t *, void *, uint32_t *, uint32_t) { return MGWFBP_EHIP; }
 int wall_clock_khz() { return 100000; }
 int prepare_static_workspace() { return MGWFBP_EHIP; }
+int launch_fused_gated(const mgwfbp_plan_t &, bool, float, float, const uint32_t *, uint32_t, uint32_t *, uint64_t, void *) { return MGWFBP_EHIP; }
+int launch_signal(uint32_t *, uint32_t, void *) { return MGWFBP_EHIP; }
+int gated_resident_per_cu(bool, int *) { return MGWFBP_EHIP; }
+int launch_await(const uint32_t *, uint32_t, uint32_t *, uint64_t, void *) { return MGWFBP_EHIP; }
 }  // namespace mgwfbp

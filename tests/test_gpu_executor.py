@@ -228,3 +228,146 @@ def test_iteration_graph_argument_errors(mg):
     assert raw.mgwfbp_iteration_replay(handle, C.c_void_p(int(s1.cuda_stream)), C.byref(t)) == mg.ESTATE
     assert "destroyed" in mg.last_error()
     raw.mgwfbp_iteration_destroy(handle)
+
+
+# ---- Algorithm 2's communication side as one gated launch -------------------------------------
+
+def streams_side_by_side(pl, tries=8):
+    """(signalling, waiting) streams whose kernels the device runs at the same time.  The runtime
+    serves its streams from four hardware queues; a pair that shares one cannot be used."""
+    for _ in range(tries):
+        a, b = torch.cuda.Stream(), torch.cuda.Stream()
+        if pl.streams_side_by_side(a, b):
+            return a, b
+    pytest.fail(f"no pair of streams ran side by side in {tries} tries")
+
+
+@pytest.mark.parametrize("name,update", [("tiny", False), ("tiny", True), ("googlenet", False), ("resnet50", True)])
+def test_gated_iteration_equals_oracle(mg, name, update):
+    """mgwfbp_run_iteration_gated: one launch walks the groups in arrival order and waits on the
+    device for each group's arrival counter; values equal the oracle's, the iteration is not
+    shorter than its backward pass (Eq. 8), and a second iteration (counters at 2) works too."""
+    if name == "tiny":
+        w = wl.tiny_workload(9, L=12)
+        tb = w.tb_ms * 0.1
+        pl = mg.mgwfbp_plan(w.p, tb, 0.0, 0.05, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    else:
+        w = wl.cnn_workload(name)
+        tb = w.tb_ms * (1.0 / w.tb_ms.sum())                   # a 1 ms backward pass
+        pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    groups = pl.groups()
+    grads = wl.make_gradients(w, 21, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 21, "cuda")
+    for t in vt:
+        t.normal_(0, 1e-3)
+    w0, v0 = [t.clone() for t in wt], [t.clone() for t in vt]
+    pl.bind(grads, out, wt, vt)
+    s_comp, s_comm = streams_side_by_side(pl)
+    torch.cuda.synchronize()
+    t_iter = pl.run_iteration_gated(s_comp, s_comm, tb_ms=tb, update=update, lr=0.1, momentum=0.9)
+    backward = float(np.sum(tb))
+    assert t_iter >= backward - (0.02 + 1e-3 * backward)
+    assert not pl.gated_gave_up()
+
+    def check(w_ref, v_ref):
+        for l, n in enumerate(int(x) for x in w.p):
+            avg = od.reduce([grads[g][l].cpu().numpy() for g in range(w.n_workers)])
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), avg.view(np.uint32)), l
+            if update:
+                ww, vv = w_ref[l].cpu().numpy(), v_ref[l].cpu().numpy()
+                od.sgd(ww, vv, avg, 0.1, 0.9)
+                assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), ww.view(np.uint32)), l
+                assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), vv.view(np.uint32)), l
+    check(w0, v0)
+    # next iteration: fresh gradients, counters move on to 2
+    w1, v1 = [t.clone() for t in wt], [t.clone() for t in vt]
+    fresh = wl.make_gradients(w, 22, "cuda")
+    for g in range(w.n_workers):
+        for l in range(w.L):
+            grads[g][l].copy_(fresh[g][l])
+    for t in out:
+        t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    pl.run_iteration_gated(s_comp, s_comm, tb_ms=tb, update=update, lr=0.1, momentum=0.9)
+    check(w1, v1)
+    assert len(groups) >= 1
+
+
+def test_gated_launch_waits_for_signals_in_any_order_and_gives_up_when_none_comes(mg):
+    """The launch and the signals through the C ABI.  Signals come from another stream in reverse
+    group order, each behind a short stand-in: every group still runs, after its own signal.  A
+    launch whose groups are never signalled ends by itself after give_up_ms (a bounded wait that
+    the host forces to fail: every workgroup still exits normally) and says so."""
+    w = wl.custom_workload([70001, 5, 4096 * 3, 300, 9000, 64, 12289], 3, sigma=1e-2)
+    merged = [7, 5, 4, 2]
+    pl = mg.mgwfbp_plan_explicit(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, 3, merged)
+    groups = pl.groups()
+    grads = wl.make_gradients(w, 5, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    pl.bind(grads, out)
+    s_sig, s_launch = streams_side_by_side(pl)
+    torch.cuda.synchronize()
+    # 1. never signalled: gives up after 20 ms, nothing is written
+    pl.gated_launch(arrival=1, give_up_ms=20.0, stream=s_launch)
+    torch.cuda.synchronize()
+    assert pl.gated_gave_up()
+    assert all(bool(torch.isnan(t).all()) for t in out)
+    # 2. signalled in reverse order from another stream
+    pl.gated_launch(arrival=1, give_up_ms=5000.0, stream=s_launch)
+    with torch.cuda.stream(s_sig):
+        for k in reversed(range(len(groups))):
+            torch.cuda._sleep(200_000)                        # ~0.1 ms of device time between arrivals
+            pl.gated_signal(k, 1, stream=s_sig)
+    torch.cuda.synchronize()
+    assert not pl.gated_gave_up()
+    exp = od.merged_gradient_path([to_np(r) for r in grads], groups)
+    for l in range(w.L):
+        assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), l
+    # 3. counters only grow: a launch for arrival 1 again runs at once, one for arrival 2 waits
+    for t in out:
+        t.fill_(float("nan"))
+    pl.gated_launch(arrival=1, give_up_ms=5000.0, stream=s_launch)
+    torch.cuda.synchronize()
+    assert not pl.gated_gave_up() and all(bool(torch.isfinite(t).all()) for t in out)
+    pl.gated_launch(arrival=2, give_up_ms=10.0, stream=s_launch)
+    torch.cuda.synchronize()
+    assert pl.gated_gave_up()
+    with pytest.raises(mg.MgwfbpError):
+        pl.gated_signal(len(groups), 1)                       # no such group
+    with pytest.raises(mg.MgwfbpError):
+        pl.run_iteration_gated(s_launch, s_launch)            # needs two streams
+
+
+def test_streams_that_share_a_hardware_queue_are_refused(mg):
+    """mgwfbp_streams_side_by_side: a stream does not run beside itself; among fresh pairs most run
+    side by side; a pair that does not is refused by the gated iteration at once (MGWFBP_ESTATE,
+    nothing run) instead of after give_up_ms."""
+    import time
+    w = wl.tiny_workload(9, L=12)
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms * 0.1, 0.0, 0.05, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    grads = wl.make_gradients(w, 3, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    pl.bind(grads, out)
+    s = torch.cuda.Stream()
+    assert not pl.streams_side_by_side(s, s)
+    good, bad = [], []
+    for _ in range(16):                                       # torch hands out 32 pooled streams in turn
+        a, b = torch.cuda.Stream(), torch.cuda.Stream()
+        (good if pl.streams_side_by_side(a, b) else bad).append((a, b))
+    assert len(good) >= 8
+    a, b = good[0]
+    assert pl.streams_side_by_side(a, b)                      # remembered
+    pl.run_iteration_gated(a, b, tb_ms=w.tb_ms * 0.1)
+    assert all(bool(torch.isfinite(t).all()) for t in out)
+    if bad:
+        for t in out:
+            t.fill_(float("nan"))
+        a, b = bad[0]
+        t0 = time.perf_counter()
+        with pytest.raises(mg.MgwfbpError) as ei:
+            pl.run_iteration_gated(a, b, tb_ms=w.tb_ms * 0.1, give_up_ms=5000.0)
+        assert ei.value.code == mg.ESTATE
+        assert time.perf_counter() - t0 < 1.0
+        torch.cuda.synchronize()
+        assert all(bool(torch.isnan(t).all()) for t in out)

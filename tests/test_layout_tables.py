@@ -54,14 +54,14 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
         assert pad == 0 or off % pad == 0
     small_eff = min(small, tile)
     lists = sorted({int(x) for x in tiles[:, 4]})
-    assert lists[:2] == [0, 1] and (2 in lists) == (long_tiles not in (-1, 0) and tile == 4096)
-    for which in lists:                       # per-group lists, whole-plan list, double-length list
+    assert lists[:2] == [0, 1] and (2 in lists) == (long_tiles not in (-1, 0) and tile == 4096) and 4 in lists
+    for which in lists:       # per-group lists, whole-plan list, double-length list, arrival-ordered list
         cover = np.zeros(P, dtype=np.uint8)
         sel = tiles[tiles[:, 4] == which]
         assert len(sel) > 0
         last_group, seen_full_in_group = -1, False
         for first, nseg, start, n, _, tlen, tpad in (tuple(int(x) for x in r) for r in sel):
-            if which >= 2:
+            if which in (2, 3):
                 assert tlen == (8192 if long_tiles == 1 else long_tiles) and 1 <= n <= tlen
             else:
                 assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
@@ -87,7 +87,7 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
                 lo = start
                 is_full = False
             cover[lo:lo + n] += 1
-            if which == 0:
+            if which in (0, 4):
                 # group after group; inside a group the slow tiles (gather, ragged) come first
                 assert grp >= last_group
                 if grp != last_group:
