@@ -174,8 +174,9 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             list 0: the per-group lists (group after group); list 1: the second copy used
  *             by whole-plan launches; list 2 or 3 (when built): the whole plan in longer
  *             tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses it by default,
- *             3 if only mgwfbp_tune may select it; list 4: the whole plan in tiles of tile_elems,
- *             group after group in communication order (mgwfbp_gated_launch).
+ *             3 if only mgwfbp_tune may select it; list 4: the whole plan group after group in
+ *             communication order (mgwfbp_gated_launch), in tiles of tile_elems, groups of up
+ *             to 64 Ki elements in tiles of 512.
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too
  *             few workgroups).

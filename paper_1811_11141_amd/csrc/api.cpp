@@ -602,7 +602,7 @@ int mgwfbp_plan_layout(const mgwfbp_plan_t *pl, uint64_t *n_segments, uint64_t *
                 }
                 if (i >= tmp.ordered_tile_begin) {
                     r[4] = 4;
-                    r[5] = tmp.opt.tile_elems;
+                    r[5] = tmp.groups[tmp.segs[t.seg].group].gated_tile_elems;
                 }
             }
             // the per-group lists carry their own (possibly halved) tile length

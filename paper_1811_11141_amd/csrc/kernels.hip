@@ -117,24 +117,71 @@ __device__ __forceinline__ T nway_mean_fixed(const float *const (&sp)[NW], uint3
     return acc * inv_n;
 }
 
+// Loads with the device-scope bit: served from where every compute die's writes are visible
+// instead of this die's L2, for data that a kernel running at the same time produced.  The
+// 128-bit form is written as an instruction (there is no 128-bit atomic load to ask the compiler
+// for); the compiler's wait-count bookkeeping does not see it, so the results of a batch go
+// through device_loads_done() before their first use.
+__device__ __forceinline__ float ld_device(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ v4f ld_device(const v4f *p)
+{
+    v4f r;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1 nt" : "=v"(r) : "v"(p));
+    return r;
+}
+__device__ __forceinline__ void device_loads_done(float &, float &, float &, float &) {}
+__device__ __forceinline__ void device_loads_done(float &) {}
+__device__ __forceinline__ void device_loads_done(v4f &a, v4f &b, v4f &c, v4f &d)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+__device__ __forceinline__ void device_loads_done(v4f &a) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(a)); }
+
 // Run-time N: `ptr(g)` yields worker g's base pointer; loads go out four at a time.
-template <bool NT, class T, class PtrFn>
+// COH: with device-scope loads.
+template <bool NT, class T, bool COH = false, class PtrFn>
 __device__ __forceinline__ T nway_mean_dyn(PtrFn ptr, int nw, uint32_t i, float inv_n)
 {
-    T acc = ld<NT>(reinterpret_cast<const T *>(ptr(0)) + i);
-    int g = 1;
-    for (; g + 4 <= nw; g += 4) {
-        const T a = ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
-        const T b = ld<NT>(reinterpret_cast<const T *>(ptr(g + 1)) + i);
-        const T c = ld<NT>(reinterpret_cast<const T *>(ptr(g + 2)) + i);
-        const T d = ld<NT>(reinterpret_cast<const T *>(ptr(g + 3)) + i);
-        acc = acc + a;
-        acc = acc + b;
-        acc = acc + c;
-        acc = acc + d;
+    if constexpr (COH) {
+        T acc = ld_device(reinterpret_cast<const T *>(ptr(0)) + i);
+        device_loads_done(acc);
+        int g = 1;
+        for (; g + 4 <= nw; g += 4) {
+            T a = ld_device(reinterpret_cast<const T *>(ptr(g)) + i);
+            T b = ld_device(reinterpret_cast<const T *>(ptr(g + 1)) + i);
+            T c = ld_device(reinterpret_cast<const T *>(ptr(g + 2)) + i);
+            T d = ld_device(reinterpret_cast<const T *>(ptr(g + 3)) + i);
+            device_loads_done(a, b, c, d);
+            acc = acc + a;
+            acc = acc + b;
+            acc = acc + c;
+            acc = acc + d;
+        }
+        for (; g < nw; ++g) {
+            T a = ld_device(reinterpret_cast<const T *>(ptr(g)) + i);
+            device_loads_done(a);
+            acc = acc + a;
+        }
+        return acc * inv_n;
+    } else {
+        T acc = ld<NT>(reinterpret_cast<const T *>(ptr(0)) + i);
+        int g = 1;
+        for (; g + 4 <= nw; g += 4) {
+            const T a = ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
+            const T b = ld<NT>(reinterpret_cast<const T *>(ptr(g + 1)) + i);
+            const T c = ld<NT>(reinterpret_cast<const T *>(ptr(g + 2)) + i);
+            const T d = ld<NT>(reinterpret_cast<const T *>(ptr(g + 3)) + i);
+            acc = acc + a;
+            acc = acc + b;
+            acc = acc + c;
+            acc = acc + d;
+        }
+        for (; g < nw; ++g) acc = acc + ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
+        return acc * inv_n;
     }
-    for (; g < nw; ++g) acc = acc + ld<NT>(reinterpret_cast<const T *>(ptr(g)) + i);
-    return acc * inv_n;
 }
 
 // Write the averaged value and, when STEP, apply the update.  Pointers are in units of float.
@@ -492,8 +539,7 @@ __device__ __forceinline__ void fast_tile(SrcFn src, float *outp, float *wp, flo
 // U > 0: full aligned tiles of U*kBlock float4 take fast_tile; everything else (ragged tails,
 // misaligned tensors, gather tiles) takes the general path below.
 // COH: the gradients were written by a kernel that ran while this one was already running (the
-// gated launch): full tiles read them with device-scope loads, every other tile first drops what
-// this die's caches hold.
+// gated launch): every load of a gradient carries the device-scope bit (the run-time-N code only).
 template <int NW, int U, bool STEP, bool NT, int D, bool COH = false>
 __device__ __forceinline__ void fused_tile(const DeviceTables &dt, uint32_t tile_index, int nw, float inv_n,
                                            float lr, float mu, int pace, float *merged_out, uint64_t base_off,
@@ -530,7 +576,6 @@ __device__ __forceinline__ void fused_tile(const DeviceTables &dt, uint32_t tile
                 return;
             }
         }
-        if constexpr (COH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         if (!STEP && merged_out && threadIdx.x < tl.pad) st<NT>(outp + n + threadIdx.x, 0.0f);
         const uint32_t n4 = vec ? (n >> 2) : 0;
         if constexpr (NW > 0) {
@@ -553,17 +598,16 @@ __device__ __forceinline__ void fused_tile(const DeviceTables &dt, uint32_t tile
             auto ptr = [sp_tbl, start](int g) { return sp_tbl[g] + start; };
 #pragma unroll 1
             for (uint32_t i = threadIdx.x; i < n4; i += kBlock) {
-                const v4f avg = nway_mean_dyn<NT, v4f>(ptr, nw, i, inv_n);
+                const v4f avg = nway_mean_dyn<NT, v4f, COH>(ptr, nw, i, inv_n);
                 finish<STEP, NT, v4f>(avg, outp, wp, vp, i, lr, mu);
             }
 #pragma unroll 1
             for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += kBlock) {
-                const float avg = nway_mean_dyn<NT, float>(ptr, nw, i, inv_n);
+                const float avg = nway_mean_dyn<NT, float, COH>(ptr, nw, i, inv_n);
                 finish<STEP, NT, float>(avg, outp, wp, vp, i, lr, mu);
             }
         }
     } else {
-        if constexpr (COH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         stage_gather_offsets(dt, tl, s_rel, s_len);
 #pragma unroll 1
         for (uint32_t k = threadIdx.x; k < tl.n; k += kBlock) {
@@ -575,7 +619,7 @@ __device__ __forceinline__ void fused_tile(const DeviceTables &dt, uint32_t tile
                 continue;
             }
             const float *const *sp_tbl = dt.src + static_cast<size_t>(si) * nw;
-            const float avg = nway_mean_dyn<NT, float>([sp_tbl](int g) { return sp_tbl[g]; }, nw, i, inv_n);
+            const float avg = nway_mean_dyn<NT, float, COH>([sp_tbl](int g) { return sp_tbl[g]; }, nw, i, inv_n);
             if (!STEP && merged_out)  // a gather tile is one contiguous run of the merged buffer
                 st<NT>(merged_out + (tl.start - base_off) + k, avg);
             else
@@ -614,9 +658,9 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
 //   * The gradients were written while this kernel was already running, by a kernel that may
 //     have run on another compute die, and each die has its own L2.  The polls read the counter
 //     with device-scope loads that order nothing (an acquiring load drops the die's cached
-//     lines each time: 30 us more per ResNet-50 pass when every tile did it).  Full tiles then
-//     read the gradients with device-scope loads as well, which costs nothing measurable; the
-//     few ragged and gather tiles take one acquire fence instead.
+//     lines each time: 30 us more per ResNet-50 pass when every tile did it).  The gradients
+//     are then read with device-scope loads as well, which costs nothing measurable, and the
+//     tables stay in the die's L2.
 //   * The worker loop is the run-time one (any N), one load in flight per wave.
 __device__ __forceinline__ uint32_t load_agent(const uint32_t *p)
 {

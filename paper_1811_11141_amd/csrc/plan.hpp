@@ -47,6 +47,9 @@ struct TileDev {
 static_assert(sizeof(TileDev) == 24, "TileDev layout");
 
 constexpr uint32_t kMaxGatherSegs = 256;  // segments one gather tile may span
+// arrival-ordered list: groups of up to kGatedSmallGroupElems elements are cut into kGatedShortTile pieces
+constexpr uint32_t kGatedShortTile = 512;
+constexpr uint64_t kGatedSmallGroupElems = 64u * 1024u;
 
 struct DeviceTables {
     const SegDev *segs = nullptr;
@@ -76,6 +79,7 @@ struct GroupInfo {
     uint32_t seg_begin = 0, seg_end = 0;
     uint32_t tile_begin = 0, tile_end = 0;
     uint32_t tile_elems = 0;  // tile length of the group's own list (<= the plan's tile_elems)
+    uint32_t gated_tile_elems = 0;  // and of its part of the arrival-ordered list
     double start_ms = 0, finish_ms = 0;
 };
 

@@ -237,8 +237,13 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         g.tile_end = static_cast<uint32_t>(pl.tiles.size());
         cut(tile, all_slow, all_full);
         {
+            // In the gated launch a small group is usually alone on the chip when it arrives, and a
+            // full tile is then a chain of N * 8 loads, each waited for (35 us for N = 8).  Cut into
+            // 512-element pieces the group runs the general code instead: one 128-bit access per
+            // lane and worker, four in flight.
+            g.gated_tile_elems = g.elems <= kGatedSmallGroupElems ? std::min(tile, kGatedShortTile) : tile;
             std::vector<TileDev> os, of;
-            cut(tile, os, of);
+            cut(g.gated_tile_elems, os, of);
             ordered.insert(ordered.end(), os.begin(), os.end());
             ordered.insert(ordered.end(), of.begin(), of.end());
         }

@@ -35,12 +35,15 @@ WORKLOADS = {   # tag -> (bench.py workload arguments, description, N, P)
 }
 UNITS = {"fused": lambda n: n + 1, "step": lambda n: n + 5, "step_without_out": lambda n: n + 4,
          "pack": lambda n: 2 * n, "reduce": lambda n: n + 1, "unpack": lambda n: 2, "pack_reduce": lambda n: n + 1,
-         "unpack_only": lambda n: 2, "unpack_update": lambda n: 6, "unpack_update_without_out": lambda n: 5}
+         "unpack_only": lambda n: 2, "unpack_update": lambda n: 6, "unpack_update_without_out": lambda n: 5,
+         "gated_all_arrived": lambda n: n + 1}
 # variant -> (summary file stem, regex of the kernel's name in rocprofv3's output)
 KERNELS = {"fused": ("k_fused", r"k_fused<\d+, \d+, false"), "step": ("k_fused_update", r"k_fused<\d+, \d+, true"),
            "pack": ("k_pack", r"k_pack<"), "reduce": ("k_reduce", r"k_reduce<"), "unpack": ("k_unpack", r"k_unpack<false"),
-           "unpack_update": ("k_unpack_update", r"k_unpack<true")}
-TRACES = [("resnet50_n8", v, 100) for v in ("fused", "step", "pack", "reduce", "unpack", "unpack_update")] + \
+           "unpack_update": ("k_unpack_update", r"k_unpack<true"),
+           "gated_all_arrived": ("k_fused_gated", r"k_fused_gated<\d+, false")}
+TRACES = [("resnet50_n8", v, 100) for v in ("fused", "step", "pack", "reduce", "unpack", "unpack_update",
+                                            "gated_all_arrived")] + \
          [("googlenet_n8", v, 100) for v in ("fused", "step", "pack", "unpack", "unpack_update")] + \
          [("vgg16_n16", v, 30) for v in ("fused", "step")]
 COUNTER_RUNS = [("resnet50_n8", 16), ("googlenet_n8", 16), ("vgg16_n16", 6)]
@@ -217,7 +220,8 @@ def _traffic_summary(wl_tag: str, steps: int) -> dict:
             ("pack", KERNELS["pack"][1], "Average"), ("reduce", KERNELS["reduce"][1], "Average"),
             ("unpack", KERNELS["unpack"][1], "Average"), ("unpack_only", KERNELS["unpack"][1], "Average"),
             ("unpack_update", KERNELS["unpack_update"][1], "Max"),
-            ("unpack_update_without_out", KERNELS["unpack_update"][1], "Min")]
+            ("unpack_update_without_out", KERNELS["unpack_update"][1], "Min"),
+            ("gated_all_arrived", KERNELS["gated_all_arrived"][1], "Average")]
     for variant, pattern, stat in spec:
         k = pick(pattern)
         if k is None:

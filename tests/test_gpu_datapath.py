@@ -1049,13 +1049,18 @@ def test_full_size_materialised(mg):
     ("resnet50", 12, 0.5, None, False),        # a worker count with a run-time worker loop
     ("resnet50", None, 0.5, None, True),       # one launch per group, as Algorithm 2 would issue them
     ("googlenet", None, 0.5, None, True),
+    # the whole plan as one gated launch whose groups have all arrived (arrival-ordered tiles,
+    # device-scope loads, small groups in 512-element tiles)
+    ("resnet50", None, 0.5, None, "gated"), ("resnet50", 12, 0.5, None, "gated"),
+    ("googlenet", None, 0.5, None, "gated"), ("alexnet", None, 0.5, None, "gated"),
+    ("vgg16", None, 0.5, None, "gated"),
     ("googlenet", None, 0.5, 1024, False), ("googlenet", None, 0.5, 2048, False),
     ("alexnet", None, 0.5, 8192, False)])
 def test_full_size_sets(mg, name, n_workers, a_ms, tile, per_group):
     """The ResNet-50 / GoogLeNet / AlexNet / VGG-16 shaped sets at full size and worker count,
     in the launch configurations bench.py times (default tile, whole plan in one launch; VGG-16
-    at both worker counts and all three start-up costs), plus the other tile sizes and the
-    launch-per-group sequence.  Every element of every layer is compared with the oracle: the
+    at both worker counts and all three start-up costs), plus the other tile sizes, the
+    launch-per-group sequence and the single gated launch.  Every element of every layer is compared with the oracle: the
     averaged gradients after the fused pass, then w, v and the averaged gradients again after
     the fused update."""
     w = wl.cnn_workload(name, a_ms=a_ms, n_workers=n_workers)
@@ -1070,7 +1075,9 @@ def test_full_size_sets(mg, name, n_workers, a_ms, tile, per_group):
     w0, v0 = [t.clone() for t in wt], [t.clone() for t in vt]
     pl.bind(grads, out, wt, vt)
     n_groups = pl.info()["n_groups"]
-    if per_group:
+    if per_group == "gated":
+        pl.gated_launch(0, give_up_ms=2000.0)
+    elif per_group:
         for k in range(n_groups):
             pl.pack_reduce_unpack(group=k)
     else:
@@ -1079,7 +1086,11 @@ def test_full_size_sets(mg, name, n_workers, a_ms, tile, per_group):
     compare_whole_set(name, w, grads, out=out)
     for t in out:
         t.fill_(float("nan"))
-    if per_group:
+    if per_group == "gated":
+        pl.gated_launch(0, update=True, lr=0.1, momentum=0.9, give_up_ms=2000.0)
+        torch.cuda.synchronize()
+        assert not pl.gated_gave_up()
+    elif per_group:
         for k in range(n_groups):
             pl.step(0.1, 0.9, group=k)
     else:

@@ -66,7 +66,11 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
             else:
                 assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
                 # a group's own list may use shorter tiles than the whole-plan list, never longer
-                assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
+                if which == 4:   # the arrival-ordered list cuts small groups into 512-element pieces
+                    gsz = sum(plen(e[1]) for e in exp if e[3] == exp[first][3])
+                    assert tlen == (min(tile, 512) if gsz <= 64 * 1024 else tile)
+                else:
+                    assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
             assert 1 <= nseg <= 256
             if nseg == 1:
                 lyr, sn, soff, grp = exp[first]
