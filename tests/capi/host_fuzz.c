@@ -56,6 +56,18 @@ int main(void)
             if (mgwfbp_pack_reduce_unpack(pl, -1, NULL, 0, NULL) != MGWFBP_ESTATE) bad++;
             if (mgwfbp_step(pl, 0, 0.1f, 0.9f, NULL, 0, NULL) != MGWFBP_ESTATE) bad++;
             if (mgwfbp_tune(pl, NULL, NULL, NULL) != MGWFBP_ESTATE) bad++;
+            {
+                int32_t flag = 0;
+                double t_it = 0.0;
+                int dummy_a = 0, dummy_b = 0;   /* two different stream handles; nothing is launched */
+                if (mgwfbp_gated_launch(pl, 0, 0.0f, 0.0f, 1u, 10.0, NULL) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_gated_signal(pl, 0, 1u, NULL) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_gated_gave_up(pl, &flag) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_streams_side_by_side(pl, &dummy_a, &dummy_b, &flag) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_run_iteration_gated(pl, NULL, 0, 0.0f, 0.0f, &dummy_a, &dummy_b, 10.0, &t_it) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_WGS_PER_CU, 16) != MGWFBP_EINVAL) bad++;
+                if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_WGS_PER_CU, (int)(rnd() % 15) + 1) != MGWFBP_OK) bad++;
+            }
             free(gol); free(off); free(ge); free(mu); free(gs); free(gf); free(segs); free(tl);
         }
         {
