@@ -78,6 +78,8 @@ def parse():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--small", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--skip", default="", help="comma-separated variants to leave out of --extras (under a "
+                    "profiler that runs one kernel at a time the signals of per_group_gated cannot run beside the launch)")
     ap.add_argument("--variant", default="fused", choices=VARIANTS, help="what one step runs (the headline is 'fused')")
     ap.add_argument("--tune", type=int, default=0,
                     help="1: let mgwfbp_tune pick the launch shape of the timed plans at set-up (untimed)")
@@ -216,6 +218,7 @@ def main():
             break
     else:
         wanted -= {"per_group_gated", "gated_all_arrived"}
+    wanted -= {v for v in args.skip.split(",") if v}
     for st in sets:
         st["arrival"] = 0
 
@@ -375,7 +378,7 @@ def main():
         # the headline line is complete without these: a failing extra is reported, not fatal
         try:
             for variant in VARIANTS:
-                if variant != args.variant and variant not in extra and (variant in wanted or "gated" not in variant):
+                if variant != args.variant and variant not in extra and variant in wanted:
                     extra[variant] = side_figure(variant, k2, w2)
             # the launch-per-group sequence captured once per gradient set into a HIP graph
             graphs = []
