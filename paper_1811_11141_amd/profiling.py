@@ -1,8 +1,10 @@
 """rocprofv3 runs of bench.py and the short summaries under profiles/ made from them.
 
-    python3 -m paper_1811_11141_amd.profiling run        on the MI355X machine: every rocprofv3 run below,
-                                                         raw output under gpurun_out/prof/
-    python3 -m paper_1811_11141_amd.profiling summarise  anywhere: gpurun_out/prof/ -> profiles/*.md and
+    python3 -m paper_1811_11141_amd.profiling run [all|traces|counters]
+                                                         on the MI355X machine: the rocprofv3 runs below, raw
+                                                         output under $MGWFBP_PROFILE_RAW (default
+                                                         profile_raw/ in the repository)
+    python3 -m paper_1811_11141_amd.profiling summarise  anywhere: that raw output -> profiles/*.md and
                                                          profiles/traffic.json (what bench.py reports
                                                          as roofline.traffic)
 
@@ -24,7 +26,7 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-RAW = os.path.join(ROOT, "gpurun_out", "prof")
+RAW = os.path.abspath(os.environ.get("MGWFBP_PROFILE_RAW", os.path.join(ROOT, "profile_raw")))
 PROFILES = os.path.join(ROOT, "profiles")
 QUIET = "--extras 0 --others 0 --cpu-baseline 0"
 
