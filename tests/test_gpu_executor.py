@@ -371,3 +371,65 @@ def test_streams_that_share_a_hardware_queue_are_refused(mg):
         assert time.perf_counter() - t0 < 1.0
         torch.cuda.synchronize()
         assert all(bool(torch.isnan(t).all()) for t in out)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_gated_launch_random_shapes(mg, seed):
+    """Random layer counts, sizes (tiny, around tile boundaries, mid-sized), worker counts, merge
+    sets, gather thresholds, padded layouts and misaligned pointers through the gated launch:
+    first with the groups signalled in a random order from a second stream, then as an update with
+    every group already arrived; out[], w and v against the oracle, bit for bit."""
+    rng = np.random.default_rng(7000 + seed)
+    L = int(rng.integers(1, 33))
+    sizes = []
+    for kd in rng.integers(0, 4, size=L):
+        if kd == 0:
+            sizes.append(int(rng.integers(1, 600)))
+        elif kd == 1:
+            sizes.append(max(1, int(rng.integers(1, 6)) * int(rng.choice([512, 4096])) + int(rng.integers(-5, 6))))
+        elif kd == 2:
+            sizes.append(int(rng.integers(1, 40)) * 4)
+        else:
+            sizes.append(int(rng.integers(10_000, 200_000)))
+    N = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 17]))
+    w = wl.custom_workload(sizes, N, sigma=1e-2)
+    merged = [l for l in range(2, L + 1) if rng.random() < 0.5]
+    groups = [[l - 1 for l in g] for g in op.groups_from_merged(L, merged)]
+    pl = mg.mgwfbp_plan_explicit(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, N, merged)
+    pl.set_option(mg.OPT_SMALL_ELEMS, int(rng.choice([0, 1, 64, 512, 1024])))
+    pl.set_option(mg.OPT_PAD_ELEMS, int(rng.choice([0, 0, 4, 32])))
+    pl.set_option(mg.OPT_GATED_WGS_PER_CU, int(rng.choice([-1, 1, 3, 15])))
+    misalign = bool(rng.integers(0, 2))
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+
+    def tensor(n, scale):
+        k = int(rng.integers(0, 4)) if misalign else 0
+        base = torch.empty(n + 4, dtype=torch.float32, device="cuda").normal_(0, scale, generator=gen)
+        return base[k:k + n]
+
+    grads = [[tensor(n, 1e-2) for n in sizes] for _ in range(N)]
+    out = [tensor(n, 1.0) for n in sizes]
+    wt = [tensor(n, 0.1) for n in sizes]
+    vt = [tensor(n, 1e-3) for n in sizes]
+    g_np, w_np, v_np = [to_np(r) for r in grads], to_np(wt), to_np(vt)
+    for t in out:
+        t.fill_(float("nan"))
+    pl.bind(grads, out, wt, vt)
+    exp = od.merged_gradient_path(g_np, groups)
+    s_sig, s_launch = streams_side_by_side(pl)
+    torch.cuda.synchronize()
+    pl.gated_launch(arrival=1, give_up_ms=5000.0, stream=s_launch)
+    with torch.cuda.stream(s_sig):
+        for k in rng.permutation(len(groups)):
+            pl.gated_signal(int(k), 1, stream=s_sig)
+    torch.cuda.synchronize()
+    assert not pl.gated_gave_up()
+    for l in range(L):
+        assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), (seed, l)
+    pl.gated_launch(arrival=1, update=True, lr=0.3, momentum=0.7, give_up_ms=5000.0, stream=s_launch)
+    torch.cuda.synchronize()
+    assert not pl.gated_gave_up()
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.3, 0.7)
+    for l in range(L):
+        assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), (seed, l)
+        assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32)), (seed, l)
