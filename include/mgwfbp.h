@@ -390,14 +390,17 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
  *                         update != 0 the update of w[], v[]; fused form, results as
  *                         mgwfbp_pack_reduce_unpack / mgwfbp_step with group = -1).  It starts
  *                         at once and waits on the device.  Every wait is bounded: a workgroup
- *                         that has waited give_up_ms (0 < give_up_ms <= 60000) for a group sets a
+ *                         that has waited about give_up_ms (0 < give_up_ms <= 60000; counted in
+ *                         looks at the counter, each a microsecond or more) for a group sets a
  *                         give-up word and ends, the others end at their next look at it, so the
  *                         launch always drains; tiles not yet run are then left undone.
  *                         Needs tile_elems at its default (4096).
- *   mgwfbp_gated_signal   enqueues, behind the work already in `hip_stream`, a release store of
- *                         `arrival` to the group's counter: call it on the stream that produces
- *                         the group's gradients, after the kernel that writes the lowest layer.
- *                         That stream must not be the one the launch is on, nor wait for it.
+ *   mgwfbp_gated_signal   enqueues, behind the work already in `hip_stream`, a small kernel that
+ *                         stores `arrival` to the group's counter: call it on the stream that
+ *                         produces the group's gradients, after the kernel that writes the lowest
+ *                         layer (the end of that kernel is what makes the gradients visible to the
+ *                         launch, which reads them past its own caches).  That stream must not be
+ *                         the one the launch is on, nor wait for it.
  *   mgwfbp_gated_gave_up  after the launch's stream has been waited for: *gave_up = 1 if the
  *                         last launch gave up.
  * The launch holds two workgroups per compute unit fewer than the unit can take of this kernel
@@ -413,8 +416,10 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
  *                         stream_b is still running, 0 if not (also for stream_a == stream_b).  It
  *                         finds out with a handshake of two tiny kernels (the waiting one ends by
  *                         itself after 2 ms), blocks until both streams are idle, and remembers in
- *                         the plan the pairs that passed.  The plan must be bound.  Take another
- *                         stream when a pair fails: most pairs pass.
+ *                         the plan the pairs that passed (until mgwfbp_bind is called again; a
+ *                         stream that is destroyed and created anew has to be checked anew).  The
+ *                         plan must be bound.  Take another stream when a pair fails: most pairs
+ *                         pass.
  *
  * mgwfbp_run_iteration_gated is mgwfbp_run_iteration in this form: the stand-in backward pass on
  * `compute_stream` signals each group's arrival, `comm_stream` (a different stream) holds the one
