@@ -7,6 +7,9 @@
 //   k_pack    Algorithm 2's layer buffer: each worker's layers of a group laid end to end.
 //   k_reduce  Eq. 2 over N contiguous merged buffers.
 //   k_unpack  merged buffer back to per-layer tensors (+ update of Eq. 1-2 with momentum).
+//   k_fused_gated  k_fused over the whole plan as one launch whose workgroups wait, tile by tile,
+//             for the arrival counter of the tile's group (Algorithm 2's communication thread
+//             on the device); k_signal and k_await are its helpers.
 //
 // The path is bound by HBM bandwidth (0.2-0.3 flop per byte); there is nothing for the matrix
 // cores to do.  In the reductions (k_fused, k_reduce) one workgroup of 128 lanes (2 wave64) owns
@@ -21,7 +24,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <utility>
 
 #include "../../include/mgwfbp.h"
