@@ -175,8 +175,8 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             by whole-plan launches; list 2 or 3 (when built): the whole plan in longer
  *             tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses it by default,
  *             3 if only mgwfbp_tune may select it; list 4: the whole plan group after group in
- *             communication order (mgwfbp_gated_launch), in tiles of tile_elems, groups of up
- *             to 64 Ki elements in tiles of 512.
+ *             communication order (mgwfbp_gated_launch), in tiles of 2048 or (long plans) 4096
+ *             elements whatever tile_elems is, groups of up to 64 Ki elements in tiles of 512.
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too
  *             few workgroups).
@@ -394,7 +394,6 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
  *                         looks at the counter, each a microsecond or more) for a group sets a
  *                         give-up word and ends, the others end at their next look at it, so the
  *                         launch always drains; tiles not yet run are then left undone.
- *                         Needs tile_elems at its default (4096).
  *   mgwfbp_gated_signal   enqueues, behind the work already in `hip_stream`, a small kernel that
  *                         stores `arrival` to the group's counter: call it on the stream that
  *                         produces the group's gradients, after the kernel that writes the lowest

@@ -290,10 +290,11 @@ int bind_impl(mgwfbp_plan_t *pl, const float *const *grads, float *const *out, f
     pl->has_wv = w != nullptr;
     pl->bound = true;
     for (int step = 0; step < 2; ++step)
-        if (int rc = gated_resident_per_cu(step != 0, &pl->gated_resident_per_cu[step])) {
-            release_device(pl);
-            return rc;
-        }
+        for (int lng = 0; lng < 2; ++lng)
+            if (int rc = gated_resident_per_cu(step != 0, lng != 0, &pl->gated_resident_per_cu[step][lng])) {
+                release_device(pl);
+                return rc;
+            }
     // set-up is the place for runtime queries: find this device's copy of the static workspace
     // now, so that mgwfbp_pack_reduce_unpack_static never has to ask
     if (int rc = prepare_static_workspace()) {

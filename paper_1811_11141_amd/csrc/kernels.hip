@@ -120,27 +120,37 @@ __device__ __forceinline__ T nway_mean_fixed(const float *const (&sp)[NW], uint3
 }
 
 // Loads with the device-scope bit: served from where every compute die's writes are visible
-// instead of this die's L2, for data that a kernel running at the same time produced.  The
-// 128-bit form is written as an instruction (there is no 128-bit atomic load to ask the compiler
-// for); the compiler's wait-count bookkeeping does not see it, so the results of a batch go
-// through device_loads_done() before their first use.
-__device__ __forceinline__ float ld_device(const float *p)
+// instead of this die's L2, for data that a kernel running at the same time produced.  There is
+// no 128-bit atomic load to ask the compiler for, so the 128-bit form is written as instructions;
+// the compiler's wait-count bookkeeping does not see them, so each statement ends with its own
+// wait and the values are complete when it returns.
+__device__ __forceinline__ void ld_device(const float *p, float &a)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ v4f ld_device(const v4f *p)
+__device__ __forceinline__ void ld_device(const v4f *p, v4f &a)
 {
-    v4f r;
-    asm volatile("global_load_dwordx4 %0, %1, off sc1 nt" : "=v"(r) : "v"(p));
-    return r;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(a) : "v"(p));
 }
-__device__ __forceinline__ void device_loads_done(float &, float &, float &, float &) {}
-__device__ __forceinline__ void device_loads_done(float &) {}
-__device__ __forceinline__ void device_loads_done(v4f &a, v4f &b, v4f &c, v4f &d)
+__device__ __forceinline__ void ld_device4(const float *pa, const float *pb, const float *pc, const float *pd,
+                                           float &a, float &b, float &c, float &d)
 {
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+    a = __hip_atomic_load(pa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    b = __hip_atomic_load(pb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    c = __hip_atomic_load(pc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    d = __hip_atomic_load(pd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void device_loads_done(v4f &a) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(a)); }
+__device__ __forceinline__ void ld_device4(const v4f *pa, const v4f *pb, const v4f *pc, const v4f *pd,
+                                           v4f &a, v4f &b, v4f &c, v4f &d)
+{
+    asm volatile("global_load_dwordx4 %0, %4, off sc1 nt\n\t"
+                 "global_load_dwordx4 %1, %5, off sc1 nt\n\t"
+                 "global_load_dwordx4 %2, %6, off sc1 nt\n\t"
+                 "global_load_dwordx4 %3, %7, off sc1 nt\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d)
+                 : "v"(pa), "v"(pb), "v"(pc), "v"(pd));
+}
 
 // Run-time N: `ptr(g)` yields worker g's base pointer; loads go out four at a time.
 // COH: with device-scope loads.
@@ -148,23 +158,35 @@ template <bool NT, class T, bool COH = false, class PtrFn>
 __device__ __forceinline__ T nway_mean_dyn(PtrFn ptr, int nw, uint32_t i, float inv_n)
 {
     if constexpr (COH) {
-        T acc = ld_device(reinterpret_cast<const T *>(ptr(0)) + i);
-        device_loads_done(acc);
-        int g = 1;
+        // workers 0..3 together, then 4..7, ...: N = 8 is two round trips
+        T acc;
+        int g = 0;
+        if (nw >= 4) {
+            T b, c, d;
+            ld_device4(reinterpret_cast<const T *>(ptr(0)) + i, reinterpret_cast<const T *>(ptr(1)) + i,
+                       reinterpret_cast<const T *>(ptr(2)) + i, reinterpret_cast<const T *>(ptr(3)) + i,
+                       acc, b, c, d);
+            acc = acc + b;
+            acc = acc + c;
+            acc = acc + d;
+            g = 4;
+        } else {
+            ld_device(reinterpret_cast<const T *>(ptr(0)) + i, acc);
+            g = 1;
+        }
         for (; g + 4 <= nw; g += 4) {
-            T a = ld_device(reinterpret_cast<const T *>(ptr(g)) + i);
-            T b = ld_device(reinterpret_cast<const T *>(ptr(g + 1)) + i);
-            T c = ld_device(reinterpret_cast<const T *>(ptr(g + 2)) + i);
-            T d = ld_device(reinterpret_cast<const T *>(ptr(g + 3)) + i);
-            device_loads_done(a, b, c, d);
+            T a, b, c, d;
+            ld_device4(reinterpret_cast<const T *>(ptr(g)) + i, reinterpret_cast<const T *>(ptr(g + 1)) + i,
+                       reinterpret_cast<const T *>(ptr(g + 2)) + i, reinterpret_cast<const T *>(ptr(g + 3)) + i,
+                       a, b, c, d);
             acc = acc + a;
             acc = acc + b;
             acc = acc + c;
             acc = acc + d;
         }
         for (; g < nw; ++g) {
-            T a = ld_device(reinterpret_cast<const T *>(ptr(g)) + i);
-            device_loads_done(a);
+            T a;
+            ld_device(reinterpret_cast<const T *>(ptr(g)) + i, a);
             acc = acc + a;
         }
         return acc * inv_n;
@@ -1199,10 +1221,7 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
 int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
                        uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream)
 {
-    if (pl.opt.tile_elems != 4096) {
-        set_error("the gated launch runs on 4096-element tiles (MGWFBP_OPT_TILE_ELEMS at its default)");
-        return MGWFBP_EINVAL;
-    }
+    const bool lng = pl.gated_tile_elems == 4096;  // else 2048
     hipStream_t s = static_cast<hipStream_t>(stream);
     // cleared by a kernel, not a memset: the caller may be capturing a graph
     k_signal<<<1, 64, 0, s>>>(ctl, 0u);
@@ -1212,7 +1231,7 @@ int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, c
     // this kernel (16 by wave slots; the update form's registers allow 14) and so leaves room
     // for the kernels that bump the counters: a chip filled with waiting workgroups would never
     // see a counter move.  Every workgroup gets the same number of tiles (the last pass aside).
-    const int holds = pl.gated_resident_per_cu[step ? 1 : 0];
+    const int holds = pl.gated_resident_per_cu[step ? 1 : 0][lng ? 1 : 0];
     if (holds <= kGatedReserve) {
         set_error("the gated launch needs a device that holds more than " + std::to_string(kGatedReserve) +
                   " of its workgroups per compute unit");
@@ -1226,16 +1245,26 @@ int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, c
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int pace = pl.opt.pace >= 0 ? pl.opt.pace : 2;
     const uint32_t tb = pl.ordered_tile_begin;
-    if (step) k_fused_gated<8, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
-    else k_fused_gated<8, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+    if (lng) {
+        if (step) k_fused_gated<8, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+        else k_fused_gated<8, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+    } else {
+        if (step) k_fused_gated<4, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+        else k_fused_gated<4, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+    }
     return check_launch("gated launch");
 }
 
-int gated_resident_per_cu(bool step, int *per_cu)
+int gated_resident_per_cu(bool step, bool long_tiles, int *per_cu)
 {
     int n = 0;
-    const hipError_t e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, true>, kBlock, 0)
-                              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, false>, kBlock, 0);
+    hipError_t e;
+    if (long_tiles)
+        e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, true>, kBlock, 0)
+                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, false>, kBlock, 0);
+    else
+        e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<4, true>, kBlock, 0)
+                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<4, false>, kBlock, 0);
     if (e != hipSuccess) {
         set_error(std::string("hipOccupancyMaxActiveBlocksPerMultiprocessor: ") + hipGetErrorString(e));
         return MGWFBP_EHIP;

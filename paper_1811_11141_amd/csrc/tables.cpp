@@ -140,6 +140,18 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     w_tbl.clear();
     v_tbl.clear();
 
+    // Tile length of the arrival-ordered list (the gated launch), whatever tile_elems says: its
+    // workgroups stay and walk several tiles each, so the length only sets how finely the work is
+    // dealt.  A plan that the launch covers in about two rounds of 4096-element tiles is cut into
+    // 2048-element tiles (GoogLeNet's sizes: 99 -> 80 us with every group arrived, ResNet-50's
+    // update 237 -> 227 us, its reduction 145 -> 147 us); a long plan keeps 4096 (VGG-16, N = 16:
+    // 1556 us against 1666 us, every tile pays its table loads and its store drain).
+    {
+        uint64_t total = 0;
+        for (const GroupInfo &g : pl.groups) total += g.elems;
+        const uint64_t two_rounds = 2ull * 14ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
+        pl.gated_tile_elems = (total + 4095) / 4096 <= two_rounds ? 2048u : 4096u;
+    }
     for (size_t k = 0; k < pl.groups.size(); ++k) {
         GroupInfo &g = pl.groups[k];
         g.seg_begin = static_cast<uint32_t>(pl.segs.size());
@@ -241,7 +253,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             // full tile is then a chain of N * 8 loads, each waited for (35 us for N = 8).  Cut into
             // 512-element pieces the group runs the general code instead: one 128-bit access per
             // lane and worker, four in flight.
-            g.gated_tile_elems = g.elems <= kGatedSmallGroupElems ? std::min(tile, kGatedShortTile) : tile;
+            g.gated_tile_elems = g.elems <= kGatedSmallGroupElems ? kGatedShortTile : pl.gated_tile_elems;
             std::vector<TileDev> os, of;
             cut(g.gated_tile_elems, os, of);
             ordered.insert(ordered.end(), os.begin(), os.end());

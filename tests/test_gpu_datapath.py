@@ -652,7 +652,7 @@ def test_full_size_two_halves(mg, name, per_group):
 def test_random_shapes_all_entry_points(mg, seed):
     """Random layer counts, sizes (tiny, around tile boundaries, large), worker counts, merge
     sets, tilings and pointer misalignments; every data-path entry point against the oracle
-    (the gated launch with every group arrived where the tiling allows it)."""
+    (the gated launch with every group arrived)."""
     rng = np.random.default_rng(1000 + seed)
     L = int(rng.integers(1, 41))
     tile = int(rng.choice([1024, 2048, 4096, 8192]))
@@ -704,11 +704,9 @@ def test_random_shapes_all_entry_points(mg, seed):
     for k in range(len(groups)):
         pl.pack_reduce_unpack(group=k)
     check_out("fused per group")
-    gated = tile == 4096                                      # the gated launch runs on the default tiles only
-    if gated:
-        pl.gated_launch(0)                                    # counters are at 0: every group has arrived
-        check_out("gated")
-        assert not pl.gated_gave_up()
+    pl.gated_launch(0)                                        # counters are at 0: every group has arrived
+    check_out("gated")
+    assert not pl.gated_gave_up()
     pl.pack_reduce_unpack(workspace=alloc_ws(pl))
     check_out("materialised")
     layers = [l for g in groups for l in g]
@@ -727,9 +725,8 @@ def test_random_shapes_all_entry_points(mg, seed):
     od.merged_gradient_path(g_np, groups, w_np, v_np, 0.05, 0.8)
     pl.unpack_update(mb, update=True, lr=0.2, momentum=0.5)
     od.merged_gradient_path(g_np, groups, w_np, v_np, 0.2, 0.5)
-    if gated:
-        pl.gated_launch(0, update=True, lr=0.3, momentum=0.7)
-        od.merged_gradient_path(g_np, groups, w_np, v_np, 0.3, 0.7)
+    pl.gated_launch(0, update=True, lr=0.3, momentum=0.7)
+    od.merged_gradient_path(g_np, groups, w_np, v_np, 0.3, 0.7)
     torch.cuda.synchronize()
     for l in range(L):
         assert_same(wt[l].cpu().numpy(), w_np[l], f"w layer {l} (seed {seed})")

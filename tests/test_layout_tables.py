@@ -63,14 +63,16 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
         for first, nseg, start, n, _, tlen, tpad in (tuple(int(x) for x in r) for r in sel):
             if which in (2, 3):
                 assert tlen == (8192 if long_tiles == 1 else long_tiles) and 1 <= n <= tlen
+            elif which == 4:
+                # the arrival-ordered list has tile lengths of its own, whatever tile_elems says: 512 for
+                # small groups, else 2048 while the plan is at most 2 * 14 * 256 tiles of 4096 elements
+                gsz = sum(plen(e[1]) for e in exp if e[3] == exp[first][3])
+                assert tlen == (512 if gsz <= 64 * 1024 else (2048 if -(-P // 4096) <= 7168 else 4096))
+                assert 1 <= n <= max(tlen, min(tile, 1024), small_eff)
             else:
                 assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"
                 # a group's own list may use shorter tiles than the whole-plan list, never longer
-                if which == 4:   # the arrival-ordered list cuts small groups into 512-element pieces
-                    gsz = sum(plen(e[1]) for e in exp if e[3] == exp[first][3])
-                    assert tlen == (min(tile, 512) if gsz <= 64 * 1024 else tile)
-                else:
-                    assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
+                assert tlen in (tile, tile // 2, tile // 4) and tlen >= 1024 and (which == 0 or tlen == tile)
             assert 1 <= nseg <= 256
             if nseg == 1:
                 lyr, sn, soff, grp = exp[first]
