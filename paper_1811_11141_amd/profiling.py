@@ -1,6 +1,6 @@
 """rocprofv3 runs of bench.py and the short summaries under profiles/ made from them.
 
-    python3 -m paper_1811_11141_amd.profiling run [all|traces|counters]
+    python3 -m paper_1811_11141_amd.profiling run [all|traces|counters] [variant]
                                                          on the MI355X machine: the rocprofv3 runs below, raw
                                                          output under $MGWFBP_PROFILE_RAW (default
                                                          profile_raw/ in the repository)
@@ -116,8 +116,10 @@ def _prune(out_dir: str) -> None:
             os.remove(p)
 
 
-def run(part: str = "all") -> None:
+def run(part: str = "all", only: str = "") -> None:
     for wl_tag, variant, steps in (TRACES if part in ("all", "traces") else []):
+        if only and variant != only:
+            continue
         out = os.path.join(RAW, f"trace_{wl_tag}_{variant}")
         args = bench_args(wl_tag, variant, steps)
         # the unprofiled figure of the same command on the same box, for comparison
@@ -261,6 +263,6 @@ def summarise() -> None:
 if __name__ == "__main__":
     # run [all|traces|counters] on the GPU machine, summarise anywhere
     if len(sys.argv) > 1 and sys.argv[1] == "run":
-        run(sys.argv[2] if len(sys.argv) > 2 else "all")
+        run(sys.argv[2] if len(sys.argv) > 2 else "all", sys.argv[3] if len(sys.argv) > 3 else "")
     else:
         summarise()

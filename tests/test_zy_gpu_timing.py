@@ -16,7 +16,7 @@ enqueued operations is enough to move any of these by that much.
   * a replayed iteration graph ends at most 0.2 ms after its backward pass and within 0.2 ms of
     the eager schedule (measured 8-11 us and 4-8 us);
   * the iteration with the communication side as one gated launch ends at most 0.2 ms after its
-    backward pass (measured 8.7 us on the ResNet-50 and GoogLeNet sets; 15.5 us with a launch per
+    backward pass (measured 5.7 us on the ResNet-50 and GoogLeNet sets; 15.5 us with a launch per
     group);
   * tuning may not make the pass more than 10 % slower (repeated timings of one launch shape
     scatter by 2-4 % between runs, the candidates differ from each other by 1-5 %);
