@@ -107,9 +107,9 @@ struct mgwfbp_plan_s {
     // third list: the whole plan cut into longer tiles, for the fused reduce pass when that fills
     // the chip's batches of workgroups better (0 tiles = not built)
     uint32_t long_tile_begin = 0, long_tile_count = 0, long_tile_elems = 0;
-    // fourth list: the whole plan in full-length tiles, group after group in communication order
-    // (inside a group slow tiles first), for the single gated launch that walks the groups in the
-    // order their gradients arrive
+    // fourth list: the whole plan group after group in communication order (inside a group slow
+    // tiles first), in tiles of its own length (gated_tile_elems; small groups 512), for the
+    // single gated launch that walks the groups in the order their gradients arrive
     uint32_t ordered_tile_begin = 0, ordered_tile_count = 0;
     uint32_t gated_tile_elems = 4096;  // full-tile length of that list: 2048 or 4096
     std::vector<const float *> host_src;  // host copies of the bound pointers (alias checks)
