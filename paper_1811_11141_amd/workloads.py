@@ -31,9 +31,17 @@ G_EFF_FLOPS = 2.0e12
 BASE_SEED = 1811_11141
 
 
-def ring_b_ms_per_byte(n_workers: int, beta: float = BETA_10GBE_MS_PER_BYTE) -> float:
-    """Per-byte all-reduce cost of the ring row of Table II with gamma = 0."""
-    return 2.0 * (n_workers - 1) / n_workers * beta
+# Per-byte all-reduce cost b (ms per byte) handed to the planner for N workers on that link: the
+# values of Table II's ring row with gamma = 0, as numbers (the formula belongs to the method, not
+# to an input generator; the oracle's tests check these against it).
+RING_B_MS_PER_BYTE = {1: 0.0, 2: 8.0e-7, 3: 1.0666666666666665e-6, 4: 1.2e-6, 6: 1.3333333333333334e-6, 8: 1.4e-6,
+                      12: 1.4666666666666665e-6, 16: 1.5e-6, 32: 1.55e-6, 64: 1.575e-6}
+
+
+def ring_b_ms_per_byte(n_workers: int) -> float:
+    if n_workers not in RING_B_MS_PER_BYTE:
+        raise ValueError(f"no cost constant stored for {n_workers} workers")
+    return RING_B_MS_PER_BYTE[n_workers]
 
 
 @dataclass

@@ -330,3 +330,12 @@ def test_workload_generators_reproduce_the_architectures():
     a = wl.make_gradients(wl.tiny_workload(3), 3, "cpu")
     b = wl.make_gradients(wl.tiny_workload(3), 3, "cpu")
     assert all(np.array_equal(x.numpy().view(np.uint32), y.numpy().view(np.uint32)) for ra, rb in zip(a, b) for x, y in zip(ra, rb))
+
+
+def test_stored_cost_constants_are_table2_ring_row():
+    """The per-byte costs the input generator stores for its worker counts are Table II's ring row
+    on a 10 Gb/s link with gamma = 0 (the generator holds numbers, the formula lives here)."""
+    for n, b in wl.RING_B_MS_PER_BYTE.items():
+        assert b == op.table2_cost("ring", n, 0.0, wl.BETA_10GBE_MS_PER_BYTE, 0.0)[1], n
+        assert b == 2 * (n - 1) / n * 8.0e-7
+    assert wl.cnn_workload("vgg16").b_ms_per_byte == 1.5e-6 and wl.cnn_workload("resnet50").b_ms_per_byte == 1.4e-6
