@@ -12,7 +12,9 @@
    Algorithm 2 on two streams with timed stand-ins for the backward pass) for the no-merging,
    single-group, Theorem-1 and optimal plans, and compare the measured end of the last group
    with the iteration time the model predicts (Eq. 8); the same iteration is also replayed
-   from a HIP graph (mgwfbp_iteration_capture).
+   from a HIP graph (mgwfbp_iteration_capture) and run with the communication side as one gated
+   launch (mgwfbp_run_iteration_gated).  calibrate_arrival() fits Eq. 9 to one message that
+   arrives alone, for the launch per group and for the gated launch.
 
 3. Scaling (--scaling): the trace-based simulation of Section V-C on the synthetic traces.
 
@@ -113,6 +115,51 @@ def calibrate_in_schedule(workload: str = "resnet50", device: str = "cuda:0", re
             "rms_residual_ms": float(np.sqrt(np.mean(resid ** 2)))}
 
 
+def _stream_pair(pl, device, tries: int = 8):
+    """Two streams whose kernels the device runs at the same time (the gated launch needs that)."""
+    import torch
+
+    for _ in range(tries):
+        a, b = torch.cuda.Stream(device=device), torch.cuda.Stream(device=device)
+        if pl.streams_side_by_side(a, b):
+            return a, b
+    raise RuntimeError("no pair of streams ran side by side")
+
+
+def calibrate_arrival(n_workers: int = 8, device: str = "cuda:0", reps: int = 7,
+                      sizes=(1 << 10, 1 << 12, 1 << 14, 1 << 16, 1 << 18, 1 << 20, 1 << 21, 1 << 22, 1 << 23)):
+    """Eq. 9 for one message that arrives alone: a one-layer net of p parameters, a 0.3 ms backward
+    pass, and the time from the end of that pass to the end of the iteration, for the launch per
+    group (mgwfbp_run_iteration) and for the gated launch (mgwfbp_run_iteration_gated).  Fits
+    (a, b) to each: a is what a message costs however small it is."""
+    import torch
+
+    from . import binding as mg
+    from . import workloads as wl
+
+    tb = np.array([0.3])
+    nbytes, launch, gated = [], [], []
+    for p in sizes:
+        w = wl.custom_workload([int(p)], n_workers, tb_ms=tb)
+        grads = wl.make_gradients(w, 11, device)
+        pl = mg.mgwfbp_plan(w.p, tb, 0.0, w.a_ms, w.b_ms_per_byte, n_workers, mg.MODE_SINGLE)
+        pl.bind(grads, [torch.empty_like(t) for t in grads[0]])
+        s_comp, s_comm = _stream_pair(pl, device)
+        pl.run_iteration(s_comp, s_comm, timeline=False)
+        pl.run_iteration_gated(s_comp, s_comm)
+        t_l = [pl.run_iteration(s_comp, s_comm, timeline=False)["t_iter_ms"] for _ in range(reps)]
+        t_g = [pl.run_iteration_gated(s_comp, s_comm) for _ in range(reps)]
+        nbytes.append(4.0 * p)
+        launch.append(float(np.median(t_l)) - 0.3)
+        gated.append(float(np.median(t_g)) - 0.3)
+        pl.destroy()
+    out = {"n_workers": n_workers, "message_bytes": nbytes}
+    for name, ms in (("launch_per_group", launch), ("gated_launch", gated)):
+        a, b = mg.mgwfbp_fit_cost(np.array(nbytes), np.array(ms))
+        out[name] = {"after_arrival_ms": ms, "a_ms": a, "b_ms_per_byte": b}
+    return out
+
+
 def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: float = 5.0,
              device: str = "cuda:0", reps: int = 5):
     """Predicted (Eq. 8 with the given a, b) and measured iteration times of four plans.
@@ -126,14 +173,20 @@ def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: floa
 
     w = wl.cnn_workload(workload)
     tb = w.tb_ms * (backward_ms / w.tb_ms.sum())
-    s_comp, s_comm = torch.cuda.Stream(device=device), torch.cuda.Stream(device=device)
+    s_comp = s_comm = None
     out = {"workload": workload, "a_ms": a_ms, "b_ms_per_byte": b_ms_per_byte,
            "backward_ms": backward_ms, "plans": {}}
     for name, mode in (("wfbp", mg.MODE_WFBP), ("single", mg.MODE_SINGLE),
                        ("theorem1", mg.MODE_PAPER_GREEDY), ("optimal", mg.MODE_OPTIMAL)):
         pl = _bound_plans(mg, wl, w, mode, a_ms, b_ms_per_byte, tb, 1, device)[0]
+        if s_comp is None:
+            s_comp, s_comm = _stream_pair(pl, device)
+        elif not pl.streams_side_by_side(s_comp, s_comm):     # remembered per plan: a handshake of 20 us
+            raise RuntimeError("the stream pair stopped running side by side")
         pl.run_iteration(s_comp, s_comm)                      # warm-up
+        pl.run_iteration_gated(s_comp, s_comm)
         t = [pl.run_iteration(s_comp, s_comm) for _ in range(reps)]
+        gated = np.array([pl.run_iteration_gated(s_comp, s_comm) for _ in range(reps)])
         light = np.array([pl.run_iteration(s_comp, s_comm, timeline=False)["t_iter_ms"] for _ in range(reps)])
         it = pl.capture_iteration(s_comp, s_comm)
         it.replay(s_comp)                                     # warm-up
@@ -146,6 +199,7 @@ def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: floa
                               "measured_t_iter_ms": float(np.median(meas)),
                               "measured_t_iter_without_timestamps_ms": float(np.median(light)),
                               "measured_t_iter_graph_replay_ms": float(np.median(graph)),
+                              "measured_t_iter_gated_launch_ms": float(np.median(gated)),
                               "measured_backward_ms": float(np.median(bwd)),
                               "not_overlapped_ms": float(np.median(meas - bwd))}
         pl.destroy()
@@ -187,7 +241,8 @@ def main():
     cal = calibrate(args.workload)
     cal2 = calibrate_in_schedule(args.workload)
     sched = [schedule(args.workload, cal2["a_ms"], cal2["b_ms_per_byte"], t) for t in args.backward_ms]
-    print(json.dumps({"calibration_back_to_back": cal, "calibration_in_schedule": cal2, "schedule": sched}))
+    print(json.dumps({"calibration_back_to_back": cal, "calibration_in_schedule": cal2,
+                      "calibration_one_message_after_arrival": calibrate_arrival(), "schedule": sched}))
 
 
 if __name__ == "__main__":
