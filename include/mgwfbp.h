@@ -175,7 +175,7 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *plan, int32_t key, int64_t value);
  *             by whole-plan launches; list 2 or 3 (when built): the whole plan in longer
  *             tiles (MGWFBP_OPT_LONG_TILES), 2 if the fused reduce pass uses it by default,
  *             3 if only mgwfbp_tune may select it; list 4: the whole plan group after group in
- *             communication order (mgwfbp_gated_launch), in tiles of 2048 or (long plans) 4096
+ *             communication order (mgwfbp_gated_launch), in tiles of 1024 or (long plans) 4096
  *             elements whatever tile_elems is, groups of up to 64 Ki elements in tiles of 512.
  *             tile length: elements of a full tile in that list (a group launched alone is
  *             cut into shorter tiles than the whole plan when it would otherwise give too

@@ -1221,7 +1221,7 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
 int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
                        uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream)
 {
-    const bool lng = pl.gated_tile_elems == 4096;  // else 2048
+    const bool lng = pl.gated_tile_elems == 4096;  // else 1024
     hipStream_t s = static_cast<hipStream_t>(stream);
     // cleared by a kernel, not a memset: the caller may be capturing a graph
     k_signal<<<1, 64, 0, s>>>(ctl, 0u);
@@ -1249,8 +1249,8 @@ int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, c
         if (step) k_fused_gated<8, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
         else k_fused_gated<8, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
     } else {
-        if (step) k_fused_gated<4, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
-        else k_fused_gated<4, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+        if (step) k_fused_gated<2, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
+        else k_fused_gated<2, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
     }
     return check_launch("gated launch");
 }
@@ -1263,8 +1263,8 @@ int gated_resident_per_cu(bool step, bool long_tiles, int *per_cu)
         e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, true>, kBlock, 0)
                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<8, false>, kBlock, 0);
     else
-        e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<4, true>, kBlock, 0)
-                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<4, false>, kBlock, 0);
+        e = step ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<2, true>, kBlock, 0)
+                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_fused_gated<2, false>, kBlock, 0);
     if (e != hipSuccess) {
         set_error(std::string("hipOccupancyMaxActiveBlocksPerMultiprocessor: ") + hipGetErrorString(e));
         return MGWFBP_EHIP;

@@ -111,7 +111,7 @@ struct mgwfbp_plan_s {
     // tiles first), in tiles of its own length (gated_tile_elems; small groups 512), for the
     // single gated launch that walks the groups in the order their gradients arrive
     uint32_t ordered_tile_begin = 0, ordered_tile_count = 0;
-    uint32_t gated_tile_elems = 4096;  // full-tile length of that list: 2048 or 4096
+    uint32_t gated_tile_elems = 4096;  // full-tile length of that list: 1024 or 4096
     std::vector<const float *> host_src;  // host copies of the bound pointers (alias checks)
     std::vector<float *> host_out;
     bool long_by_default = false;  // the rule (or the option) says to use it
@@ -133,7 +133,7 @@ struct mgwfbp_plan_s {
     uint64_t *d_clock = nullptr;
     // behind them, for the gated launch: one arrival counter per group and the give-up word
     uint32_t *d_ready = nullptr, *d_gave_up = nullptr;
-    // workgroups of the gated kernel a compute unit holds: [reduce, update][2048-, 4096-element tiles]
+    // workgroups of the gated kernel a compute unit holds: [reduce, update][1024-, 4096-element tiles]
     int gated_resident_per_cu[2][2] = {{0, 0}, {0, 0}};
     uint32_t gated_epoch = 0;  // arrival number the executor used last
     // and two words for the handshake that shows whether two streams' kernels run at the same time
@@ -236,7 +236,7 @@ int launch_unpack(const mgwfbp_plan_t &pl, const LaunchScope &sc, const float *r
 // ctl: the plan's give-up word; a small kernel in front of the launch clears it.
 int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
                        uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream);
-// How many workgroups of the gated kernel (update form or not, 4096- or 2048-element tiles) one
+// How many workgroups of the gated kernel (update form or not, 4096- or 1024-element tiles) one
 // compute unit of the current device holds.
 int gated_resident_per_cu(bool step, bool long_tiles, int *per_cu);
 // Sets *counter = epoch (device scope, release) behind the work already in the stream.

@@ -142,15 +142,20 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
 
     // Tile length of the arrival-ordered list (the gated launch), whatever tile_elems says: its
     // workgroups stay and walk several tiles each, so the length only sets how finely the work is
-    // dealt.  A plan that the launch covers in about two rounds of 4096-element tiles is cut into
-    // 2048-element tiles (GoogLeNet's sizes: 99 -> 80 us with every group arrived, ResNet-50's
-    // update 237 -> 227 us, its reduction 145 -> 147 us); a long plan keeps 4096 (VGG-16, N = 16:
-    // 1556 us against 1666 us, every tile pays its table loads and its store drain).
+    // dealt and how long a tile that is alone on the chip takes (a full tile is a chain of N * U
+    // loads, each waited for).  A plan that the launch covers in about two rounds of 4096-element
+    // tiles is cut into 1024-element tiles (GoogLeNet's sizes against 4096: 99 -> 81 us with every
+    // group arrived, ResNet-50's update 237 -> 225 us, its reduction 145 -> 148 us; a 4 MB message
+    // that arrives alone is done after 13 us instead of 22 us with 2048); a long plan keeps 4096
+    // (VGG-16, N = 16: 1556 us against 1666 us with 2048, every tile pays its table loads and its
+    // store drain).  One length per plan: the tiles are dealt by count, and a mix of lengths leaves
+    // the workgroups with unequal shares (AlexNet's sizes with two of four groups in 1024-element
+    // tiles: 339 -> 361 us).
     {
         uint64_t total = 0;
         for (const GroupInfo &g : pl.groups) total += g.elems;
         const uint64_t two_rounds = 2ull * 14ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
-        pl.gated_tile_elems = (total + 4095) / 4096 <= two_rounds ? 2048u : 4096u;
+        pl.gated_tile_elems = (total + 4095) / 4096 <= two_rounds ? 1024u : 4096u;
     }
     for (size_t k = 0; k < pl.groups.size(); ++k) {
         GroupInfo &g = pl.groups[k];

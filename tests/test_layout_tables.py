@@ -65,9 +65,9 @@ def check_layout(p, merged, tile, small, long_tiles=-1, pad=0):
                 assert tlen == (8192 if long_tiles == 1 else long_tiles) and 1 <= n <= tlen
             elif which == 4:
                 # the arrival-ordered list has tile lengths of its own, whatever tile_elems says: 512 for
-                # small groups, else 2048 while the plan is at most 2 * 14 * 256 tiles of 4096 elements
+                # small groups, else 1024 while the plan is at most 2 * 14 * 256 tiles of 4096 elements
                 gsz = sum(plen(e[1]) for e in exp if e[3] == exp[first][3])
-                assert tlen == (512 if gsz <= 64 * 1024 else (2048 if -(-P // 4096) <= 7168 else 4096))
+                assert tlen == (512 if gsz <= 64 * 1024 else (1024 if -(-P // 4096) <= 7168 else 4096))
                 assert 1 <= n <= max(tlen, min(tile, 1024), small_eff)
             else:
                 assert 1 <= n <= tile, "no tile exceeds tile_elems (the LDS staging size)"

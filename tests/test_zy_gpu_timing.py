@@ -155,7 +155,7 @@ def test_calibrated_schedule_ranks_plans_like_the_model(mg):
 
 def test_a_message_that_arrives_alone_is_done_sooner_in_the_gated_launch(mg):
     """Eq. 9 fitted to single messages after their arrival: the start-up term of the gated launch is
-    below that of a launch per group (measured 4-5 us against 14-15 us for messages up to 256 KB)."""
+    below that of a launch per group (measured 4.6-7.5 us against 15-16.5 us for messages up to 2 MB)."""
     from paper_1811_11141_amd import experiments as ex
 
     c = ex.calibrate_arrival(reps=5, sizes=(1 << 10, 1 << 13, 1 << 16))
