@@ -436,3 +436,54 @@ def test_gated_launch_random_shapes(mg, seed):
     for l in range(L):
         assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), (seed, l)
         assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32)), (seed, l)
+
+
+@pytest.mark.parametrize("update", [False, True])
+def test_gated_launch_reads_what_the_producer_wrote_while_it_was_waiting(mg, update):
+    """The pattern the gated launch exists for: it is already running (and waiting) when the
+    gradients of a group are produced on another stream, and it must read those values, not what
+    the tensors held when it started.  The tensors hold NaN until, group by group in a random
+    order, a copy kernel on the signalling stream fills them and the group is signalled: a tile
+    that ran before its signal, or read a line cached from before, would leave NaN behind."""
+    rng = np.random.default_rng(99 + int(update))
+    sizes = [70001, 5, 4096 * 3, 300, 9000, 64, 12289, 300000, 1024 * 7, 513]
+    N = 4
+    w = wl.custom_workload(sizes, N, sigma=1e-2)
+    merged = [10, 8, 7, 4, 3]
+    groups = [[l - 1 for l in g] for g in op.groups_from_merged(w.L, merged)]
+    pl = mg.mgwfbp_plan_explicit(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, N, merged)
+    fresh = wl.make_gradients(w, 31, "cuda")
+    grads = [[torch.full_like(t, float("nan")) for t in rep] for rep in fresh]
+    out = [torch.full_like(t, float("nan")) for t in fresh[0]]
+    wt, vt = wl.make_weights(w, 31, "cuda")
+    for t in vt:
+        t.normal_(0, 1e-3)
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    s_sig, s_launch = streams_side_by_side(pl)
+    for arrival in (1, 2):                                    # the second pass finds the first one's values in place
+        for rep in grads:
+            for t in rep:
+                t.fill_(float("nan"))
+        for t in out:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        pl.gated_launch(arrival=arrival, update=update, lr=0.1, momentum=0.9, give_up_ms=5000.0, stream=s_launch)
+        with torch.cuda.stream(s_sig):
+            for k in rng.permutation(len(groups)):
+                torch.cuda._sleep(100_000)                    # the launch is waiting by now
+                for l in groups[int(k)]:
+                    for g in range(N):
+                        grads[g][l].copy_(fresh[g][l])
+                pl.gated_signal(int(k), arrival, stream=s_sig)
+        torch.cuda.synchronize()
+        assert not pl.gated_gave_up()
+        exp = od.merged_gradient_path([to_np(r) for r in fresh], groups)
+        for l in range(w.L):
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), (arrival, l)
+        if update:
+            od.merged_gradient_path([to_np(r) for r in fresh], groups, w_np, v_np, 0.1, 0.9)
+            for l in range(w.L):
+                assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), (arrival, l)
+                assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32)), (arrival, l)
+        fresh = wl.make_gradients(w, 32 + arrival, "cuda")     # other values for the next pass
