@@ -1158,12 +1158,14 @@ enum class Stream { reduce, update };
 int pace_for(const mgwfbp_plan_t &pl, Stream kind, uint64_t workgroups)
 {
     if (pl.opt.pace >= 0) return pl.opt.pace;
+    // the steps were found on 256 compute units at 6656, 7680 and 8192 workgroups: 26, 30 and 32 per unit
+    const uint64_t cus = static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
     switch (kind) {
     case Stream::reduce:
-        if (workgroups < 6656) return 2;
+        if (workgroups < 26 * cus) return 2;
         if (pl.N >= 16) return 8;
-        return workgroups < 7680 ? 8 : 12;
-    default: return workgroups < 8192 ? 2 : pl.N >= 16 ? 4 : 8;
+        return workgroups < 30 * cus ? 8 : 12;
+    default: return workgroups < 32 * cus ? 2 : pl.N >= 16 ? 4 : 8;
     }
 }
 }  // namespace
@@ -1196,9 +1198,10 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const bool nt = pl.opt.nontemporal != 0;
     const int u = static_cast<int>(sc.tile_elems / (kBlock * 4));  // float4 per lane per worker
-    // 256 CUs x 4 SIMDs x 8 waves = 8192 wave slots = 4096 workgroups; below about half of that
-    // the launch cannot saturate HBM with one load per wave and is bound by latency instead
-    const bool deep = sc.n_tiles < 2048;
+    // a compute unit has 4 SIMDs x 8 waves = 32 wave slots = 16 workgroups; below about half of
+    // that over the whole chip the launch cannot saturate HBM with one load per wave and is bound
+    // by latency instead
+    const bool deep = sc.n_tiles < 8u * static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
     // the update runs on one tile length; what it can choose per launch is the workgroups per CU
     const uint32_t occupancy_lds = step && !sc.occupancy_lds && nt && u == 8
         ? update_occupancy_lds(pl.N, pl.n_cus, pl.lds_per_cu, sc.n_tiles, pl.opt.update_wgs_per_cu)
@@ -1323,7 +1326,7 @@ int launch_reduce(const mgwfbp_plan_t &pl, const LaunchScope &sc, float *ws, uin
     const dim3 grid(static_cast<uint32_t>((sc.elems + tile - 1) / tile));
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int u = static_cast<int>(tile / (kBlock * 4));
-    const bool deep = grid.x < 2048;
+    const bool deep = grid.x < 8u * static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
     const int pace = pace_for(pl, Stream::reduce, grid.x);
     const bool nt = pl.opt.nontemporal != 0;
     switch (pl.N) {

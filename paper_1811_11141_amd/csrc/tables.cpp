@@ -53,8 +53,8 @@ int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTil
     int best = 0;
     double best_eff = 0.0;
     for (int c = 0; c < kTileChoices; ++c) {
-        // a launch of fewer than 2048 workgroups is too short to stream: not a candidate
-        if (c > 0 && workgroups[c] < 2048) break;
+        // a launch of fewer than 8 workgroups per compute unit is too short to stream: not a candidate
+        if (c > 0 && workgroups[c] < 8ull * static_cast<uint64_t>(n_cus)) break;
         const uint64_t resident = static_cast<uint64_t>(fused_workgroups_per_cu(n_workers, kTileChoice[c])) * n_cus;
         const double eff = launch_fill_efficiency(workgroups[c], resident, n_cus);
         // a longer tile must promise at least 2 % to replace a shorter one
@@ -82,7 +82,11 @@ int best_tile_choice(int n_workers, int n_cus, const uint64_t (&workgroups)[kTil
 uint32_t update_occupancy_lds(int n_workers, int n_cus, uint32_t lds_per_cu, uint64_t workgroups,
                               int forced_per_cu)
 {
-    if (lds_per_cu != 160u * 1024u) return 0;  // the byte counts below are for this LDS size
+    // The byte counts below are measured ones for this LDS size.  Asking the runtime's occupancy
+    // calculator for them instead was tried: the counts it named for 10 and for 9 workgroups per
+    // unit ran at identical speed, and the rule built on them chose worse shapes than none (a
+    // tensor of 5002 tiles: 201 us against 181 us uncapped and 170 us at a true 11 per unit).
+    if (lds_per_cu != 160u * 1024u) return 0;
     if (forced_per_cu == 0) return 0;
     if (forced_per_cu > 0) {
         switch (forced_per_cu) {
@@ -94,7 +98,8 @@ uint32_t update_occupancy_lds(int n_workers, int n_cus, uint32_t lds_per_cu, uin
         }
     }
     if (n_workers != 1 && n_workers != 2 && n_workers != 4 && n_workers != 8 && n_workers != 16) return 0;
-    if (workgroups < 2048 || n_cus <= 0) return 0;  // short launches run the deeper-pipelined kernel
+    // short launches (under 8 workgroups per compute unit) run the deeper-pipelined kernel
+    if (n_cus <= 0 || workgroups < 8ull * static_cast<uint64_t>(n_cus)) return 0;
     struct Choice { int per_cu; uint32_t lds; double peak; };
     const Choice choices[] = {{n_workers >= 16 ? 12 : 14, 0, 1.0}, {11, 11000, 1.0}, {10, 12500, 0.985},
                               {9, 14000, 0.955}, {8, 16000, 0.915}};
@@ -157,6 +162,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
         const uint64_t two_rounds = 2ull * 14ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
         pl.gated_tile_elems = (total + 4095) / 4096 <= two_rounds ? 1024u : 4096u;
     }
+    const uint64_t short_launch = 8ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);  // workgroups
     for (size_t k = 0; k < pl.groups.size(); ++k) {
         GroupInfo &g = pl.groups[k];
         g.seg_begin = static_cast<uint32_t>(pl.segs.size());
@@ -238,13 +244,13 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
                 (t.nseg == 1 && t.n == tile_len ? full : slow).push_back(t);
             }
         };
-        // A launch of this group alone is short: below about 2048 workgroups it cannot fill the
-        // chip and every wave's chain of dependent loads decides its duration, so the group's
-        // own list uses shorter tiles (more workgroups, shorter chains) while the whole-plan
-        // list keeps the long tiles that stream best.
+        // A launch of this group alone is short: below about 8 workgroups per compute unit (half
+        // the chip's wave slots) it cannot fill the chip and every wave's chain of dependent loads
+        // decides its duration, so the group's own list uses shorter tiles (more workgroups,
+        // shorter chains) while the whole-plan list keeps the long tiles that stream best.
         g.tile_elems = tile;
         while (g.tile_elems >= 2048 && (g.tile_elems / 2) % 1024 == 0 && g.tile_elems > tile / 4 &&
-               (g.elems + g.tile_elems - 1) / g.tile_elems < 2048)
+               (g.elems + g.tile_elems - 1) / g.tile_elems < short_launch)
             g.tile_elems /= 2;
         std::vector<TileDev> slow, full;
         cut(g.tile_elems, slow, full);
@@ -292,7 +298,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
             pl.long_by_default = pick != 0;
             if (pick == 0) {  // nothing beats 4096: keep the best of the others for the tuner
                 double best_eff = 0.0;
-                for (int c = 1; c < kTileChoices && counts[c] >= 2048; ++c) {
+                for (int c = 1; c < kTileChoices && counts[c] >= short_launch; ++c) {
                     const uint64_t res = static_cast<uint64_t>(fused_workgroups_per_cu(pl.N, kTileChoice[c])) * pl.n_cus;
                     const double eff = launch_fill_efficiency(counts[c], res, pl.n_cus);
                     if (eff > best_eff) {

@@ -287,5 +287,6 @@ def test_update_kernel_occupancy_rule(tmp_path):
     for per_cu, lds in ((11, 11000), (10, 12500), (9, 14000), (8, 16000)):
         assert set(_launch_rules(tmp_path, "update", 8, 256, KB160, per_cu, *sizes).values()) == {lds}
     # a chip with half the compute units reaches the same fill with half the workgroups
-    half = _launch_rules(tmp_path, "update", 8, 128, KB160, -1, 2001, 2251, 2501, 3001, 3251)
+    half = _launch_rules(tmp_path, "update", 8, 128, KB160, -1, 1023, 2001, 2251, 2501, 3001, 3251)
     assert half[2501] == r8[5002] and half[3001] == r8[6002] and half[3251] == r8[6502]
+    assert half[1023] == 0 and half[2001] == r8[4002]       # "short" is 8 workgroups per compute unit
