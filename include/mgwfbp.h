@@ -93,9 +93,9 @@ enum {
                                    0: whatever the kernel's registers allow (14; 12 for N = 16);
                                    8, 9, 10, 11: that many.  Results do not depend on it            */
     MGWFBP_OPT_GATED_WGS_PER_CU = 8 /* workgroups per compute unit in mgwfbp_gated_launch, which
-                                   stay for the whole launch: -1 (default) two fewer than a unit
-                                   holds, or 1 .. 15 (never more than that default): the rest is
-                                   room for the kernels that signal                                 */
+                                   stay for the whole launch: -1 (default) four fewer than a unit
+                                   holds, or 1 .. 15 (never more than two fewer than it holds):
+                                   the rest is room for the kernels that produce the gradients     */
 };
 
 /*
@@ -402,10 +402,17 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
  *                         the one the launch is on, nor wait for it.
  *   mgwfbp_gated_gave_up  after the launch's stream has been waited for: *gave_up = 1 if the
  *                         last launch gave up.
- * The launch holds two workgroups per compute unit fewer than the unit can take of this kernel
- * (16; 14 with update != 0), or fewer still with MGWFBP_OPT_GATED_WGS_PER_CU, so that the kernels
- * that produce gradients and bump counters find room on the chip while it waits; each workgroup
- * walks its share of the tiles.  One gated launch per plan at a time.
+ *   mgwfbp_gated_workgroups  how many workgroups the launch would use now, and how many of them a
+ *                         compute unit holds at most (either pointer may be NULL; 0 workgroups:
+ *                         the device holds too few of them).
+ * By default the launch holds four workgroups per compute unit fewer than the unit can take of
+ * this kernel (16; 14 with update != 0), another number with MGWFBP_OPT_GATED_WGS_PER_CU (never
+ * less than two free), so that the kernels that produce gradients and bump counters find room
+ * on the chip while it waits; each workgroup walks its share of the tiles.  The default leaves
+ * room for kernels with workgroups of 256 lanes and moderate register use.  A kernel that needs
+ * whole SIMDs (a matrix-core GEMM using every register) is not placed while the launch has
+ * workgroups on every compute unit, and a host call that synchronises the device blocks behind
+ * it: the launch then gives up after give_up_ms.  One gated launch per plan at a time.
  *
  * The signalling kernels must be able to run WHILE the launch is running.  The runtime serves its
  * streams from a few hardware queues (four by default), and two streams that share a queue run
@@ -432,6 +439,7 @@ int mgwfbp_gated_launch(mgwfbp_plan_t *plan, int32_t update, float lr, float mom
                         double give_up_ms, void *hip_stream);
 int mgwfbp_gated_signal(mgwfbp_plan_t *plan, int32_t group, uint32_t arrival, void *hip_stream);
 int mgwfbp_gated_gave_up(mgwfbp_plan_t *plan, int32_t *gave_up);
+int mgwfbp_gated_workgroups(mgwfbp_plan_t *plan, int32_t update, uint32_t *workgroups, uint32_t *per_compute_unit);
 int mgwfbp_streams_side_by_side(mgwfbp_plan_t *plan, void *stream_a, void *stream_b, int32_t *side_by_side);
 int mgwfbp_run_iteration_gated(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                                float momentum, void *compute_stream, void *comm_stream,

@@ -30,7 +30,8 @@ EXPORTS = [
     "mgwfbp_pack_reduce_unpack", "mgwfbp_step", "mgwfbp_pack", "mgwfbp_reduce", "mgwfbp_unpack",
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update", "mgwfbp_pack_reduce_unpack_static",
     "mgwfbp_run_iteration", "mgwfbp_run_iteration_streams", "mgwfbp_run_iteration_gated",
-    "mgwfbp_gated_launch", "mgwfbp_gated_signal", "mgwfbp_gated_gave_up", "mgwfbp_streams_side_by_side", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
+    "mgwfbp_gated_launch", "mgwfbp_gated_signal", "mgwfbp_gated_gave_up", "mgwfbp_gated_workgroups",
+    "mgwfbp_streams_side_by_side", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
     "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
@@ -87,6 +88,7 @@ def _load() -> C.CDLL:
     lib.mgwfbp_gated_launch.argtypes = [vp, i32, f32, f32, C.c_uint32, f64, vp]
     lib.mgwfbp_gated_signal.argtypes = [vp, i32, C.c_uint32, vp]
     lib.mgwfbp_gated_gave_up.argtypes = [vp, P(i32)]
+    lib.mgwfbp_gated_workgroups.argtypes = [vp, i32, P(C.c_uint32), P(C.c_uint32)]
     lib.mgwfbp_streams_side_by_side.argtypes = [vp, vp, vp, P(i32)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_read.argtypes = [vp, u64, vp, vp]
@@ -332,6 +334,12 @@ class Plan:
         g = C.c_int32()
         _check(_lib.mgwfbp_gated_gave_up(self._h, C.byref(g)))
         return bool(g.value)
+
+    def gated_workgroups(self, update: bool = False):
+        """(workgroups of the gated launch, at most that many per compute unit)"""
+        g, per = C.c_uint32(), C.c_uint32()
+        _check(_lib.mgwfbp_gated_workgroups(self._h, int(update), C.byref(g), C.byref(per)))
+        return g.value, per.value
 
     def capture_iteration(self, compute_stream, comm_stream, tb_ms=None, update: bool = False,
                           lr: float = 0.0, momentum: float = 0.0) -> "IterationGraph":

@@ -803,6 +803,20 @@ int mgwfbp_streams_side_by_side(mgwfbp_plan_t *pl, void *stream_a, void *stream_
     });
 }
 
+int mgwfbp_gated_workgroups(mgwfbp_plan_t *pl, int32_t update, uint32_t *workgroups, uint32_t *per_compute_unit)
+{
+    return guarded([&]() -> int {
+        int rc = check_bound(pl, false, false);
+        if (rc) return rc;
+        if (!workgroups && !per_compute_unit) return fail(MGWFBP_EINVAL, "both outputs are NULL");
+        const uint32_t g = gated_grid(*pl, update != 0);
+        const uint32_t cus = static_cast<uint32_t>(pl->n_cus > 0 ? pl->n_cus : 256);
+        if (workgroups) *workgroups = g;
+        if (per_compute_unit) *per_compute_unit = (g + cus - 1) / cus;
+        return MGWFBP_OK;
+    });
+}
+
 int mgwfbp_gated_signal(mgwfbp_plan_t *pl, int32_t group, uint32_t arrival, void *hip_stream)
 {
     return guarded([&]() -> int {

@@ -678,7 +678,8 @@ k_fused(DeviceTables dt, uint32_t tile_begin, int nw, float inv_n, float lr, flo
 //     the give-up word and ends, and every other workgroup ends at its next look at that word,
 //     so the launch always drains; the host then reports the failure.
 //   * The caller launches fewer workgroups than the chip holds at once, so the kernels that
-//     bump the counters (and the backward pass itself) find free slots.
+//     bump the counters find free slots (kernels that need whole SIMDs do not: every compute
+//     unit has some of this launch's workgroups).
 //   * The gradients were written while this kernel was already running, by a kernel that may
 //     have run on another compute die, and each die has its own L2.  The polls read the counter
 //     with device-scope loads that order nothing (an acquiring load drops the die's cached
@@ -695,7 +696,8 @@ __device__ __forceinline__ uint32_t peek_agent(const uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-constexpr int kGatedReserve = 2;  // workgroup slots per compute unit the gated launch leaves free
+constexpr int kGatedReserve = 2;         // workgroup slots per compute unit the gated launch leaves free at least
+constexpr int kGatedDefaultReserve = 4;  // and by default
 
 // *ctl: the give-up word, zero when the launch starts
 template <int U, bool STEP>
@@ -1221,6 +1223,22 @@ int launch_fused(const mgwfbp_plan_t &pl, const LaunchScope &sc, bool step, floa
     return check_launch("fused kernel launch");
 }
 
+// Workgroups of the gated launch: at most the chosen number per compute unit, and every workgroup
+// the same number of tiles (the last pass aside).  0 if the device holds too few.
+uint32_t gated_grid(const mgwfbp_plan_t &pl, bool step)
+{
+    const int holds = pl.gated_resident_per_cu[step ? 1 : 0][pl.gated_tile_elems == 4096 ? 1 : 0];
+    if (holds <= kGatedReserve || pl.ordered_tile_count == 0) return 0;
+    // by default four workgroup slots (eight waves, two per SIMD) of every compute unit stay free,
+    // which is what a producer with 256-lane workgroups needs to be placed at all; the option may
+    // go up to two free slots, enough for one-wave kernels like the stand-ins only
+    const int want = pl.opt.gated_wgs_per_cu > 0 ? pl.opt.gated_wgs_per_cu : std::max(1, holds - kGatedDefaultReserve);
+    const uint32_t cap = static_cast<uint32_t>(std::min(want, holds - kGatedReserve)) *
+                         static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
+    const uint32_t nt = pl.ordered_tile_count, passes = (nt + cap - 1) / cap;
+    return (nt + passes - 1) / passes;
+}
+
 int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, const uint32_t *ready,
                        uint32_t epoch, uint32_t *ctl, uint64_t max_polls, void *stream)
 {
@@ -1230,24 +1248,19 @@ int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, c
     k_signal<<<1, 64, 0, s>>>(ctl, 0u);
     if (int rc = check_launch("launch that clears the give-up word")) return rc;
     if (pl.ordered_tile_count == 0) return MGWFBP_OK;
-    // the launch takes kGatedReserve fewer workgroups per compute unit than the unit can hold of
-    // this kernel (16 by wave slots; the update form's registers allow 14) and so leaves room
-    // for the kernels that bump the counters: a chip filled with waiting workgroups would never
-    // see a counter move.  Every workgroup gets the same number of tiles (the last pass aside).
+    // the launch takes fewer workgroups per compute unit than the unit can hold of this kernel
+    // (16 by wave slots; the update form's registers allow 14) and so leaves room for the kernels
+    // that bump the counters: a chip filled with waiting workgroups would never see a counter move
     const int holds = pl.gated_resident_per_cu[step ? 1 : 0][lng ? 1 : 0];
     if (holds <= kGatedReserve) {
         set_error("the gated launch needs a device that holds more than " + std::to_string(kGatedReserve) +
                   " of its workgroups per compute unit");
         return MGWFBP_ESTATE;
     }
-    const int want = pl.opt.gated_wgs_per_cu > 0 ? pl.opt.gated_wgs_per_cu : holds;
-    const uint32_t cap = static_cast<uint32_t>(std::min(want, holds - kGatedReserve)) *
-                         static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
-    const uint32_t nt = pl.ordered_tile_count, passes = (nt + cap - 1) / cap;
-    const dim3 grid((nt + passes - 1) / passes);
+    const dim3 grid(gated_grid(pl, step));
     const float inv_n = 1.0f / static_cast<float>(pl.N);
     const int pace = pl.opt.pace >= 0 ? pl.opt.pace : 2;
-    const uint32_t tb = pl.ordered_tile_begin;
+    const uint32_t tb = pl.ordered_tile_begin, nt = pl.ordered_tile_count;
     if (lng) {
         if (step) k_fused_gated<8, true><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);
         else k_fused_gated<8, false><<<grid, kBlock, 0, s>>>(pl.dt, tb, nt, pl.N, inv_n, lr, mu, pace, ready, epoch, ctl, max_polls);

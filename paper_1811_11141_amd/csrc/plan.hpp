@@ -239,6 +239,8 @@ int launch_fused_gated(const mgwfbp_plan_t &pl, bool step, float lr, float mu, c
 // How many workgroups of the gated kernel (update form or not, 4096- or 1024-element tiles) one
 // compute unit of the current device holds.
 int gated_resident_per_cu(bool step, bool long_tiles, int *per_cu);
+// Workgroups the gated launch would use now (0: the device holds too few, or nothing to do).
+uint32_t gated_grid(const mgwfbp_plan_t &pl, bool step);
 // Sets *counter = epoch (device scope, release) behind the work already in the stream.
 int launch_signal(uint32_t *counter, uint32_t epoch, void *stream);
 // One wave polls *word until it equals `value` (then *result = 1) or max_polls polls of ~1 us have

@@ -14,6 +14,7 @@ int wall_clock_khz() { return 100000; }
 int prepare_static_workspace() { return MGWFBP_EHIP; }
 int launch_fused_gated(const mgwfbp_plan_t &, bool, float, float, const uint32_t *, uint32_t, uint32_t *, uint64_t, void *) { return MGWFBP_EHIP; }
 int launch_signal(uint32_t *, uint32_t, void *) { return MGWFBP_EHIP; }
+uint32_t gated_grid(const mgwfbp_plan_t &, bool) { return 0; }
 int gated_resident_per_cu(bool, bool, int *) { return MGWFBP_EHIP; }
 int launch_await(const uint32_t *, uint32_t, uint32_t *, uint64_t, void *) { return MGWFBP_EHIP; }
 }  // namespace mgwfbp

@@ -487,3 +487,38 @@ def test_gated_launch_reads_what_the_producer_wrote_while_it_was_waiting(mg, upd
                 assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), (arrival, l)
                 assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32)), (arrival, l)
         fresh = wl.make_gradients(w, 32 + arrival, "cuda")     # other values for the next pass
+
+
+@pytest.mark.parametrize("update", [False, True])
+def test_gated_launch_leaves_room_for_producers_with_full_size_workgroups(mg, update):
+    """The default grid of the gated launch leaves four workgroup slots per compute unit free: a
+    producer whose workgroups have 256 lanes (an elementwise torch kernel per group, on the
+    signalling stream) is placed and runs while the ResNet-50-sized launch waits, for the reduction
+    and for the update form (with two slots free the update form starved it and gave up)."""
+    w = wl.cnn_workload("resnet50")
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    grads = wl.make_gradients(w, 8, "cuda")
+    out = [torch.empty_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 8, "cuda")
+    pl.bind(grads, out, wt, vt)
+    total, per_cu = pl.gated_workgroups(update)
+    holds = 14 if update else 16
+    assert 0 < per_cu <= holds - 4 and total <= per_cu * 256
+    greedy = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    greedy.set_option(mg.OPT_GATED_WGS_PER_CU, 15)
+    greedy.bind(grads, out, wt, vt)
+    assert per_cu <= greedy.gated_workgroups(update)[1] <= holds - 2      # never fewer than two free
+    greedy.destroy()
+    s_sig, s_launch = streams_side_by_side(pl)
+    scratch = torch.zeros(4096, 4096, device="cuda")
+    with torch.cuda.stream(s_sig):
+        scratch.add_(1.0)                                     # first use on this stream, before any waiting
+    torch.cuda.synchronize()
+    pl.gated_launch(arrival=1, update=update, lr=0.1, momentum=0.9, give_up_ms=2000.0, stream=s_launch)
+    with torch.cuda.stream(s_sig):
+        for k in range(pl.info()["n_groups"]):
+            scratch.add_(1.0)
+            pl.gated_signal(k, 1, stream=s_sig)
+    torch.cuda.synchronize()
+    assert not pl.gated_gave_up()
+    assert float(scratch[0, 0]) == pl.info()["n_groups"] + 1
