@@ -92,10 +92,15 @@ enum {
                                    launch so that its batches of resident workgroups fill well;
                                    0: whatever the kernel's registers allow (14; 12 for N = 16);
                                    8, 9, 10, 11: that many.  Results do not depend on it            */
-    MGWFBP_OPT_GATED_WGS_PER_CU = 8 /* workgroups per compute unit in mgwfbp_gated_launch, which
+    MGWFBP_OPT_GATED_WGS_PER_CU = 8, /* workgroups per compute unit in mgwfbp_gated_launch, which
                                    stay for the whole launch: -1 (default) four fewer than a unit
                                    holds, or 1 .. 15 (never more than two fewer than it holds):
                                    the rest is room for the kernels that produce the gradients     */
+    MGWFBP_OPT_GATED_CUS = 9        /* compute units the stream of mgwfbp_gated_launch may use, when
+                                   the caller made it with a compute-unit mask
+                                   (hipExtStreamCreateWithCUMask) so that the other units stay
+                                   free for kernels that need whole SIMDs: the grid is sized for
+                                   that many units.  0 (default): all of the device              */
 };
 
 /*
@@ -414,6 +419,17 @@ int mgwfbp_run_iteration_streams(mgwfbp_plan_t *plan, const double *tb_ms, int32
  * workgroups on every compute unit, and a host call that synchronises the device blocks behind
  * it: the launch then gives up after give_up_ms.  One gated launch per plan at a time.
  *
+ * For a backward pass made of such kernels the launch can be confined to part of the chip:
+ *   mgwfbp_confined_stream_create   a stream (default priority) whose kernels run on the first
+ *                         n_compute_units of the current device only (a multiple of 32 below the
+ *                         device's count; the runtime's compute-unit mask).  Every such stream
+ *                         takes a hardware queue of its own: make one, not many.
+ *   mgwfbp_confined_stream_destroy  releases it (the caller has waited for its work).
+ * With MGWFBP_OPT_GATED_CUS set to the same number before mgwfbp_bind, mgwfbp_gated_launch on that
+ * stream sizes its grid for those units and leaves the others untouched: kernels that need whole
+ * SIMDs then run beside it, on the rest of the chip, and the launch streams at the rate its
+ * units reach (half of an MI355X: about 0.65 of the whole chip's).
+ *
  * The signalling kernels must be able to run WHILE the launch is running.  The runtime serves its
  * streams from a few hardware queues (four by default), and two streams that share a queue run
  * their kernels one after the other: the signals would then sit behind the launch that waits for
@@ -440,6 +456,8 @@ int mgwfbp_gated_launch(mgwfbp_plan_t *plan, int32_t update, float lr, float mom
 int mgwfbp_gated_signal(mgwfbp_plan_t *plan, int32_t group, uint32_t arrival, void *hip_stream);
 int mgwfbp_gated_gave_up(mgwfbp_plan_t *plan, int32_t *gave_up);
 int mgwfbp_gated_workgroups(mgwfbp_plan_t *plan, int32_t update, uint32_t *workgroups, uint32_t *per_compute_unit);
+int mgwfbp_confined_stream_create(uint32_t n_compute_units, void **hip_stream);
+int mgwfbp_confined_stream_destroy(void *hip_stream);
 int mgwfbp_streams_side_by_side(mgwfbp_plan_t *plan, void *stream_a, void *stream_b, int32_t *side_by_side);
 int mgwfbp_run_iteration_gated(mgwfbp_plan_t *plan, const double *tb_ms, int32_t update, float lr,
                                float momentum, void *compute_stream, void *comm_stream,

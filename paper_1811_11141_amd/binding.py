@@ -22,6 +22,7 @@ MODE_OPTIMAL, MODE_PAPER_GREEDY, MODE_WFBP, MODE_SINGLE = 0, 1, 2, 3
 OPT_TILE_ELEMS, OPT_SMALL_ELEMS, OPT_NONTEMPORAL, OPT_PACE, OPT_LONG_TILES, OPT_PAD_ELEMS = 1, 2, 3, 4, 5, 6
 OPT_UPDATE_WGS_PER_CU = 7
 OPT_GATED_WGS_PER_CU = 8
+OPT_GATED_CUS = 9
 STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 
 EXPORTS = [
@@ -31,7 +32,8 @@ EXPORTS = [
     "mgwfbp_pack_reduce", "mgwfbp_unpack_update", "mgwfbp_pack_reduce_unpack_static",
     "mgwfbp_run_iteration", "mgwfbp_run_iteration_streams", "mgwfbp_run_iteration_gated",
     "mgwfbp_gated_launch", "mgwfbp_gated_signal", "mgwfbp_gated_gave_up", "mgwfbp_gated_workgroups",
-    "mgwfbp_streams_side_by_side", "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
+    "mgwfbp_streams_side_by_side", "mgwfbp_confined_stream_create", "mgwfbp_confined_stream_destroy",
+    "mgwfbp_iteration_capture", "mgwfbp_iteration_replay",
     "mgwfbp_iteration_destroy", "mgwfbp_fit_cost", "mgwfbp_table2_cost", "mgwfbp_scaling_curve", "mgwfbp_plan_destroy",
     "mgwfbp_last_error",
 ]
@@ -89,6 +91,8 @@ def _load() -> C.CDLL:
     lib.mgwfbp_gated_signal.argtypes = [vp, i32, C.c_uint32, vp]
     lib.mgwfbp_gated_gave_up.argtypes = [vp, P(i32)]
     lib.mgwfbp_gated_workgroups.argtypes = [vp, i32, P(C.c_uint32), P(C.c_uint32)]
+    lib.mgwfbp_confined_stream_create.argtypes = [C.c_uint32, P(vp)]
+    lib.mgwfbp_confined_stream_destroy.argtypes = [vp]
     lib.mgwfbp_streams_side_by_side.argtypes = [vp, vp, vp, P(i32)]
     lib.mgwfbp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.mgwfbp_probe_read.argtypes = [vp, u64, vp, vp]
@@ -442,6 +446,26 @@ def mgwfbp_step(plan: Plan, lr: float, momentum: float, group: int = -1, workspa
 
 
 TABLE2 = {"binary_tree": 0, "recursive_doubling": 1, "recursive_halving_doubling": 2, "ring": 3}
+
+
+class ConfinedStream:
+    """A HIP stream whose kernels run on the first n_compute_units of the current device only
+    (mgwfbp_confined_stream_create), wrapped for torch as `.stream`."""
+
+    def __init__(self, n_compute_units: int):
+        import torch
+
+        h = C.c_void_p()
+        _check(_lib.mgwfbp_confined_stream_create(n_compute_units, C.byref(h)))
+        self._h = h
+        self.n_compute_units = n_compute_units
+        self.stream = torch.cuda.ExternalStream(h.value)
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            self.stream.synchronize()
+            _check(_lib.mgwfbp_confined_stream_destroy(self._h))
+            self._h = None
 
 
 def mgwfbp_fit_cost(nbytes, ms):

@@ -556,6 +556,10 @@ int mgwfbp_plan_set_option(mgwfbp_plan_t *pl, int32_t key, int64_t value)
                 return fail(MGWFBP_EINVAL, "gated_wgs_per_cu must be -1 or 1 .. 15");
             pl->opt.gated_wgs_per_cu = static_cast<int>(value);
             return MGWFBP_OK;
+        case MGWFBP_OPT_GATED_CUS:
+            if (value < 0 || value > 65536) return fail(MGWFBP_EINVAL, "gated_cus must be 0 (all) or a number of compute units");
+            pl->opt.gated_cus = static_cast<int>(value);
+            return MGWFBP_OK;
         default: return fail(MGWFBP_EINVAL, "unknown option key");
         }
     });
@@ -803,6 +807,39 @@ int mgwfbp_streams_side_by_side(mgwfbp_plan_t *pl, void *stream_a, void *stream_
     });
 }
 
+int mgwfbp_confined_stream_create(uint32_t n_compute_units, void **hip_stream)
+{
+    return guarded([&]() -> int {
+        if (!hip_stream) return fail(MGWFBP_EINVAL, "hip_stream is NULL");
+        *hip_stream = nullptr;
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("device query: ") + hipGetErrorString(e));
+        if (n_compute_units == 0 || n_compute_units % 32 != 0 || static_cast<int>(n_compute_units) >= cus)
+            return fail(MGWFBP_EINVAL, "n_compute_units must be a multiple of 32 below the device's " +
+                                           std::to_string(cus) + " compute units");
+        // one bit per compute unit, whole 32-bit words: the first n_compute_units of the device
+        std::vector<uint32_t> mask(static_cast<size_t>((cus + 31) / 32), 0u);
+        for (uint32_t i = 0; i < n_compute_units / 32; ++i) mask[i] = 0xffffffffu;
+        hipStream_t s = nullptr;
+        e = hipExtStreamCreateWithCUMask(&s, static_cast<uint32_t>(mask.size()), mask.data());
+        if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipExtStreamCreateWithCUMask: ") + hipGetErrorString(e));
+        *hip_stream = s;
+        return MGWFBP_OK;
+    });
+}
+
+int mgwfbp_confined_stream_destroy(void *hip_stream)
+{
+    return guarded([&]() -> int {
+        if (!hip_stream) return MGWFBP_OK;
+        const hipError_t e = hipStreamDestroy(static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return fail(MGWFBP_EHIP, std::string("hipStreamDestroy: ") + hipGetErrorString(e));
+        return MGWFBP_OK;
+    });
+}
+
 int mgwfbp_gated_workgroups(mgwfbp_plan_t *pl, int32_t update, uint32_t *workgroups, uint32_t *per_compute_unit)
 {
     return guarded([&]() -> int {
@@ -810,7 +847,8 @@ int mgwfbp_gated_workgroups(mgwfbp_plan_t *pl, int32_t update, uint32_t *workgro
         if (rc) return rc;
         if (!workgroups && !per_compute_unit) return fail(MGWFBP_EINVAL, "both outputs are NULL");
         const uint32_t g = gated_grid(*pl, update != 0);
-        const uint32_t cus = static_cast<uint32_t>(pl->n_cus > 0 ? pl->n_cus : 256);
+        uint32_t cus = static_cast<uint32_t>(pl->n_cus > 0 ? pl->n_cus : 256);
+        if (pl->opt.gated_cus > 0) cus = std::min(cus, static_cast<uint32_t>(pl->opt.gated_cus));
         if (workgroups) *workgroups = g;
         if (per_compute_unit) *per_compute_unit = (g + cus - 1) / cus;
         return MGWFBP_OK;

@@ -1233,8 +1233,9 @@ uint32_t gated_grid(const mgwfbp_plan_t &pl, bool step)
     // which is what a producer with 256-lane workgroups needs to be placed at all; the option may
     // go up to two free slots, enough for one-wave kernels like the stand-ins only
     const int want = pl.opt.gated_wgs_per_cu > 0 ? pl.opt.gated_wgs_per_cu : std::max(1, holds - kGatedDefaultReserve);
-    const uint32_t cap = static_cast<uint32_t>(std::min(want, holds - kGatedReserve)) *
-                         static_cast<uint32_t>(pl.n_cus > 0 ? pl.n_cus : 256);
+    int cus = pl.n_cus > 0 ? pl.n_cus : 256;
+    if (pl.opt.gated_cus > 0) cus = std::min(cus, pl.opt.gated_cus);  // the caller's stream is confined to these
+    const uint32_t cap = static_cast<uint32_t>(std::min(want, holds - kGatedReserve)) * static_cast<uint32_t>(cus);
     const uint32_t nt = pl.ordered_tile_count, passes = (nt + cap - 1) / cap;
     return (nt + passes - 1) / passes;
 }

@@ -70,6 +70,7 @@ struct Options {
                           // 1 = 8192, or 5120 / 6144 / 7168 / 8192 elements
     int update_wgs_per_cu = -1;  // update kernel: -1 by rule, 0 uncapped, 8..11 forced
     int gated_wgs_per_cu = -1;   // gated launch: -1 = all but the reserve, or 1..15
+    int gated_cus = 0;           // gated launch: compute units its stream may use (0 = all of the device)
 };
 
 struct GroupInfo {

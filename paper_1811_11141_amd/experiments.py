@@ -2,6 +2,7 @@
 
     python -m paper_1811_11141_amd.experiments --workload resnet50
     python -m paper_1811_11141_amd.experiments --workload resnet50 --scaling     (host only)
+    python -m paper_1811_11141_amd.experiments --workload resnet50 --producers   (kernels beside a waiting gated launch)
 
 1. Calibration (what Section V-A does for the network): time every group of a plan alone,
    as a function of its message size M = 4 * (parameters in the group), and fit
@@ -160,6 +161,84 @@ def calibrate_arrival(n_workers: int = 8, device: str = "cuda:0", reps: int = 7,
     return out
 
 
+def producers_beside_gated_launch(workload: str = "resnet50", device: str = "cuda:0", give_up_ms: float = 1000.0):
+    """What a waiting gated launch does to the kernels that produce the gradients.  One producer
+    kernel per group on the signalling stream, each followed by the group's signal: an elementwise
+    kernel (256-lane workgroups, few registers), an fp32 GEMM (160 registers, 65 KiB LDS) and an
+    fp16 matrix-core GEMM (the whole register file of a SIMD), 4096^3 each.  Shapes of the launch:
+    the default grid, 8 and 4 workgroups per compute unit on the whole chip, and the default grid on
+    a stream confined to half the compute units.  Reports the producers' time alone and beside the
+    waiting launch, and whether the launch gave up (the producers were not placed in time)."""
+    import time
+
+    import torch
+
+    from . import binding as mg
+    from . import workloads as wl
+
+    w = wl.cnn_workload(workload)
+    grads = wl.make_gradients(w, 5, device)
+    out = [torch.empty_like(t) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 5, device)
+    a32 = torch.randn(4096, 4096, device=device)
+    b32 = torch.randn(4096, 4096, device=device)
+    a16, b16 = a32.half(), b32.half()
+    producers = {"elementwise": lambda: a32.add_(1.0), "gemm_fp32": lambda: torch.mm(a32, b32),
+                 "gemm_fp16_matrix_cores": lambda: torch.mm(a16, b16)}
+    n_cus = torch.cuda.get_device_properties(device).multi_processor_count
+    half = n_cus // 2 // 32 * 32
+    confined = mg.ConfinedStream(half)
+    out_rows = {"workload": workload, "compute_units": n_cus, "shapes": {}}
+    try:
+        for shape, per_cu, cus in (("default", -1, 0), ("8_per_unit", 8, 0), ("4_per_unit", 4, 0),
+                                   (f"default_on_{half}_units", -1, half)):
+            for update in (False, True):
+                pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+                pl.set_option(mg.OPT_GATED_WGS_PER_CU, per_cu)
+                pl.set_option(mg.OPT_GATED_CUS, cus)
+                pl.bind(grads, out, wt, vt)
+                if cus:
+                    s_launch = confined.stream
+                    for _ in range(8):
+                        s_sig = torch.cuda.Stream(device=device)
+                        if pl.streams_side_by_side(s_sig, s_launch):
+                            break
+                    else:
+                        raise RuntimeError("no stream ran beside the confined one")
+                else:
+                    s_sig, s_launch = _stream_pair(pl, device)
+                ng = pl.info()["n_groups"]
+                row = {"workgroups": pl.gated_workgroups(update)[0], "per_unit": pl.gated_workgroups(update)[1]}
+                arrival = 0
+                for name, fn in producers.items():
+                    with torch.cuda.stream(s_sig):
+                        fn(); fn()                            # first calls on a stream allocate workspaces
+                        torch.cuda.synchronize()
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(s_sig)
+                        for _ in range(ng):
+                            fn()
+                        e1.record(s_sig)
+                    torch.cuda.synchronize()
+                    alone = e0.elapsed_time(e1)
+                    arrival += 1
+                    t0 = time.perf_counter()
+                    pl.gated_launch(arrival, update=update, lr=0.1, momentum=0.9, give_up_ms=give_up_ms, stream=s_launch)
+                    with torch.cuda.stream(s_sig):
+                        for k in range(ng):
+                            fn()
+                            pl.gated_signal(k, arrival, stream=s_sig)
+                    torch.cuda.synchronize()
+                    row[name] = {"alone_ms": alone, "beside_the_waiting_launch_ms": (time.perf_counter() - t0) * 1e3,
+                                 "gave_up": pl.gated_gave_up()}
+                out_rows["shapes"][shape + ("_update" if update else "")] = row
+                pl.destroy()
+    finally:
+        torch.cuda.synchronize()
+        confined.destroy()
+    return out_rows
+
+
 def schedule(workload: str, a_ms: float, b_ms_per_byte: float, backward_ms: float = 5.0,
              device: str = "cuda:0", reps: int = 5):
     """Predicted (Eq. 8 with the given a, b) and measured iteration times of four plans.
@@ -234,9 +313,13 @@ def main():
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "googlenet", "alexnet", "vgg16"])
     ap.add_argument("--backward-ms", type=float, nargs="+", default=[5.0, 1.0])
     ap.add_argument("--scaling", action="store_true", help="only the host-side scaling table (no GPU)")
+    ap.add_argument("--producers", action="store_true", help="only: producer kernels beside a waiting gated launch")
     args = ap.parse_args()
     if args.scaling:
         print(json.dumps(scaling(args.workload)))
+        return
+    if args.producers:
+        print(json.dumps(producers_beside_gated_launch(args.workload)))
         return
     cal = calibrate(args.workload)
     cal2 = calibrate_in_schedule(args.workload)

@@ -522,3 +522,65 @@ def test_gated_launch_leaves_room_for_producers_with_full_size_workgroups(mg, up
     torch.cuda.synchronize()
     assert not pl.gated_gave_up()
     assert float(scratch[0, 0]) == pl.info()["n_groups"] + 1
+
+
+def test_gated_launch_confined_to_half_the_chip_lets_matrix_core_producers_run(mg):
+    """mgwfbp_confined_stream_create + MGWFBP_OPT_GATED_CUS: the gated launch (update form) sits on
+    the first 128 compute units only, so producers that need whole SIMDs -- an fp16 matrix-core
+    GEMM per group on the signalling stream -- run on the rest of the chip while it waits (on the
+    whole chip they are never placed and the launch gives up).  Results against the oracle; the
+    fused pass on the confined stream, too."""
+    w = wl.cnn_workload("googlenet")
+    pl = mg.mgwfbp_plan(w.p, w.tb_ms, 0.0, w.a_ms, w.b_ms_per_byte, w.n_workers, mg.MODE_OPTIMAL)
+    pl.set_option(mg.OPT_GATED_CUS, 128)
+    grads = wl.make_gradients(w, 12, "cuda")
+    out = [torch.full_like(t, float("nan")) for t in grads[0]]
+    wt, vt = wl.make_weights(w, 12, "cuda")
+    for t in vt:
+        t.normal_(0, 1e-3)
+    w_np, v_np = to_np(wt), to_np(vt)
+    pl.bind(grads, out, wt, vt)
+    with pytest.raises(mg.MgwfbpError):
+        mg.ConfinedStream(100)                                # whole 32-unit words only
+    with pytest.raises(mg.MgwfbpError):
+        mg.ConfinedStream(4096)                               # more than the device has
+    cs = mg.ConfinedStream(128)
+    try:
+        total, per_cu = pl.gated_workgroups(True)
+        assert 0 < total <= per_cu * 128
+        for _ in range(8):
+            s_sig = torch.cuda.Stream()
+            if pl.streams_side_by_side(s_sig, cs.stream):
+                break
+        else:
+            pytest.fail("no stream ran beside the confined one")
+        a = torch.randn(2048, 2048, device="cuda").half()
+        b = torch.randn(2048, 2048, device="cuda").half()
+        with torch.cuda.stream(s_sig):
+            ref = torch.mm(a, b)                              # first call on this stream, before any waiting
+        torch.cuda.synchronize()
+        groups = pl.groups()
+        pl.gated_launch(arrival=1, update=True, lr=0.1, momentum=0.9, give_up_ms=2000.0, stream=cs.stream)
+        with torch.cuda.stream(s_sig):
+            for k in range(len(groups)):
+                c = torch.mm(a, b)
+                pl.gated_signal(k, 1, stream=s_sig)
+        torch.cuda.synchronize()
+        assert not pl.gated_gave_up()
+        assert torch.equal(c, ref)
+        g_np = [to_np(r) for r in grads]
+        exp = od.merged_gradient_path(g_np, groups)
+        od.merged_gradient_path(g_np, groups, w_np, v_np, 0.1, 0.9)
+        for l in range(w.L):
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), l
+            assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), l
+            assert np.array_equal(vt[l].cpu().numpy().view(np.uint32), v_np[l].view(np.uint32)), l
+        for t in out:
+            t.fill_(float("nan"))
+        pl.pack_reduce_unpack(stream=cs.stream)               # any launch may go to the confined stream
+        torch.cuda.synchronize()
+        for l in range(w.L):
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), l
+    finally:
+        torch.cuda.synchronize()
+        cs.destroy()
