@@ -66,6 +66,11 @@ int main(void)
                 if (mgwfbp_streams_side_by_side(pl, &dummy_a, &dummy_b, &flag) != MGWFBP_ESTATE) bad++;
                 if (mgwfbp_run_iteration_gated(pl, NULL, 0, 0.0f, 0.0f, &dummy_a, &dummy_b, 10.0, &t_it) != MGWFBP_ESTATE) bad++;
                 if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_WGS_PER_CU, 16) != MGWFBP_EINVAL) bad++;
+                if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_CUS, -1) != MGWFBP_EINVAL) bad++;
+                if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_CUS, (int)(rnd() % 9) * 32) != MGWFBP_OK) bad++;
+                if (mgwfbp_gated_workgroups(pl, 0, NULL, NULL) != MGWFBP_ESTATE) bad++;
+                if (mgwfbp_confined_stream_create(128, NULL) != MGWFBP_EINVAL) bad++;
+                if (mgwfbp_confined_stream_destroy(NULL) != MGWFBP_OK) bad++;
                 if (mgwfbp_plan_set_option(pl, MGWFBP_OPT_GATED_WGS_PER_CU, (int)(rnd() % 15) + 1) != MGWFBP_OK) bad++;
             }
             free(gol); free(off); free(ge); free(mu); free(gs); free(gf); free(segs); free(tl);
