@@ -417,21 +417,31 @@ def test_gated_launch_random_shapes(mg, seed):
     g_np, w_np, v_np = [to_np(r) for r in grads], to_np(wt), to_np(vt)
     for t in out:
         t.fill_(float("nan"))
-    pl.bind(grads, out, wt, vt)
+    without_out = seed % 4 == 3                               # the update alone: out[] not bound
+    pl.bind(grads, None if without_out else out, wt, vt)
     exp = od.merged_gradient_path(g_np, groups)
     s_sig, s_launch = streams_side_by_side(pl)
     torch.cuda.synchronize()
-    pl.gated_launch(arrival=1, give_up_ms=5000.0, stream=s_launch)
-    with torch.cuda.stream(s_sig):
-        for k in rng.permutation(len(groups)):
-            pl.gated_signal(int(k), 1, stream=s_sig)
-    torch.cuda.synchronize()
-    assert not pl.gated_gave_up()
-    for l in range(L):
-        assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), (seed, l)
+    if without_out:
+        with pytest.raises(mg.MgwfbpError):
+            pl.gated_launch(arrival=1, stream=s_launch)       # the reduction needs somewhere to write
+        with torch.cuda.stream(s_sig):
+            for k in rng.permutation(len(groups)):
+                pl.gated_signal(int(k), 1, stream=s_sig)
+    else:
+        pl.gated_launch(arrival=1, give_up_ms=5000.0, stream=s_launch)
+        with torch.cuda.stream(s_sig):
+            for k in rng.permutation(len(groups)):
+                pl.gated_signal(int(k), 1, stream=s_sig)
+        torch.cuda.synchronize()
+        assert not pl.gated_gave_up()
+        for l in range(L):
+            assert np.array_equal(out[l].cpu().numpy().view(np.uint32), exp[l].view(np.uint32)), (seed, l)
     pl.gated_launch(arrival=1, update=True, lr=0.3, momentum=0.7, give_up_ms=5000.0, stream=s_launch)
     torch.cuda.synchronize()
     assert not pl.gated_gave_up()
+    if without_out:
+        assert all(bool(torch.isnan(t).all()) for t in out)
     od.merged_gradient_path(g_np, groups, w_np, v_np, 0.3, 0.7)
     for l in range(L):
         assert np.array_equal(wt[l].cpu().numpy().view(np.uint32), w_np[l].view(np.uint32)), (seed, l)
