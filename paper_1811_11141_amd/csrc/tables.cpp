@@ -148,7 +148,7 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     // Tile length of the arrival-ordered list (the gated launch), whatever tile_elems says: its
     // workgroups stay and walk several tiles each, so the length only sets how finely the work is
     // dealt and how long a tile that is alone on the chip takes (a full tile is a chain of N * U
-    // loads, each waited for).  A plan that the launch covers in about two rounds of 4096-element
+    // loads, each waited for).  A plan that the launch covers in about two passes of 4096-element
     // tiles is cut into 1024-element tiles (GoogLeNet's sizes against 4096: 99 -> 81 us with every
     // group arrived, ResNet-50's update 237 -> 225 us, its reduction 145 -> 148 us; a 4 MB message
     // that arrives alone is done after 13 us instead of 22 us with 2048); a long plan keeps 4096
@@ -159,8 +159,8 @@ void build_tables(mgwfbp_plan_t &pl, const float *const *grads, float *const *ou
     {
         uint64_t total = 0;
         for (const GroupInfo &g : pl.groups) total += g.elems;
-        const uint64_t two_rounds = 2ull * 14ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
-        pl.gated_tile_elems = (total + 4095) / 4096 <= two_rounds ? 1024u : 4096u;
+        const uint64_t two_passes = 2ull * 14ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);
+        pl.gated_tile_elems = (total + 4095) / 4096 <= two_passes ? 1024u : 4096u;
     }
     const uint64_t short_launch = 8ull * static_cast<uint64_t>(pl.n_cus > 0 ? pl.n_cus : 256);  // workgroups
     for (size_t k = 0; k < pl.groups.size(); ++k) {
